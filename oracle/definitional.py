@@ -1,0 +1,172 @@
+"""Definitional oracle: every quantity evaluated exactly as the paper prints it.
+
+Pure Python, fp64 (``float``), explicit loops and ``math.fsum``.  Slow on
+purpose; meant for inputs of a few hundred tokens.  Test infrastructure only.
+
+Indexing (Sec. 2.1): the state ``s_t`` holds the prompt and the response tokens
+before position ``t``; the action ``a_t`` is response token ``t``.  So the
+hidden state that predicts window token ``t`` of a sequence is the one at the
+packed position just before that token, and ``values[t]`` is ``V(s_t)``.
+
+Batch layout: ``B`` sequences packed back to back.  Sequence ``i`` occupies
+packed positions ``cu_seqlens[i] .. cu_seqlens[i+1]-1``: first ``ctx_len[i]``
+context tokens (prompt plus tokens generated in earlier steps), then
+``win_len[i]`` tokens generated in the current step.  ``done[i]`` is 1 when the
+sequence emitted its end-of-sequence token inside the window and 0 when it was
+cut at the window length (Sec. 3.2).
+"""
+import math
+
+
+# --------------------------------------------------------------------------
+# Token filter (Sec. 3.2; abstract: prompt and truncated tokens are filtered)
+# --------------------------------------------------------------------------
+def select(cu_seqlens, ctx_len, done, input_ids, tail_drop):
+    """Token filter of Sec. 3.2.
+
+    Policy tokens: every token generated in the current step, finished or not,
+    except the ``tail_drop`` latest tokens of an unfinished sequence.  Value
+    tokens: all window tokens of finished sequences.  Prompt/context tokens
+    belong to neither set.
+    """
+    B = len(ctx_len)
+    resp_off = [0]
+    sel_off = [0]
+    keep_len = []
+    sel_rows, sel_targets, sel_resp_idx = [], [], []
+    n_val = 0
+    for i in range(B):
+        seq_start = int(cu_seqlens[i])
+        win_len = int(cu_seqlens[i + 1]) - seq_start - int(ctx_len[i])
+        first_window_pos = seq_start + int(ctx_len[i])
+        if int(done[i]) != 0:
+            keep = win_len
+            n_val += win_len
+        else:
+            keep = max(win_len - int(tail_drop), 0)
+        for t in range(win_len):
+            if t < keep:
+                pos = first_window_pos + t          # packed position of a_t
+                sel_rows.append(pos - 1)            # hidden state of s_t
+                sel_targets.append(int(input_ids[pos]))
+                sel_resp_idx.append(resp_off[i] + t)
+        keep_len.append(keep)
+        resp_off.append(resp_off[i] + win_len)
+        sel_off.append(sel_off[i] + keep)
+    return dict(resp_off=resp_off, sel_off=sel_off, keep_len=keep_len,
+                sel_rows=sel_rows, sel_targets=sel_targets,
+                sel_resp_idx=sel_resp_idx,
+                M=sel_off[B], N_resp=resp_off[B], N_val=n_val)
+
+
+# --------------------------------------------------------------------------
+# log pi_theta(a_t | s_t): the quantity inside the ratio of Eq. (ppoloss)
+# --------------------------------------------------------------------------
+def token_logprobs(hidden, w_head, sel_rows, sel_targets):
+    """``log softmax(W h)[target]`` for each kept token, by brute force.
+
+    ``hidden`` is a list of rows (lists of floats), ``w_head`` a list of V rows
+    of H floats (``Linear.weight`` layout, no bias, temperature 1).
+    Returns ``(logp, lse)``.
+    """
+    logp, lse = [], []
+    for row, tgt in zip(sel_rows, sel_targets):
+        h = hidden[row]
+        z = [math.fsum(hk * wk for hk, wk in zip(h, w_v)) for w_v in w_head]
+        zmax = max(z)
+        log_sum = zmax + math.log(math.fsum(math.exp(zv - zmax) for zv in z))
+        lse.append(log_sum)
+        logp.append(z[tgt] - log_sum)
+    return logp, lse
+
+
+# --------------------------------------------------------------------------
+# Extended GAE, Eq. (egae) with Eq. (TD), and the return R_t of Sec. 2.4
+# --------------------------------------------------------------------------
+def td_residuals(rewards, values, done, gamma, bootstrap=None):
+    """delta_t = r_t + gamma V(s_{t+1}) - V(s_t), Eq. (TD), for one sequence.
+
+    The state after the last window token has no value estimate.  For a
+    finished response it is terminal, V = 0.  For a truncated one Sec. 3.1
+    assumes V(s_l) = V(s_{l-1}); a caller-supplied ``bootstrap`` replaces that
+    assumption.
+    """
+    l = len(rewards)
+    delta = []
+    for t in range(l):
+        if t + 1 < l:
+            v_next = values[t + 1]
+        elif done:
+            v_next = 0.0
+        elif bootstrap is not None:
+            v_next = bootstrap
+        else:
+            v_next = values[l - 1]
+        delta.append(rewards[t] + gamma * v_next - values[t])
+    return delta
+
+
+def egae_sequence(rewards, values, done, gamma, lam, bootstrap=None):
+    """A_t = sum_{k=t}^{l-1} (gamma lam)^{k-t} delta_k  (Eq. (egae)), and
+    R_t = sum_i gamma^i r_{t+i} (Sec. 2.4), for one sequence, as double sums."""
+    l = len(rewards)
+    delta = td_residuals(rewards, values, done, gamma, bootstrap)
+    c = gamma * lam
+    adv = [math.fsum((c ** (k - t)) * delta[k] for k in range(t, l))
+           for t in range(l)]
+    ret = [math.fsum((gamma ** i) * rewards[t + i] for i in range(l - t))
+           for t in range(l)]
+    return adv, ret
+
+
+def egae(rewards, values, resp_off, done, gamma, lam, bootstrap=None):
+    """Eq. (egae) over a response-packed batch: element ``resp_off[i]+t`` of
+    each array is window token ``t`` of sequence ``i``."""
+    adv, ret = [], []
+    for i in range(len(done)):
+        lo, hi = int(resp_off[i]), int(resp_off[i + 1])
+        b = None if bootstrap is None else float(bootstrap[i])
+        a, r = egae_sequence([float(x) for x in rewards[lo:hi]],
+                             [float(x) for x in values[lo:hi]],
+                             int(done[i]) != 0, gamma, lam, b)
+        adv += a
+        ret += r
+    return adv, ret
+
+
+# --------------------------------------------------------------------------
+# Clipped surrogate, Eq. (ppoloss); clipped value loss, Eqs. (valueclip/loss)
+# --------------------------------------------------------------------------
+def _clip(x, lo, hi):
+    return min(max(x, lo), hi)
+
+
+def ppo_losses(logp_new, logp_old, adv, v_new, v_old, ret,
+               resp_off, keep_len, done,
+               eps_low, eps_high, xi_low, xi_high):
+    """Token-level means (Sec. 4.1.1) over the policy set and the value set.
+
+    policy_loss = -J_PPO (the paper maximises J_PPO), value_loss = +J_value.
+    Empty sets give 0.  Tokens outside a set are never touched.
+    """
+    pol_terms, val_terms = [], []
+    for i in range(len(done)):
+        lo, hi = int(resp_off[i]), int(resp_off[i + 1])
+        for t in range(hi - lo):
+            j = lo + t
+            if t < int(keep_len[i]):
+                ratio = math.exp(float(logp_new[j]) - float(logp_old[j]))
+                a = float(adv[j])
+                pol_terms.append(min(ratio * a,
+                                     _clip(ratio, 1.0 - eps_low, 1.0 + eps_high) * a))
+            if int(done[i]) != 0:
+                v, vo, r = float(v_new[j]), float(v_old[j]), float(ret[j])
+                v_clip = _clip(v, vo - xi_low, vo + xi_high)
+                val_terms.append(max((v - r) ** 2, (v_clip - r) ** 2))
+    policy_sum = -math.fsum(pol_terms)
+    value_sum = 0.5 * math.fsum(val_terms)
+    n_pol, n_val = len(pol_terms), len(val_terms)
+    return dict(policy_loss=policy_sum / n_pol if n_pol else 0.0,
+                value_loss=value_sum / n_val if n_val else 0.0,
+                policy_sum=policy_sum, value_sum=value_sum,
+                n_policy=n_pol, n_value=n_val)
