@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the T-PPO per-token core on one MI355X.
+
+One "step" = one pass of the whole hot path over one synthetic batch resident
+in HBM: tppo_select -> tppo_token_logprobs -> tppo_egae -> tppo_ppo_losses.
+Metric: selected (kept) tokens per second.  Default workload: the 32B-shaped
+head (32 sequences, prompt 1024 + window 8192, hidden 5120, vocabulary 152064,
+bf16, token ids sampled from the policy).
+
+Prints ONE JSON line with the whole-path throughput, the roofline position of
+the dominant kernel (the fused LM-head MFMA kernel, timed with HIP events on
+the launch stream inside the timed region) and the CPU oracle timed on a
+bounded sample of the same batch on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="head32b",
+                    choices=["small", "head7b", "head32b", "longcot", "longcot5x"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=3072)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2506_15050_amd import binding as tp, synth
+
+    torch.cuda.set_device(0)
+    tp.load()
+    name = args.workload
+    has_head = synth.CONFIGS[name]["V"] > 0
+    t0 = time.time()
+    b = synth.make_batch(name)
+
+    def dev(a):
+        t = torch.from_numpy(np.ascontiguousarray(a))
+        if a.dtype == np.uint16:
+            t = t.view(torch.int16).view(torch.bfloat16)
+        return t.cuda()
+
+    if has_head and b["cfg"].get("ids_from_policy"):
+        synth.sample_ids_from_policy(b, device="cuda")
+    d = {k: dev(b[k]) for k in ("cu_seqlens", "ctx_len", "done", "rewards", "values", "v_new")}
+    ids = dev(b["input_ids"]) if has_head else None
+    hidden = dev(b["hidden"]) if has_head else None
+    w_head = dev(b["w_head"]) if has_head else None
+    n_resp, n_tok = b["n_resp"], b["n_tok"]
+    print(f"[bench] inputs for '{name}' ready in {time.time() - t0:.1f}s "
+          f"(n_tok={n_tok}, n_resp={n_resp})", file=sys.stderr, flush=True)
+
+    # --- set-up pass: the caller learns M once (it is fixed by the batch), and
+    # the old policy's log-probs are the new ones plus the seeded gap
+    sel = tp.tppo_select(d["cu_seqlens"], d["ctx_len"], d["done"], ids, b["tail_drop"], n_tok=n_tok)
+    M = int(sel["counts"][0].item())
+    if has_head:
+        logp0, _ = tp.tppo_token_logprobs(hidden, w_head, sel["sel_rows"], sel["sel_targets"], M=M,
+                                          out_index=sel["sel_resp_idx"], out_size=n_resp, want_lse=False)
+        logp0 = torch.where(torch.isfinite(logp0), logp0, torch.zeros_like(logp0))
+    else:
+        logp0 = dev(b["logp_new_synth"])
+    logp_old = logp0 + dev(b["logp_gap"])
+    status = tp.new_status("cuda")
+    lib = tp.load()
+    H, V = b["H"], b["V"]
+    ws_head = tp._workspace(lib.tppo_token_logprobs_workspace_bytes(M, H, V, tp.TPPO_BF16), "cuda") if has_head else None
+    ws_egae = tp._workspace(lib.tppo_egae_workspace_bytes(n_resp, b["B"]), "cuda")
+    ws_loss = tp._workspace(lib.tppo_ppo_losses_workspace_bytes(n_resp, b["B"]), "cuda")
+    adv_ret = (torch.empty(n_resp, device="cuda"), torch.empty(n_resp, device="cuda"))
+    loss_out = torch.empty(32, dtype=torch.uint8, device="cuda")
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    stage_names = ("select", "logprobs", "egae", "losses")
+    marks = []
+
+    def step(record):
+        e = [ev() for _ in range(5)] if record else None
+        if record:
+            e[0].record()
+        s = tp.tppo_select(d["cu_seqlens"], d["ctx_len"], d["done"], ids, b["tail_drop"], n_tok=n_tok,
+                           status=status)
+        if record:
+            e[1].record()
+        if has_head:
+            logp, _ = tp.tppo_token_logprobs(hidden, w_head, s["sel_rows"], s["sel_targets"], M=M,
+                                             out_index=s["sel_resp_idx"], out_size=n_resp,
+                                             want_lse=False, status=status, workspace=ws_head)
+        else:
+            logp = logp0
+        if record:
+            e[2].record()
+        adv, ret = tp.tppo_egae(d["rewards"], d["values"], s["resp_off"], d["done"], b["gamma"], b["lam"],
+                                status=status, workspace=ws_egae, out=adv_ret)
+        if record:
+            e[3].record()
+        tp.tppo_ppo_losses(logp, logp_old, adv, d["v_new"], d["values"], ret, s["resp_off"],
+                           s["keep_len"], d["done"], b["eps_low"], b["eps_high"], b["xi_low"],
+                           b["xi_high"], status=status, workspace=ws_loss, out=loss_out)
+        if record:
+            e[4].record()
+            marks.append(e)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    assert int(status.item()) == 0, f"device status {int(status.item())}"
+    losses = tp.read_loss_out(loss_out)
+
+    stage_ms = {n: float(np.mean([m[i].elapsed_time(m[i + 1]) for m in marks]))
+                for i, n in enumerate(stage_names)}
+    ms_per_step = elapsed / args.steps * 1e3
+    value = M * args.steps / elapsed
+
+    if has_head:
+        flops = 2.0 * M * V * H
+        achieved = flops / (stage_ms["logprobs"] * 1e-3) / 1e12
+        roofline = dict(bound="mfma", kernel="head_mfma_kernel", achieved=achieved,
+                        peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=achieved / MFMA_BF16_PEAK_TFLOPS, traffic=None,
+                        flops_per_launch=flops, avg_ms=stage_ms["logprobs"])
+    else:
+        nbytes = 16.0 * n_resp
+        achieved = nbytes / (stage_ms["egae"] * 1e-3) / 1e9
+        roofline = dict(bound="hbm", kernel="egae_scan_kernel", achieved=achieved, peak=HBM_PEAK_GBS,
+                        unit="GB/s", frac=achieved / HBM_PEAK_GBS, traffic=None,
+                        bytes_per_launch=nbytes, avg_ms=stage_ms["egae"])
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(b, M, args.cpu_sample_rows, has_head)
+
+    out = {
+        "metric": "selected tokens/sec (logprob+EGAE+loss) at 1 MI355X",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if has_head else "f32", "data": "synthetic",
+        "config": {"workload": name, "sequences": b["B"], "n_tok": n_tok, "n_resp": n_resp,
+                   "kept_tokens_M": M, "hidden": H, "vocab": V, "tail_drop": b["tail_drop"],
+                   "gamma": b["gamma"], "lambda": b["lam"]},
+        "stages_ms": stage_ms,
+        "losses": {k: losses[k] for k in ("policy_loss", "value_loss", "n_policy", "n_value")},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(b, M, sample_rows, has_head):
+    """The CPU oracle, as it stands, on a bounded sample of the same batch:
+    the LM head on `sample_rows` seeded kept rows, the other stages on the full
+    batch; per-token costs are added."""
+    from oracle import fast as ofast
+    t = time.perf_counter()
+    ids = b["input_ids"] if has_head else np.zeros(b["n_tok"], np.int32)
+    sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], ids, b["tail_drop"])
+    t_sel = time.perf_counter() - t
+    t_head, n_head = 0.0, 0
+    if has_head:
+        pick = np.sort(np.random.default_rng(0).choice(M, size=min(sample_rows, M), replace=False))
+        t = time.perf_counter()
+        olp, _ = ofast.token_logprobs(b["hidden"], b["w_head"], sel["sel_rows"][pick], sel["sel_targets"][pick])
+        t_head, n_head = time.perf_counter() - t, len(pick)
+        logp_new = np.zeros(b["n_resp"], np.float32)
+    else:
+        logp_new = b["logp_new_synth"]
+    t = time.perf_counter()
+    adv, ret = ofast.egae(b["rewards"], b["values"], sel["resp_off"], b["done"], b["gamma"], b["lam"])
+    t_egae = time.perf_counter() - t
+    t = time.perf_counter()
+    ofast.ppo_losses(logp_new, logp_new + b["logp_gap"], adv, b["v_new"], b["values"], ret,
+                     sel["resp_off"], sel["keep_len"], b["done"], b["eps_low"], b["eps_high"],
+                     b["xi_low"], b["xi_high"])
+    t_loss = time.perf_counter() - t
+    per_token = (t_sel + t_egae + t_loss) / max(M, 1) + (t_head / n_head if n_head else 0.0)
+    return dict(value=1.0 / per_token, unit="tokens/s", cores=len(os.sched_getaffinity(0)),
+                kind="oracle",
+                sample=(f"LM head on {n_head} seeded kept rows of {M} ({t_head:.1f}s); select, EGAE and "
+                        f"losses on the full batch ({t_sel + t_egae + t_loss:.1f}s); per-token costs added"))
+
+
+if __name__ == "__main__":
+    main()

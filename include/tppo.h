@@ -1,0 +1,207 @@
+/*
+ * tppo.h -- C ABI of the MI355X (gfx950) per-token core of Truncated PPO.
+ *
+ * Four operations of one T-PPO training step (Algorithm 1, lines 6, 8, 9):
+ *   tppo_select          token filter of Sec. 3.2 -> compact gather indices
+ *   tppo_token_logprobs  log pi_theta(a_t|s_t) of the kept tokens (the quantity
+ *                        in the ratio of Eq. (ppoloss)), LM head fused with
+ *                        log-softmax and target gather; logits are never stored
+ *   tppo_egae            Extended GAE advantages (Eq. (egae), Sec. 3.1) and
+ *                        Monte-Carlo returns R_t (Sec. 2.4)
+ *   tppo_ppo_losses      clipped surrogate (Eq. (ppoloss)) and clipped value
+ *                        loss (Eqs. (valueclip), (valueloss)) over the policy /
+ *                        value token sets of Sec. 3.2
+ *
+ * Conventions common to every entry point
+ *   - Every array pointer is DEVICE memory owned by the caller, valid until the
+ *     work enqueued by the call has finished.  The library allocates nothing,
+ *     frees nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued asynchronously on it; no call synchronises with the
+ *     host, which is why scalar results are written to device memory.
+ *   - Scratch memory comes from the caller: `*_workspace_bytes` gives the size
+ *     for the same size arguments; the workspace needs no initialisation and
+ *     must be 256-byte aligned.  One workspace must not be shared by calls
+ *     that may overlap in time.
+ *   - Return value: 0 on success, a negative tppo_error otherwise.  On error
+ *     nothing has been enqueued.  Errors the host cannot see (bad indices in
+ *     device arrays) set bits of the optional device word `status` (may be
+ *     NULL; the caller zeroes it) and the offending element is skipped.
+ *   - Indices and offsets are int32, sizes int64; address arithmetic in the
+ *     kernels is 64-bit.
+ *
+ * Batch layout (Sec. 2.1, Sec. 3.2).  B sequences packed back to back.
+ * Sequence i owns packed positions cu_seqlens[i] .. cu_seqlens[i+1]-1: first
+ * ctx_len[i] >= 1 context tokens (prompt and tokens generated in earlier
+ * steps), then win_len[i] tokens generated in the current step.  done[i] = 1 if
+ * it emitted end-of-sequence inside the window, 0 if it was cut at the window
+ * length.  The "response-packed" domain numbers only window tokens: element
+ * resp_off[i]+t is window token t of sequence i, n_resp = resp_off[B].
+ */
+#ifndef TPPO_H
+#define TPPO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TPPO_OK = 0,
+    TPPO_ERR_NULL = -1,      /* a required pointer is NULL */
+    TPPO_ERR_SIZE = -2,      /* negative, inconsistent or unsupported size */
+    TPPO_ERR_PARAM = -3,     /* scalar out of range (gamma, lambda outside [0,1]; negative eps, xi, tail_drop) */
+    TPPO_ERR_DTYPE = -4,     /* unknown tppo_dtype */
+    TPPO_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small */
+    TPPO_ERR_LAUNCH = -6     /* the HIP runtime refused a launch */
+} tppo_error;
+
+/* bits of the device status word */
+enum {
+    TPPO_STATUS_BAD_TARGET = 1,   /* a target id outside [0, V): its logp is NaN */
+    TPPO_STATUS_BAD_LAYOUT = 2,   /* ctx_len < 1, negative window length or non-monotone offsets */
+    TPPO_STATUS_CAPACITY = 4,     /* more kept tokens than `capacity`: excess not written */
+    TPPO_STATUS_BAD_ROW = 8,      /* a row index outside [0, n_rows): its logp is NaN */
+    TPPO_STATUS_TIMEOUT = 16      /* an inter-workgroup wait gave up (results invalid) */
+};
+
+typedef enum { TPPO_F32 = 0, TPPO_BF16 = 1 } tppo_dtype;
+
+/* Library version, for the binding's sanity check. */
+int tppo_version(void);
+
+/* ---------------------------------------------------------------------------
+ * tppo_select -- token filter (Sec. 3.2; abstract: prompt and truncated tokens
+ * are filtered out of the policy update).
+ *
+ * Policy tokens: every window token of every sequence, finished or not, except
+ * the `tail_drop` latest tokens of an unfinished sequence:
+ *   keep_len[i] = done[i] ? win_len[i] : max(win_len[i] - tail_drop, 0).
+ * Value tokens: all window tokens of finished sequences.  Context tokens are in
+ * neither set.  For kept token t of sequence i, in order of (i, t), at compact
+ * index m = sel_off[i] + t:
+ *   sel_rows[m]     = cu_seqlens[i] + ctx_len[i] + t - 1   (the state s_t that
+ *                     predicts it: Sec. 2.1, s_t holds the tokens before t)
+ *   sel_targets[m]  = input_ids[cu_seqlens[i] + ctx_len[i] + t]
+ *   sel_resp_idx[m] = resp_off[i] + t
+ *
+ * in : cu_seqlens[B+1], ctx_len[B], done[B] int32; input_ids[n_tok] int32
+ *      (may be NULL together with sel_targets).
+ * out: resp_off[B+1], sel_off[B+1], keep_len[B] int32; sel_rows, sel_targets,
+ *      sel_resp_idx: `capacity` int32 each (each may be NULL = not wanted;
+ *      n_tok is always a sufficient capacity); counts[3] int64 =
+ *      { M = sel_off[B], n_resp = resp_off[B], N_val = number of value tokens }.
+ * Errors: NULL required pointer, B < 0, n_tok < 0, capacity < 0 ->
+ *      TPPO_ERR_NULL / TPPO_ERR_SIZE; tail_drop < 0 -> TPPO_ERR_PARAM.
+ *      B = 0 is valid (counts = 0).  Sequences with a bad layout set
+ *      TPPO_STATUS_BAD_LAYOUT and are treated as having an empty window.
+ */
+int tppo_select(const int32_t* cu_seqlens, const int32_t* ctx_len, const int32_t* done,
+                const int32_t* input_ids, int64_t B, int64_t n_tok, int32_t tail_drop,
+                int32_t* resp_off, int32_t* sel_off, int32_t* keep_len,
+                int32_t* sel_rows, int32_t* sel_targets, int32_t* sel_resp_idx,
+                int64_t capacity, int64_t* counts, int32_t* status, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * tppo_token_logprobs -- log-probability of each kept token under the current
+ * policy, log pi_theta(a_t|s_t), the numerator of the ratio in Eq. (ppoloss):
+ *   z = W_head h_{sel_rows[m]}           (V logits, never written to memory)
+ *   lse[m]  = log sum_v exp z[v]
+ *   logp[m] = z[sel_targets[m]] - lse[m]
+ * Only the M kept rows are projected; prompt rows and dropped tails cost
+ * nothing (the filtered policy update of Sec. 3.2).  No bias, temperature 1.
+ *
+ * in : hidden  [n_rows, H] row-major with leading dimension ld_hidden (elements);
+ *      w_head  [V, H] row-major (torch Linear.weight layout), leading dim ld_w;
+ *      both of type `dt` (TPPO_BF16: bf16 inputs, fp32 accumulation on the
+ *      matrix cores when H % 64 == 0 and both leading dimensions are multiples
+ *      of 8 and the base pointers 16-byte aligned, otherwise a slower generic
+ *      kernel; TPPO_F32: fp32 FMA kernel);
+ *      sel_rows[M], sel_targets[M] int32;
+ *      m_actual: optional device int64 (e.g. counts+0 of tppo_select): only the
+ *      first min(M, *m_actual) tokens are computed, so M can be a host-side
+ *      upper bound and no read-back is needed.  NULL = M.
+ *      out_index: optional int32[M]; result m is written to logp[out_index[m]]
+ *      (e.g. sel_resp_idx, to scatter into the response-packed domain).
+ * out: logp fp32, lse fp32 (NULL = not wanted), indexed by m or out_index[m].
+ * Errors: M, H, V, n_rows < 0, H = 0 or V = 0 with M > 0, ld < H ->
+ *      TPPO_ERR_SIZE; M = 0 is valid and does nothing.  Bad row / target ids set
+ *      status bits and yield NaN for that token.
+ */
+size_t tppo_token_logprobs_workspace_bytes(int64_t M, int64_t H, int64_t V, tppo_dtype dt);
+int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H, int64_t ld_hidden,
+                        const void* w_head, int64_t V, int64_t ld_w, tppo_dtype dt,
+                        const int32_t* sel_rows, const int32_t* sel_targets, int64_t M,
+                        const int64_t* m_actual, const int32_t* out_index,
+                        float* logp, float* lse,
+                        void* workspace, size_t workspace_bytes,
+                        int32_t* status, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * tppo_egae -- Extended GAE (Sec. 3.1, Eq. (egae)) and returns (Sec. 2.4), for
+ * every window token of every sequence (the filter applies to the losses, not
+ * to the recurrence).  With l = win_len[i], per sequence:
+ *   delta_t = r_t + gamma V(s_{t+1}) - V(s_t)                       (Eq. (TD))
+ *   V(s_l)  = 0                 if done[i]   (terminal state)
+ *           = bootstrap[i]      if bootstrap != NULL
+ *           = V(s_{l-1})        otherwise    (the assumption of Sec. 3.1)
+ *   A_t = sum_{k=t}^{l-1} (gamma lambda)^{k-t} delta_k            (Eq. (egae))
+ *   R_t = sum_{k=t}^{l-1} gamma^{k-t} r_k     (observed rewards only)
+ * Finished sequences therefore get standard GAE (Eq. (gae)).
+ *
+ * in : rewards[n_resp], values[n_resp] fp32, response-packed, values[j] = V(s_t)
+ *      of the rollout-time critic; resp_off[B+1], done[B] int32;
+ *      bootstrap[B] fp32 or NULL.
+ * out: adv[n_resp], ret[n_resp] fp32.  May not alias the inputs.
+ * Errors: gamma or lambda outside [0,1] -> TPPO_ERR_PARAM; negative sizes ->
+ *      TPPO_ERR_SIZE.  n_resp = 0 is valid.  resp_off must be non-decreasing
+ *      with resp_off[0] = 0 and resp_off[B] = n_resp (empty sequences allowed).
+ */
+size_t tppo_egae_workspace_bytes(int64_t n_resp, int64_t B);
+int tppo_egae(const float* rewards, const float* values, const int32_t* resp_off,
+              const int32_t* done, const float* bootstrap,
+              int64_t B, int64_t n_resp, float gamma, float lambda,
+              float* adv, float* ret, void* workspace, size_t workspace_bytes,
+              int32_t* status, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * tppo_ppo_losses -- token-level losses (Sec. 4.1.1) of one update:
+ *   rho_t = exp(logp_new - logp_old)
+ *   policy_sum = - sum_{policy tokens} min(rho_t A_t, clip(rho_t, 1-eps_low, 1+eps_high) A_t)
+ *   policy_loss = policy_sum / n_policy            (= -J_PPO, Eq. (ppoloss))
+ *   V_clip = clip(v_new, v_old - xi_low, v_old + xi_high)        (Eq. (valueclip))
+ *   value_sum = 1/2 sum_{value tokens} max((v_new - R)^2, (V_clip - R)^2)
+ *   value_loss = value_sum / n_value               (= J_value, Eq. (valueloss))
+ * Policy tokens of sequence i: window tokens t < keep_len[i]; value tokens: all
+ * window tokens of sequences with done[i] != 0 (Sec. 3.2).  Entries outside a
+ * set are not read, so whatever they hold cannot influence the result.  Empty
+ * sets give a loss of 0.  The un-normalised sums and counts let the caller
+ * combine minibatches.  Reductions are deterministic (no float atomics).
+ *
+ * in : six fp32 arrays [n_resp], response-packed; the three policy arrays
+ *      (logp_new, logp_old, adv) may all be NULL to skip the policy half,
+ *      likewise (v_new, v_old, ret); resp_off[B+1], keep_len[B], done[B] int32.
+ * out: one tppo_loss_out in device memory.
+ * Errors: eps or xi negative -> TPPO_ERR_PARAM; a half with only some of its
+ *      arrays NULL -> TPPO_ERR_NULL.
+ */
+typedef struct {
+    float policy_loss, value_loss, policy_sum, value_sum;
+    int64_t n_policy, n_value;
+} tppo_loss_out;
+
+size_t tppo_ppo_losses_workspace_bytes(int64_t n_resp, int64_t B);
+int tppo_ppo_losses(const float* logp_new, const float* logp_old, const float* adv,
+                    const float* v_new, const float* v_old, const float* ret,
+                    const int32_t* resp_off, const int32_t* keep_len, const int32_t* done,
+                    int64_t B, int64_t n_resp,
+                    float eps_low, float eps_high, float xi_low, float xi_high,
+                    tppo_loss_out* out, void* workspace, size_t workspace_bytes,
+                    int32_t* status, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TPPO_H */

@@ -1,0 +1,187 @@
+"""Thin ctypes binding of libtppo.so (see include/tppo.h for the contract).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+PyTorch provides device memory and the current HIP stream.  There is no CPU
+fallback: if the shared library is missing, every call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtppo.so")
+
+TPPO_F32, TPPO_BF16 = 0, 1
+ERRORS = {-1: "TPPO_ERR_NULL", -2: "TPPO_ERR_SIZE", -3: "TPPO_ERR_PARAM", -4: "TPPO_ERR_DTYPE",
+          -5: "TPPO_ERR_WORKSPACE", -6: "TPPO_ERR_LAUNCH"}
+STATUS_BAD_TARGET, STATUS_BAD_LAYOUT, STATUS_CAPACITY, STATUS_BAD_ROW, STATUS_TIMEOUT = 1, 2, 4, 8, 16
+
+_c_i64, _c_i32, _c_f32, _c_ptr, _c_size = (ctypes.c_int64, ctypes.c_int32, ctypes.c_float,
+                                            ctypes.c_void_p, ctypes.c_size_t)
+_SIGNATURES = {
+    "tppo_version": (ctypes.c_int, []),
+    "tppo_select": (ctypes.c_int, [_c_ptr] * 4 + [_c_i64, _c_i64, _c_i32] + [_c_ptr] * 6 +
+                    [_c_i64, _c_ptr, _c_ptr, _c_ptr]),
+    "tppo_token_logprobs_workspace_bytes": (_c_size, [_c_i64, _c_i64, _c_i64, ctypes.c_int]),
+    "tppo_token_logprobs": (ctypes.c_int, [_c_ptr, _c_i64, _c_i64, _c_i64, _c_ptr, _c_i64, _c_i64,
+                                           ctypes.c_int, _c_ptr, _c_ptr, _c_i64, _c_ptr, _c_ptr,
+                                           _c_ptr, _c_ptr, _c_ptr, _c_size, _c_ptr, _c_ptr]),
+    "tppo_egae_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
+    "tppo_egae": (ctypes.c_int, [_c_ptr] * 5 + [_c_i64, _c_i64, _c_f32, _c_f32, _c_ptr, _c_ptr,
+                                                _c_ptr, _c_size, _c_ptr, _c_ptr]),
+    "tppo_ppo_losses_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
+    "tppo_ppo_losses": (ctypes.c_int, [_c_ptr] * 9 + [_c_i64, _c_i64] + [_c_f32] * 4 +
+                        [_c_ptr, _c_ptr, _c_size, _c_ptr, _c_ptr]),
+}
+EXPORTS = tuple(_SIGNATURES)
+_lib = None
+
+
+def load():
+    """Load libtppo.so (built by ``python -m paper_2506_15050_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2506_15050_amd.build`; there is no fallback path")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"{what} failed: {ERRORS.get(rc, rc)}")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_i32(t):
+    assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()
+    return t
+
+
+def _dev_f32(t):
+    assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    return t
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def new_status(device):
+    return torch.zeros(1, dtype=torch.int32, device=device)
+
+
+def tppo_select(cu_seqlens, ctx_len, done, input_ids, tail_drop, capacity=None, status=None,
+                want_indices=True, n_tok=None):
+    """Token filter.  Returns a dict of device tensors: resp_off, sel_off, keep_len,
+    sel_rows, sel_targets, sel_resp_idx (capacity-sized) and counts (int64[3] =
+    M, n_resp, N_val)."""
+    lib = load()
+    dev = cu_seqlens.device
+    B = ctx_len.numel()
+    if input_ids is not None:
+        n_tok = input_ids.numel()
+    assert n_tok is not None, "n_tok is required when input_ids is None"
+    cap = n_tok if capacity is None else int(capacity)
+    out = dict(resp_off=torch.empty(B + 1, dtype=torch.int32, device=dev),
+               sel_off=torch.empty(B + 1, dtype=torch.int32, device=dev),
+               keep_len=torch.empty(B, dtype=torch.int32, device=dev),
+               counts=torch.empty(3, dtype=torch.int64, device=dev))
+    if want_indices:
+        for k in ("sel_rows", "sel_targets", "sel_resp_idx"):
+            out[k] = torch.empty(cap, dtype=torch.int32, device=dev)
+        if input_ids is None:
+            out["sel_targets"] = None
+    rc = lib.tppo_select(_ptr(_dev_i32(cu_seqlens)), _ptr(_dev_i32(ctx_len)), _ptr(_dev_i32(done)),
+                         _ptr(input_ids), B, n_tok, int(tail_drop),
+                         _ptr(out["resp_off"]), _ptr(out["sel_off"]), _ptr(out["keep_len"]),
+                         _ptr(out.get("sel_rows")), _ptr(out.get("sel_targets")),
+                         _ptr(out.get("sel_resp_idx")), cap, _ptr(out["counts"]), _ptr(status),
+                         _stream())
+    _check(rc, "tppo_select")
+    return out
+
+
+def tppo_token_logprobs(hidden, w_head, sel_rows, sel_targets, M=None, m_actual=None,
+                        out_index=None, out_size=None, want_lse=True, status=None, workspace=None):
+    """log pi(a_t|s_t) of the kept tokens.  hidden [n_rows, H], w_head [V, H], both
+    bf16 or both fp32.  Returns (logp, lse)."""
+    lib = load()
+    assert hidden.is_cuda and w_head.is_cuda and hidden.dtype == w_head.dtype
+    assert hidden.dim() == 2 and w_head.dim() == 2 and hidden.stride(1) == 1 and w_head.stride(1) == 1
+    dt = {torch.float32: TPPO_F32, torch.bfloat16: TPPO_BF16}[hidden.dtype]
+    n_rows, H = hidden.shape
+    V = w_head.shape[0]
+    M = sel_rows.numel() if M is None else int(M)
+    n_out = M if out_size is None else int(out_size)
+    logp = torch.empty(n_out, dtype=torch.float32, device=hidden.device)
+    lse = torch.empty(n_out, dtype=torch.float32, device=hidden.device) if want_lse else None
+    ws_bytes = lib.tppo_token_logprobs_workspace_bytes(M, H, V, dt)
+    ws = _workspace(ws_bytes, hidden.device) if workspace is None else workspace
+    rc = lib.tppo_token_logprobs(_ptr(hidden), n_rows, H, hidden.stride(0), _ptr(w_head), V,
+                                 w_head.stride(0), dt, _ptr(_dev_i32(sel_rows)),
+                                 _ptr(_dev_i32(sel_targets)), M, _ptr(m_actual), _ptr(out_index),
+                                 _ptr(logp), _ptr(lse), _ptr(ws), ws.numel(), _ptr(status), _stream())
+    _check(rc, "tppo_token_logprobs")
+    return logp, lse
+
+
+def tppo_egae(rewards, values, resp_off, done, gamma, lam, bootstrap=None, status=None,
+              workspace=None, out=None):
+    """Extended GAE advantages and Monte-Carlo returns.  Returns (adv, ret)."""
+    lib = load()
+    n_resp, B = rewards.numel(), done.numel()
+    adv, ret = out if out is not None else (torch.empty_like(rewards), torch.empty_like(rewards))
+    ws_bytes = lib.tppo_egae_workspace_bytes(n_resp, B)
+    ws = _workspace(ws_bytes, rewards.device) if workspace is None else workspace
+    rc = lib.tppo_egae(_ptr(_dev_f32(rewards)), _ptr(_dev_f32(values)), _ptr(_dev_i32(resp_off)),
+                       _ptr(_dev_i32(done)), _ptr(bootstrap), B, n_resp, float(gamma), float(lam),
+                       _ptr(adv), _ptr(ret), _ptr(ws), ws.numel(), _ptr(status), _stream())
+    _check(rc, "tppo_egae")
+    return adv, ret
+
+
+class LossOut(ctypes.Structure):
+    _fields_ = [("policy_loss", ctypes.c_float), ("value_loss", ctypes.c_float),
+                ("policy_sum", ctypes.c_float), ("value_sum", ctypes.c_float),
+                ("n_policy", ctypes.c_int64), ("n_value", ctypes.c_int64)]
+
+
+def tppo_ppo_losses(logp_new, logp_old, adv, v_new, v_old, ret, resp_off, keep_len, done,
+                    eps_low, eps_high, xi_low, xi_high, status=None, workspace=None, out=None):
+    """Clipped policy / value losses.  Returns a 32-byte device tensor holding a
+    ``tppo_loss_out``; ``read_loss_out`` copies it to the host."""
+    lib = load()
+    dev = resp_off.device
+    B = done.numel()
+    n_resp = (logp_new if logp_new is not None else v_new).numel()
+    res = torch.empty(ctypes.sizeof(LossOut), dtype=torch.uint8, device=dev) if out is None else out
+    ws_bytes = lib.tppo_ppo_losses_workspace_bytes(n_resp, B)
+    ws = _workspace(ws_bytes, dev) if workspace is None else workspace
+    rc = lib.tppo_ppo_losses(_ptr(logp_new), _ptr(logp_old), _ptr(adv), _ptr(v_new), _ptr(v_old),
+                             _ptr(ret), _ptr(_dev_i32(resp_off)), _ptr(_dev_i32(keep_len)),
+                             _ptr(_dev_i32(done)), B, n_resp, float(eps_low), float(eps_high),
+                             float(xi_low), float(xi_high), _ptr(res), _ptr(ws), ws.numel(),
+                             _ptr(status), _stream())
+    _check(rc, "tppo_ppo_losses")
+    return res
+
+
+def read_loss_out(res):
+    """Device ``tppo_loss_out`` -> dict (synchronises)."""
+    raw = bytes(res.cpu().numpy().tobytes())
+    s = LossOut.from_buffer_copy(raw)
+    return {name: getattr(s, name) for name, _ in LossOut._fields_}

@@ -1,0 +1,37 @@
+// Internal helpers shared by the HIP translation units of libtppo (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tppo.h"
+
+#define TPPO_VERSION 100
+
+namespace tppo {
+
+constexpr int kWave = 64;
+
+static inline bool is_aligned(const void* p, size_t a) {
+    return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;
+}
+
+static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static inline int launch_result() {
+    return hipGetLastError() == hipSuccess ? TPPO_OK : TPPO_ERR_LAUNCH;
+}
+
+__device__ __forceinline__ void set_status(int32_t* status, int32_t bit) {
+    if (status) atomicOr(status, bit);
+}
+
+// largest s in [lo, hi] with off[s] <= p  (off non-decreasing, off[lo] <= p)
+__device__ __forceinline__ int find_segment(const int32_t* off, int lo, int hi, int p) {
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (off[mid] <= p) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+}  // namespace tppo

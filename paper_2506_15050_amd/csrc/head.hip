@@ -1,0 +1,495 @@
+// tppo_token_logprobs: log pi_theta(a_t|s_t) of the kept tokens -- the LM head
+// W_head h fused with log-softmax and the gather of the sampled token's logit
+// (the quantity inside the ratio of Eq. (ppoloss)); logits never reach memory.
+//
+// bf16 path (matrix cores).  The logits of a 256-token x 256-vocabulary tile
+// are accumulated with v_mfma_f32_32x32x16_bf16.  The MFMA "row" operand is the
+// W tile and the "column" operand the gathered hidden rows, so a lane's 16
+// accumulators of one 32x32 block all belong to ONE token (column lane%32) and
+// 16 different vocabulary entries: the running maximum, the running sum of
+// exponentials and the target logit of a token live in that lane's registers
+// across all vocabulary tiles of the workgroup, with no cross-lane traffic
+// until the very end.  The grid is (token tiles) x (vocabulary splits); each
+// workgroup sweeps its share of vocabulary tiles and writes one
+// (max, sumexp, target logit) triple per token; a small kernel merges the
+// splits into logp and lse.
+//
+// Both operands are K-contiguous in memory ([V,H] and [rows,H]), which is the
+// layout the MFMA wants for both, so tiles are staged into LDS as 16-byte
+// chunks with an XOR swizzle of the chunk index (conflict-free ds_read_b128)
+// and read back as operand fragments directly.
+#include "common.h"
+
+namespace tppo {
+
+// ------------------------------------------------------------------ generic
+// One workgroup per kept token, one wavefront per vocabulary row at a time.
+// fp32 FMA; serves TPPO_F32 and bf16 shapes the MFMA path does not take.
+constexpr int kGenThreads = 256;
+constexpr int kGenMaxH = 16384;
+
+__device__ __forceinline__ float load_as_float(const float* p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float load_as_float(const uint16_t* p, int64_t i) {
+    return __uint_as_float((unsigned)p[i] << 16);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kGenThreads) void head_generic_kernel(
+    const T* __restrict__ hidden, int64_t n_rows, int H, int64_t ld_h, const T* __restrict__ w,
+    int V, int64_t ld_w, const int32_t* __restrict__ sel_rows,
+    const int32_t* __restrict__ sel_targets, int64_t M, const int64_t* __restrict__ m_actual,
+    const int32_t* __restrict__ out_index, float* __restrict__ logp, float* __restrict__ lse,
+    int32_t* status) {
+    extern __shared__ float s_h[];
+    __shared__ float s_part[3][kGenThreads / kWave];
+    const int64_t m = blockIdx.x;
+    const int64_t m_eff = m_actual ? min(M, *m_actual) : M;
+    if (m >= m_eff) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = sel_rows[m];
+    const int tgt = sel_targets[m];
+    const int64_t o = out_index ? (int64_t)out_index[m] : m;
+    const bool bad_row = row < 0 || row >= n_rows, bad_tgt = tgt < 0 || tgt >= V;
+    if (bad_row || bad_tgt) {
+        if (tid == 0) {
+            set_status(status, bad_row ? TPPO_STATUS_BAD_ROW : TPPO_STATUS_BAD_TARGET);
+            logp[o] = __builtin_nanf("");
+            if (lse) lse[o] = __builtin_nanf("");
+        }
+        return;
+    }
+    for (int k = tid; k < H; k += kGenThreads) s_h[k] = load_as_float(hidden, row * ld_h + k);
+    __syncthreads();
+    float mx = -INFINITY, sum = 0.f, tz = 0.f;
+    for (int v = wave; v < V; v += kGenThreads / kWave) {
+        const T* wr = w + (int64_t)v * ld_w;
+        float z = 0.f;
+        for (int k = lane; k < H; k += kWave) z = fmaf(s_h[k], load_as_float(wr, k), z);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) z += __shfl_xor(z, off);
+        const float mn = fmaxf(mx, z);
+        sum = sum * expf(mx - mn) + expf(z - mn);
+        mx = mn;
+        if (v == tgt) tz = z;
+    }
+    if (lane == 0) {
+        s_part[0][wave] = mx;
+        s_part[1][wave] = sum;
+        s_part[2][wave] = tz;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float gm = -INFINITY, gs = 0.f, gt = 0.f;
+        for (int q = 0; q < kGenThreads / kWave; ++q) gm = fmaxf(gm, s_part[0][q]);
+        for (int q = 0; q < kGenThreads / kWave; ++q) {
+            if (s_part[1][q] > 0.f) gs += s_part[1][q] * expf(s_part[0][q] - gm);
+            gt += s_part[2][q];
+        }
+        const float l = gm + logf(gs);
+        logp[o] = gt - l;
+        if (lse) lse[o] = l;
+    }
+}
+
+// ------------------------------------------------------------------ MFMA path
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int kTileV = 256;            // vocabulary rows per workgroup tile
+constexpr int kTileT = 256;            // tokens per workgroup tile
+constexpr int kBK = 64;                // K elements per LDS stage
+constexpr int kRowBytes = kBK * 2;     // 128 B per staged row
+constexpr int kStageBytes = (kTileV + kTileT) * kRowBytes;   // 64 KiB
+constexpr int kStages = 2;
+constexpr int kHeadLds = kStages * kStageBytes;              // 128 KiB of the 160 KiB LDS
+constexpr int kMaxSplits = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kNegBig = -3.0e38f;    // finite stand-in for -inf (keeps exp2(m - m') NaN-free)
+
+struct HeadParams {
+    const uint16_t* hidden;
+    const uint16_t* w;
+    const int32_t* sel_rows;
+    const int32_t* sel_targets;
+    const int64_t* m_actual;
+    float* part;                       // [3][splits][M]: max (log2 domain), sumexp, target logit
+    int64_t n_rows, ld_h, ld_w, M;
+    int H, V, row_tiles, splits, vocab_tiles;
+};
+
+// byte offset of 16-byte chunk `c` (0..7) of staged row `r`
+__device__ __forceinline__ int lds_chunk_off(int r, int c) {
+    return r * kRowBytes + ((c ^ (r & 7)) << 4);
+}
+
+// Workgroup id -> (token tile, vocabulary split).  Consecutive hardware ids go
+// round-robin over the 8 XCDs, so ids are first regrouped into 8 contiguous
+// ranges (one per XCD, each with its own L2); inside a range, 8 token tiles x
+// all splits are adjacent, so the ~32 workgroups resident on an XCD share
+// their W tiles (same split, different token tile) and hidden tiles.
+__device__ __forceinline__ void decode_block(int bid, int grid, int row_tiles, int splits, int& rt,
+                                             int& sp) {
+    const int per_xcd = grid / 8;
+    int l = bid;
+    if (bid < per_xcd * 8) l = (bid & 7) * per_xcd + (bid >> 3);
+    const int group = l / (8 * splits), in_group = l - group * 8 * splits;
+    const int rows_here = min(8, row_tiles - group * 8);
+    sp = in_group / rows_here;
+    rt = group * 8 + (in_group - sp * rows_here);
+}
+
+template <int kWavesV, int kWavesT>
+__global__ __launch_bounds__(kWavesV* kWavesT * 64) void head_mfma_kernel(HeadParams p) {
+    constexpr int kThreads = kWavesV * kWavesT * 64;
+    constexpr int kWaveV = kTileV / kWavesV, kWaveT = kTileT / kWavesT;   // wave tile
+    constexpr int kVB = kWaveV / 32, kTB = kWaveT / 32;                   // 32x32 blocks per wave
+    constexpr int kRowsPerPass = kThreads / 8;                            // 8 chunks per row
+    constexpr int kPasses = kTileV / kRowsPerPass;
+    static_assert(kTileV == kTileT, "loader assumes square tiles");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    int rt, sp;
+    decode_block(blockIdx.x, gridDim.x, p.row_tiles, p.splits, rt, sp);
+    const int64_t m_eff = p.m_actual ? min(p.M, *p.m_actual) : p.M;
+    const int64_t tok0 = (int64_t)rt * kTileT;
+    if (tok0 >= m_eff) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wv = wave / kWavesT, wt = wave % kWavesT;
+    const int vt_begin = (int)((int64_t)p.vocab_tiles * sp / p.splits);
+    const int vt_end = (int)((int64_t)p.vocab_tiles * (sp + 1) / p.splits);
+    const int k_tiles = p.H / kBK;
+    const int total_iters = (vt_end - vt_begin) * k_tiles;
+
+    // ---- loader role: chunk c of rows r0 + pass*kRowsPerPass
+    const int ld_c = tid & 7, ld_r0 = tid >> 3;
+    const uint16_t* b_ptr[kPasses];                    // gathered hidden rows (fixed for the sweep)
+#pragma unroll
+    for (int q = 0; q < kPasses; ++q) {
+        int64_t t = tok0 + ld_r0 + q * kRowsPerPass;
+        t = min(t, m_eff - 1);
+        int64_t row = p.sel_rows[t];
+        row = min(max(row, (int64_t)0), p.n_rows - 1);
+        b_ptr[q] = p.hidden + row * p.ld_h + ld_c * 8;
+    }
+
+    // ---- per-lane softmax state for my kTB token columns
+    float run_max[kTB], run_sum[kTB], tgt_logit[kTB];
+    int tgt[kTB];
+#pragma unroll
+    for (int tb = 0; tb < kTB; ++tb) {
+        run_max[tb] = kNegBig;
+        run_sum[tb] = 0.f;
+        tgt_logit[tb] = 0.f;
+        const int64_t t = tok0 + wt * kWaveT + tb * 32 + (lane & 31);
+        tgt[tb] = t < m_eff ? p.sel_targets[t] : -1;
+    }
+
+    f32x16 acc[kVB][kTB];
+#pragma unroll
+    for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+        for (int tb = 0; tb < kTB; ++tb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
+
+    uint4 stage_a[kPasses], stage_b[kPasses];
+    auto load_global = [&](int it) {
+        const int vt = vt_begin + it / k_tiles, kt = it - (it / k_tiles) * k_tiles;
+        const int64_t k_off = (int64_t)kt * kBK;
+#pragma unroll
+        for (int q = 0; q < kPasses; ++q) {
+            int64_t v = (int64_t)vt * kTileV + ld_r0 + q * kRowsPerPass;
+            v = min(v, (int64_t)p.V - 1);
+            stage_a[q] = *reinterpret_cast<const uint4*>(p.w + v * p.ld_w + k_off + ld_c * 8);
+            stage_b[q] = *reinterpret_cast<const uint4*>(b_ptr[q] + k_off);
+        }
+    };
+    auto store_lds = [&](int buf) {
+        unsigned char* base = smem + buf * kStageBytes;
+#pragma unroll
+        for (int q = 0; q < kPasses; ++q) {
+            const int r = ld_r0 + q * kRowsPerPass;
+            *reinterpret_cast<uint4*>(base + lds_chunk_off(r, ld_c)) = stage_a[q];
+            *reinterpret_cast<uint4*>(base + kTileV * kRowBytes + lds_chunk_off(r, ld_c)) = stage_b[q];
+        }
+    };
+
+    if (total_iters > 0) {
+        load_global(0);
+        store_lds(0);
+    }
+    __syncthreads();
+
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    for (int it = 0; it < total_iters; ++it) {
+        const int buf = it & 1;
+        if (it + 1 < total_iters) load_global(it + 1);
+
+        const unsigned char* a_base = smem + buf * kStageBytes + (wv * kWaveV) * kRowBytes;
+        const unsigned char* b_base = smem + buf * kStageBytes + kTileV * kRowBytes + (wt * kWaveT) * kRowBytes;
+#pragma unroll
+        for (int ks = 0; ks < kBK / 16; ++ks) {
+            const int c = ks * 2 + frag_half;
+            bf16x8 fa[kVB], fb[kTB];
+#pragma unroll
+            for (int vb = 0; vb < kVB; ++vb)
+                fa[vb] = *reinterpret_cast<const bf16x8*>(a_base + lds_chunk_off(vb * 32 + frag_row, c));
+#pragma unroll
+            for (int tb = 0; tb < kTB; ++tb)
+                fb[tb] = *reinterpret_cast<const bf16x8*>(b_base + lds_chunk_off(tb * 32 + frag_row, c));
+#pragma unroll
+            for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+                for (int tb = 0; tb < kTB; ++tb)
+                    acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[vb], fb[tb], acc[vb][tb], 0, 0, 0);
+        }
+
+        const int kt = it % k_tiles;
+        if (kt == k_tiles - 1) {
+            // ---- a vocabulary tile is complete: fold it into the running softmax
+            const int vt = vt_begin + it / k_tiles;
+            const int v_wave = vt * kTileV + wv * kWaveV;          // first vocabulary id of my wave tile
+            const int v_lane = v_wave + frag_half * 4;              // + vb*32 + (e/4)*8 + e%4
+            if (vt * kTileV + kTileV > p.V) {                       // ragged last tile: mask ids >= V
+#pragma unroll
+                for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+                    for (int tb = 0; tb < kTB; ++tb)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            if (v_lane + vb * 32 + (e >> 2) * 8 + (e & 3) >= p.V) acc[vb][tb][e] = -INFINITY;
+            }
+#pragma unroll
+            for (int tb = 0; tb < kTB; ++tb) {
+                float mx0 = -INFINITY, mx1 = -INFINITY;
+#pragma unroll
+                for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+                    for (int e = 0; e < 16; e += 2) {
+                        mx0 = fmaxf(mx0, acc[vb][tb][e]);
+                        mx1 = fmaxf(mx1, acc[vb][tb][e + 1]);
+                    }
+                const float new_max = fmaxf(run_max[tb], fmaxf(mx0, mx1) * kLog2e);
+                float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+                for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+                    for (int e = 0; e < 16; e += 4) {
+                        s0 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e], kLog2e, -new_max));
+                        s1 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e + 1], kLog2e, -new_max));
+                        s2 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e + 2], kLog2e, -new_max));
+                        s3 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e + 3], kLog2e, -new_max));
+                    }
+                run_sum[tb] = fmaf(run_sum[tb], __builtin_amdgcn_exp2f(run_max[tb] - new_max), (s0 + s1) + (s2 + s3));
+                run_max[tb] = new_max;
+            }
+            // target logit: rare (a lane owns 64 of V ids per tile), so only
+            // waves in which some lane hits take the register-select path
+            bool hit = false;
+#pragma unroll
+            for (int tb = 0; tb < kTB; ++tb) {
+                const int d = tgt[tb] - v_wave;
+                hit |= d >= 0 && d < kWaveV && ((d >> 2) & 1) == frag_half;
+            }
+            if (__any(hit)) {
+#pragma unroll
+                for (int tb = 0; tb < kTB; ++tb) {
+                    const int d = tgt[tb] - v_wave;
+                    if (d >= 0 && d < kWaveV && ((d >> 2) & 1) == frag_half) {
+                        const int vb_t = d >> 5, e_t = ((d >> 3) & 3) * 4 + (d & 3);
+                        float z = 0.f;
+#pragma unroll
+                        for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e)
+                                z = (vb == vb_t && e == e_t) ? acc[vb][tb][e] : z;
+                        tgt_logit[tb] += z;
+                    }
+                }
+            }
+#pragma unroll
+            for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+                for (int tb = 0; tb < kTB; ++tb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
+        }
+
+        if (it + 1 < total_iters) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- merge the two lane halves (same token, different vocabulary rows),
+    // then the kWavesV waves that share a token, and write the split's triple
+#pragma unroll
+    for (int tb = 0; tb < kTB; ++tb) {
+        const float om = __shfl_xor(run_max[tb], 32), os = __shfl_xor(run_sum[tb], 32);
+        const float ot = __shfl_xor(tgt_logit[tb], 32);
+        const float nm = fmaxf(run_max[tb], om);
+        run_sum[tb] = run_sum[tb] * __builtin_amdgcn_exp2f(run_max[tb] - nm) + os * __builtin_amdgcn_exp2f(om - nm);
+        run_max[tb] = nm;
+        tgt_logit[tb] += ot;
+    }
+    float* s_merge = reinterpret_cast<float*>(smem);   // [kWavesV][3][kTileT]; stages are idle now
+    if (lane < 32) {
+#pragma unroll
+        for (int tb = 0; tb < kTB; ++tb) {
+            const int col = wt * kWaveT + tb * 32 + lane;
+            s_merge[(wv * 3 + 0) * kTileT + col] = run_max[tb];
+            s_merge[(wv * 3 + 1) * kTileT + col] = run_sum[tb];
+            s_merge[(wv * 3 + 2) * kTileT + col] = tgt_logit[tb];
+        }
+    }
+    __syncthreads();
+    for (int col = tid; col < kTileT; col += kThreads) {
+        const int64_t t = tok0 + col;
+        if (t >= m_eff) continue;
+        float gm = kNegBig, gs = 0.f, gt = 0.f;
+#pragma unroll
+        for (int q = 0; q < kWavesV; ++q) gm = fmaxf(gm, s_merge[(q * 3 + 0) * kTileT + col]);
+#pragma unroll
+        for (int q = 0; q < kWavesV; ++q) {
+            gs += s_merge[(q * 3 + 1) * kTileT + col] * __builtin_amdgcn_exp2f(s_merge[(q * 3 + 0) * kTileT + col] - gm);
+            gt += s_merge[(q * 3 + 2) * kTileT + col];
+        }
+        float* out = p.part + (int64_t)sp * p.M + t;
+        out[0] = gm;
+        out[(int64_t)p.splits * p.M] = gs;
+        out[2 * (int64_t)p.splits * p.M] = gt;
+    }
+}
+
+__global__ __launch_bounds__(256) void head_combine_kernel(
+    const float* __restrict__ part, int splits, int64_t M, const int64_t* __restrict__ m_actual,
+    const int32_t* __restrict__ sel_rows, const int32_t* __restrict__ sel_targets, int64_t n_rows,
+    int V, const int32_t* __restrict__ out_index, float* __restrict__ logp,
+    float* __restrict__ lse, int32_t* status) {
+    const int64_t m = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t m_eff = m_actual ? min(M, *m_actual) : M;
+    if (m >= m_eff) return;
+    const int64_t o = out_index ? (int64_t)out_index[m] : m;
+    const int64_t row = sel_rows[m];
+    const int tgt = sel_targets[m];
+    const bool bad_row = row < 0 || row >= n_rows, bad_tgt = tgt < 0 || tgt >= V;
+    if (bad_row || bad_tgt) {
+        set_status(status, bad_row ? TPPO_STATUS_BAD_ROW : TPPO_STATUS_BAD_TARGET);
+        logp[o] = __builtin_nanf("");
+        if (lse) lse[o] = __builtin_nanf("");
+        return;
+    }
+    const int64_t plane = (int64_t)splits * M;
+    float gm = kNegBig;
+    for (int s = 0; s < splits; ++s) gm = fmaxf(gm, part[(int64_t)s * M + m]);
+    float gs = 0.f, gt = 0.f;
+    for (int s = 0; s < splits; ++s) {
+        gs += part[plane + (int64_t)s * M + m] * exp2f(part[(int64_t)s * M + m] - gm);
+        gt += part[2 * plane + (int64_t)s * M + m];
+    }
+    const float l = (gm + log2f(gs)) * kLn2;
+    logp[o] = gt - l;
+    if (lse) lse[o] = l;
+}
+
+// number of vocabulary splits: minimise rounds x tiles-per-split over the 256
+// CUs (one 128 KiB-LDS workgroup per CU), with a small per-workgroup overhead
+static int choose_splits(int64_t M, int64_t V) {
+    const int64_t row_tiles = (M + kTileT - 1) / kTileT, vocab_tiles = (V + kTileV - 1) / kTileV;
+    int best = 1;
+    double best_cost = 1e300;
+    const int max_s = (int)(vocab_tiles < kMaxSplits ? vocab_tiles : kMaxSplits);
+    for (int s = 1; s <= max_s; ++s) {
+        const double rounds = (double)((row_tiles * s + 255) / 256);
+        const double per = (double)((vocab_tiles + s - 1) / s) + 0.25;
+        const double cost = rounds * per;
+        if (cost < best_cost - 1e-9) {
+            best_cost = cost;
+            best = s;
+        }
+    }
+    return best;
+}
+
+static bool mfma_eligible(const void* hidden, int64_t H, int64_t ld_h, const void* w, int64_t ld_w,
+                          tppo_dtype dt) {
+    return dt == TPPO_BF16 && H >= kBK && H % kBK == 0 && ld_h % 8 == 0 && ld_w % 8 == 0 &&
+           is_aligned(hidden, 16) && is_aligned(w, 16);
+}
+
+}  // namespace tppo
+
+extern "C" size_t tppo_token_logprobs_workspace_bytes(int64_t M, int64_t H, int64_t V,
+                                                      tppo_dtype dt) {
+    using namespace tppo;
+    (void)H;
+    if (M <= 0 || V <= 0 || dt != TPPO_BF16) return 256;
+    return round_up((size_t)3 * (size_t)choose_splits(M, V) * (size_t)M * sizeof(float), 256);
+}
+
+extern "C" int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H, int64_t ld_hidden,
+                                   const void* w_head, int64_t V, int64_t ld_w, tppo_dtype dt,
+                                   const int32_t* sel_rows, const int32_t* sel_targets, int64_t M,
+                                   const int64_t* m_actual, const int32_t* out_index, float* logp,
+                                   float* lse, void* workspace, size_t workspace_bytes,
+                                   int32_t* status, void* stream) {
+    using namespace tppo;
+    if (dt != TPPO_F32 && dt != TPPO_BF16) return TPPO_ERR_DTYPE;
+    if (M < 0 || H < 0 || V < 0 || n_rows < 0 || M > INT32_MAX || V > INT32_MAX - kTileV ||
+        H > INT32_MAX)
+        return TPPO_ERR_SIZE;
+    if (M == 0) return TPPO_OK;
+    if (H == 0 || V == 0 || n_rows == 0 || ld_hidden < H || ld_w < H) return TPPO_ERR_SIZE;
+    if (!hidden || !w_head || !sel_rows || !sel_targets || !logp) return TPPO_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    if (!mfma_eligible(hidden, H, ld_hidden, w_head, ld_w, dt)) {
+        if (H > kGenMaxH) return TPPO_ERR_SIZE;
+        const size_t lds = (size_t)H * sizeof(float);
+        if (dt == TPPO_F32)
+            hipLaunchKernelGGL(head_generic_kernel<float>, dim3((unsigned)M), dim3(kGenThreads), lds, s,
+                               static_cast<const float*>(hidden), n_rows, (int)H, ld_hidden,
+                               static_cast<const float*>(w_head), (int)V, ld_w, sel_rows, sel_targets, M,
+                               m_actual, out_index, logp, lse, status);
+        else
+            hipLaunchKernelGGL(head_generic_kernel<uint16_t>, dim3((unsigned)M), dim3(kGenThreads), lds, s,
+                               static_cast<const uint16_t*>(hidden), n_rows, (int)H, ld_hidden,
+                               static_cast<const uint16_t*>(w_head), (int)V, ld_w, sel_rows,
+                               sel_targets, M, m_actual, out_index, logp, lse, status);
+        return launch_result();
+    }
+
+    if (!workspace || !is_aligned(workspace, 256) ||
+        workspace_bytes < tppo_token_logprobs_workspace_bytes(M, H, V, dt))
+        return TPPO_ERR_WORKSPACE;
+    HeadParams p;
+    p.hidden = static_cast<const uint16_t*>(hidden);
+    p.w = static_cast<const uint16_t*>(w_head);
+    p.sel_rows = sel_rows;
+    p.sel_targets = sel_targets;
+    p.m_actual = m_actual;
+    p.part = static_cast<float*>(workspace);
+    p.n_rows = n_rows; p.ld_h = ld_hidden; p.ld_w = ld_w; p.M = M;
+    p.H = (int)H; p.V = (int)V;
+    p.row_tiles = (int)((M + kTileT - 1) / kTileT);
+    p.vocab_tiles = (int)((V + kTileV - 1) / kTileV);
+    p.splits = choose_splits(M, V);
+
+    auto kernel = head_mfma_kernel<2, 4>;
+    static bool attr_set = false;   // raising the dynamic-LDS limit is idempotent; races are benign
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kHeadLds) != hipSuccess)
+            return TPPO_ERR_LAUNCH;
+        attr_set = true;
+    }
+    const int grid = p.row_tiles * p.splits;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(512), kHeadLds, s, p);
+    if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
+    hipLaunchKernelGGL(head_combine_kernel, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, s, p.part,
+                       p.splits, M, m_actual, sel_rows, sel_targets, n_rows, (int)V, out_index, logp,
+                       lse, status);
+    return launch_result();
+}
+
+extern "C" int tppo_version(void) { return TPPO_VERSION; }

@@ -1,0 +1,455 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Tolerances: indices bit-exact; log-probs
+abs 2e-3; EGAE |x-y| <= 1e-5*max(|y|,1); losses rel 1e-3."""
+import numpy as np
+import pytest
+
+from oracle import fast as ofast
+from paper_2506_15050_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+LOGP_ATOL = 2e-3
+EGAE_RTOL = 1e-5
+LOSS_RTOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def tp():
+    import torch
+    from paper_2506_15050_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()
+    return binding
+
+
+def dev(a):
+    import torch
+    if a is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if a.dtype == np.uint16:
+        t = t.view(torch.int16).view(torch.bfloat16)
+    return t.cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def assert_egae_close(got, ref, what):
+    ref = np.asarray(ref, np.float64)
+    err = np.abs(got.astype(np.float64) - ref)
+    tol = EGAE_RTOL * np.maximum(np.abs(ref), 1.0)
+    bad = np.nonzero(err > tol)[0]
+    assert bad.size == 0, f"{what}: {bad.size} mismatches, first at {bad[:5]}, err {err[bad[:5]]}"
+
+
+def run_select(tp, b, tail_drop=None, capacity=None, with_ids=True):
+    st = tp.new_status("cuda")
+    out = tp.tppo_select(dev(b["cu_seqlens"]), dev(b["ctx_len"]), dev(b["done"]),
+                         dev(b["input_ids"]) if with_ids else None,
+                         b["tail_drop"] if tail_drop is None else tail_drop,
+                         capacity=capacity, status=st, n_tok=b["n_tok"])
+    return out, int(host(st)[0])
+
+
+def check_select(tp, b, tail_drop=None):
+    td = b["tail_drop"] if tail_drop is None else tail_drop
+    out, status = run_select(tp, b, td)
+    ref = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], td)
+    assert status == 0
+    counts = host(out["counts"])
+    assert counts.tolist() == [ref["M"], ref["N_resp"], ref["N_val"]]
+    M = ref["M"]
+    for k in ("resp_off", "sel_off", "keep_len"):
+        assert np.array_equal(host(out[k]), ref[k]), k
+    for k in ("sel_rows", "sel_targets", "sel_resp_idx"):
+        assert np.array_equal(host(out[k])[:M], ref[k]), k
+    return out, ref
+
+
+# ------------------------------------------------------------------ select
+@pytest.mark.parametrize("name", ["tiny", "small"])
+def test_select_configs(tp, name):
+    b = synth.make_batch(name, with_head=False)
+    check_select(tp, b)
+    check_select(tp, b, tail_drop=0)
+    check_select(tp, b, tail_drop=10 ** 6)
+
+
+def test_select_large_configs(tp):
+    for name in ("head7b", "head32b"):
+        check_select(tp, synth.make_batch(name, with_head=False))
+
+
+def test_select_many_sequences_offsets_only(tp):
+    b = synth.make_batch("longcot5x")                     # B = 2176 > one scan chunk
+    out, status = run_select(tp, b, with_ids=False)
+    ids = np.zeros(b["n_tok"], np.int32)
+    ref = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], ids, b["tail_drop"])
+    assert status == 0
+    for k in ("resp_off", "sel_off", "keep_len"):
+        assert np.array_equal(host(out[k]), ref[k]), k
+    assert host(out["counts"]).tolist() == [ref["M"], ref["N_resp"], ref["N_val"]]
+    assert np.array_equal(host(out["sel_rows"])[:ref["M"]], ref["sel_rows"])
+    assert np.array_equal(host(out["sel_resp_idx"])[:ref["M"]], ref["sel_resp_idx"])
+
+
+def test_select_edge_cases(tp):
+    import torch
+    # empty batch
+    z = torch.zeros(1, dtype=torch.int32, device="cuda")
+    e = torch.zeros(0, dtype=torch.int32, device="cuda")
+    out = tp.tppo_select(z, e, e, e, 0)
+    assert host(out["counts"]).tolist() == [0, 0, 0] and host(out["resp_off"]).tolist() == [0]
+    # windows of length 1 and sequences whose whole window is dropped
+    b = synth.make_batch("tiny", with_head=False, len_dist=("fixed_trunc", 1, 1), window=1)
+    check_select(tp, b, tail_drop=0)
+    check_select(tp, b, tail_drop=1)
+    # capacity smaller than M: excess not written, status says so
+    b = synth.make_batch("tiny", with_head=False)
+    ref = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    out, status = run_select(tp, b, capacity=10)
+    assert status == tp.STATUS_CAPACITY
+    assert np.array_equal(host(out["sel_rows"]), ref["sel_rows"][:10])
+    # bad layout (ctx_len = 0) is flagged and that sequence contributes nothing
+    b2 = synth.make_batch("tiny", with_head=False)
+    b2["ctx_len"] = b2["ctx_len"].copy()
+    b2["ctx_len"][1] = 0
+    out, status = run_select(tp, b2)
+    assert status & tp.STATUS_BAD_LAYOUT
+    assert host(out["keep_len"])[1] == 0
+
+
+# ------------------------------------------------------------------ log-probs
+def check_logprobs(tp, hidden, w, rows, targets, **kw):
+    st = tp.new_status("cuda")
+    logp, lse = tp.tppo_token_logprobs(dev(hidden), dev(w), dev(rows.astype(np.int32)),
+                                       dev(targets.astype(np.int32)), status=st, **kw)
+    ref_lp, ref_lse = ofast.token_logprobs(hidden, w, rows, targets)
+    assert int(host(st)[0]) == 0
+    got_lp, got_lse = host(logp), host(lse)
+    assert np.abs(got_lp - ref_lp).max() <= LOGP_ATOL, np.abs(got_lp - ref_lp).max()
+    assert np.abs(got_lse - ref_lse).max() <= LOGP_ATOL, np.abs(got_lse - ref_lse).max()
+    return np.abs(got_lp - ref_lp).max()
+
+
+def test_logprobs_tiny_fp32(tp):
+    b = synth.make_batch("tiny")
+    sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    err = check_logprobs(tp, b["hidden"], b["w_head"], sel["sel_rows"], sel["sel_targets"])
+    assert err < 1e-4          # fp32 inputs: far inside the bf16 tolerance
+
+
+def test_logprobs_generic_bf16_odd_shapes(tp):
+    rng = np.random.default_rng(0)
+    H, V, N = 72, 333, 40                                 # H not a multiple of 64 -> generic kernel
+    hidden = synth.f32_to_bf16_bits(rng.normal(size=(N, H)).astype(np.float32))
+    w = synth.f32_to_bf16_bits((0.1 * rng.normal(size=(V, H))).astype(np.float32))
+    rows = rng.integers(0, N, size=57)
+    check_logprobs(tp, hidden, w, rows, rng.integers(0, V, size=57))
+
+
+@pytest.mark.parametrize("M,V,H", [(1, 256, 64), (37, 1000, 128), (300, 1000, 256), (513, 2049, 192),
+                                   (256, 512, 64), (700, 5000, 1024)])
+def test_logprobs_mfma_ragged_shapes(tp, M, V, H):
+    rng = np.random.default_rng(M + V)
+    N = M + 5
+    hidden = synth.f32_to_bf16_bits(rng.normal(size=(N, H)).astype(np.float32))
+    w = synth.f32_to_bf16_bits((rng.normal(size=(V, H)) / np.sqrt(H)).astype(np.float32))
+    rows = rng.integers(0, N, size=M)
+    # targets sweep every residue of the accumulator layout, plus both ends
+    targets = (np.arange(M) * 7 + 3) % V
+    targets[0], targets[-1] = 0, V - 1
+    check_logprobs(tp, hidden, w, rows, targets)
+
+
+def test_logprobs_every_target_of_one_row_sums_to_one(tp):
+    rng = np.random.default_rng(5)
+    H, V = 128, 777
+    hidden = synth.f32_to_bf16_bits(rng.normal(size=(3, H)).astype(np.float32))
+    w = synth.f32_to_bf16_bits((rng.normal(size=(V, H)) / np.sqrt(H)).astype(np.float32))
+    rows = np.full(V, 1)
+    logp, lse = tp.tppo_token_logprobs(dev(hidden), dev(w), dev(rows.astype(np.int32)),
+                                       dev(np.arange(V, dtype=np.int32)))
+    lp = host(logp).astype(np.float64)
+    assert abs(np.exp(lp).sum() - 1.0) < 1e-4
+    ref, _ = ofast.token_logprobs(hidden, w, rows, np.arange(V))
+    assert np.abs(lp - ref).max() <= LOGP_ATOL
+
+
+def test_logprobs_small_config_slice(tp):
+    b = synth.make_batch("small", B=6)
+    sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    assert sel["M"] > 1024
+    check_logprobs(tp, b["hidden"], b["w_head"], sel["sel_rows"], sel["sel_targets"])
+
+
+def test_logprobs_scatter_count_and_status(tp):
+    import torch
+    b = synth.make_batch("small", B=3, V=1500, H=128)
+    sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    M, n_resp = sel["M"], sel["N_resp"]
+    ref, _ = ofast.token_logprobs(b["hidden"], b["w_head"], sel["sel_rows"], sel["sel_targets"])
+    # scatter into the response-packed domain, with M given as an upper bound
+    # and the true count read from device memory
+    cap = b["n_tok"]
+    rows = np.zeros(cap, np.int32); rows[:M] = sel["sel_rows"]
+    tg = np.zeros(cap, np.int32); tg[:M] = sel["sel_targets"]
+    oi = np.zeros(cap, np.int32); oi[:M] = sel["sel_resp_idx"]
+    m_dev = torch.tensor([M], dtype=torch.int64, device="cuda")
+    logp, _ = tp.tppo_token_logprobs(dev(b["hidden"]), dev(b["w_head"]), dev(rows), dev(tg), M=cap,
+                                     m_actual=m_dev, out_index=dev(oi), out_size=n_resp)
+    got = host(logp)[sel["sel_resp_idx"]]
+    assert np.abs(got - ref).max() <= LOGP_ATOL
+    # a bad target id yields NaN for that token only and sets the status bit
+    tg_bad = sel["sel_targets"].copy()
+    tg_bad[5] = 1500
+    st = tp.new_status("cuda")
+    logp, _ = tp.tppo_token_logprobs(dev(b["hidden"]), dev(b["w_head"]), dev(sel["sel_rows"]),
+                                     dev(tg_bad), status=st)
+    got = host(logp)
+    assert np.isnan(got[5]) and int(host(st)[0]) == tp.STATUS_BAD_TARGET
+    keep = np.arange(M) != 5
+    assert np.abs(got[keep] - ref[keep]).max() <= LOGP_ATOL
+
+
+def _sampled_rows(sel, n, seed):
+    rng = np.random.default_rng(seed)
+    M = sel["M"]
+    pick = set(rng.choice(M, size=min(n, M), replace=False).tolist())
+    so = sel["sel_off"]
+    for i in range(len(so) - 1):                          # first and last kept token of every sequence
+        if so[i + 1] > so[i]:
+            pick.add(int(so[i])); pick.add(int(so[i + 1] - 1))
+    return np.array(sorted(pick))
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["head7b", "head32b"])
+def test_logprobs_full_size_sampled(tp, name):
+    """Full-size shapes in the launch configuration the benchmark times; the
+    oracle checks a seeded sample of outputs (plus each sequence's first and
+    last kept token) one by one."""
+    import torch
+    b = synth.make_batch(name)
+    if b["cfg"].get("ids_from_policy"):
+        synth.sample_ids_from_policy(b, device="cuda")
+    sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    hidden, w = dev(b["hidden"]), dev(b["w_head"])
+    rows, tg = dev(sel["sel_rows"]), dev(sel["sel_targets"])
+    st = tp.new_status("cuda")
+    logp, lse = tp.tppo_token_logprobs(hidden, w, rows, tg, status=st)
+    logp2, _ = tp.tppo_token_logprobs(hidden, w, rows, tg)
+    torch.cuda.synchronize()
+    assert int(host(st)[0]) == 0
+    got, got_lse = host(logp), host(lse)
+    assert np.array_equal(got, host(logp2))               # deterministic
+    assert np.isfinite(got).all() and (got <= 0).all()
+    pick = _sampled_rows(sel, 96, seed=1)
+    ref, ref_lse = ofast.token_logprobs(b["hidden"], b["w_head"], sel["sel_rows"][pick],
+                                        sel["sel_targets"][pick])
+    assert np.abs(got[pick] - ref).max() <= LOGP_ATOL, np.abs(got[pick] - ref).max()
+    assert np.abs(got_lse[pick] - ref_lse).max() <= LOGP_ATOL
+
+
+# ------------------------------------------------------------------ EGAE
+def check_egae(tp, rewards, values, resp_off, done, gamma, lam, bootstrap=None):
+    st = tp.new_status("cuda")
+    adv, ret = tp.tppo_egae(dev(rewards), dev(values), dev(resp_off.astype(np.int32)),
+                            dev(done.astype(np.int32)), gamma, lam,
+                            bootstrap=dev(bootstrap), status=st)
+    # the ABI takes gamma and lambda as fp32: the oracle gets the same rounded values
+    ref_a, ref_r = ofast.egae(rewards, values, resp_off, done, float(np.float32(gamma)),
+                              float(np.float32(lam)), bootstrap)
+    assert int(host(st)[0]) == 0
+    assert_egae_close(host(adv), ref_a, "adv")
+    assert_egae_close(host(ret), ref_r, "ret")
+    return host(adv), host(ret)
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("name", ["tiny", "small", "longcot"])
+@pytest.mark.parametrize("lam", [0.0, 0.95, 1.0])
+def test_egae_configs(tp, name, lam):
+    b = synth.make_batch(name, with_head=False)
+    check_egae(tp, b["rewards"], b["values"], b["resp_off"], b["done"], b["gamma"], lam)
+
+
+def test_egae_bootstrap_and_discount(tp):
+    b = synth.make_batch("longcot", with_head=False, B=64)
+    check_egae(tp, b["rewards"], b["values"], b["resp_off"], b["done"], 1.0, 0.95, b["bootstrap"])
+    check_egae(tp, b["rewards"], b["values"], b["resp_off"], b["done"], 0.999, 0.9, b["bootstrap"])
+    dense = np.random.default_rng(3).normal(size=b["n_resp"]).astype(np.float32) * 0.01
+    check_egae(tp, dense, b["values"], b["resp_off"], b["done"], 0.9995, 1.0)
+
+
+def test_egae_exact_zero_cases(tp):
+    b = synth.make_batch("small", with_head=False)
+    n = b["n_resp"]
+    trunc = np.zeros_like(b["done"])
+    adv, ret = check_egae(tp, np.zeros(n, np.float32), np.full(n, 0.37, np.float32), b["resp_off"],
+                          trunc, 1.0, 0.95)
+    assert np.all(adv == 0.0) and np.all(ret == 0.0)
+    adv, _ = check_egae(tp, np.zeros(n, np.float32), b["values"], b["resp_off"], trunc, 1.0, 0.95)
+    assert np.all(adv[b["resp_off"][1:] - 1] == 0.0)     # last token of a truncated sequence
+
+
+def test_egae_ragged_segment_shapes(tp):
+    rng = np.random.default_rng(12)
+    # length-1 sequences, empty sequences, many short ones inside one tile, one
+    # sequence spanning many tiles, a total that is not a multiple of the vector width
+    lens = np.concatenate([[1, 1, 0, 3, 0, 0, 2], rng.integers(1, 9, size=700), [30011], [1],
+                           rng.integers(1, 5000, size=9), [0, 7]])
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    n = int(off[-1])
+    done = rng.integers(0, 2, size=lens.size).astype(np.int32)
+    r = rng.normal(size=n).astype(np.float32)
+    v = rng.uniform(-1, 1, size=n).astype(np.float32)
+    boot = rng.uniform(-1, 1, size=lens.size).astype(np.float32)
+    for g, l in ((1.0, 0.95), (1.0, 1.0), (0.99, 0.5), (0.0, 0.7), (1.0, 0.0)):
+        check_egae(tp, r, v, off, done, g, l)
+        check_egae(tp, r, v, off, done, g, l, boot)
+
+
+def test_egae_unaligned_pointers(tp):
+    import torch
+    b = synth.make_batch("small", with_head=False)
+    n = b["n_resp"]
+    pad = lambda a: torch.cat([torch.zeros(1, device="cuda"), dev(a)])[1:]    # 4-byte aligned only
+    r, v = pad(b["rewards"]), pad(b["values"])
+    assert r.data_ptr() % 16 != 0
+    adv, ret = tp.tppo_egae(r, v, dev(b["resp_off"]), dev(b["done"]), 1.0, 0.95)
+    ref_a, ref_r = ofast.egae(b["rewards"], b["values"], b["resp_off"], b["done"], 1.0,
+                              float(np.float32(0.95)))
+    assert_egae_close(host(adv), ref_a, "adv")
+    assert_egae_close(host(ret), ref_r, "ret")
+    assert n == adv.numel()
+
+
+def test_egae_empty(tp):
+    import torch
+    e = torch.zeros(0, device="cuda")
+    z = torch.zeros(1, dtype=torch.int32, device="cuda")
+    adv, ret = tp.tppo_egae(e, e, z, torch.zeros(0, dtype=torch.int32, device="cuda"), 1.0, 0.95)
+    assert adv.numel() == 0 and ret.numel() == 0
+
+
+# ------------------------------------------------------------------ losses
+def loss_inputs(b, rng=None):
+    adv, ret = ofast.egae(b["rewards"], b["values"], b["resp_off"], b["done"], b["gamma"], b["lam"])
+    keep = np.where(b["done"] != 0, b["win_len"], np.maximum(b["win_len"] - b["tail_drop"], 0)).astype(np.int32)
+    arrs = dict(logp_new=b["logp_new_synth"], logp_old=(b["logp_new_synth"] + b["logp_gap"]).astype(np.float32),
+                adv=adv.astype(np.float32), v_new=b["v_new"], v_old=b["values"], ret=ret.astype(np.float32))
+    return arrs, keep
+
+
+def run_losses(tp, a, b, keep, eps=None, skip=None):
+    eps = eps or (b["eps_low"], b["eps_high"])
+    d = {k: dev(v) for k, v in a.items()}
+    if skip == "policy":
+        d["logp_new"] = d["logp_old"] = d["adv"] = None
+    if skip == "value":
+        d["v_new"] = d["v_old"] = d["ret"] = None
+    res = tp.tppo_ppo_losses(d["logp_new"], d["logp_old"], d["adv"], d["v_new"], d["v_old"], d["ret"],
+                             dev(b["resp_off"]), dev(keep), dev(b["done"]), eps[0], eps[1],
+                             b["xi_low"], b["xi_high"])
+    return tp.read_loss_out(res)
+
+
+def assert_loss_close(got, ref):
+    for k in ("policy_loss", "value_loss", "policy_sum", "value_sum"):
+        assert abs(got[k] - ref[k]) <= LOSS_RTOL * abs(ref[k]) + 1e-12, (k, got[k], ref[k])
+    assert got["n_policy"] == ref["n_policy"] and got["n_value"] == ref["n_value"]
+
+
+@pytest.mark.parametrize("name", ["tiny", "small", "longcot"])
+def test_losses_configs(tp, name):
+    b = synth.make_batch(name, with_head=False)
+    a, keep = loss_inputs(b)
+    ref = ofast.ppo_losses(a["logp_new"], a["logp_old"], a["adv"], a["v_new"], a["v_old"], a["ret"],
+                           b["resp_off"], keep, b["done"], b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"])
+    got = run_losses(tp, a, b, keep)
+    assert_loss_close(got, ref)
+    assert got == run_losses(tp, a, b, keep)              # deterministic reduction
+    if name == "tiny":                                    # the literal "clip 0.2" and the paper's 0.2/0.28
+        ref2 = ofast.ppo_losses(a["logp_new"], a["logp_old"], a["adv"], a["v_new"], a["v_old"], a["ret"],
+                                b["resp_off"], keep, b["done"], 0.2, 0.28, b["xi_low"], b["xi_high"])
+        assert_loss_close(run_losses(tp, a, b, keep, eps=(0.2, 0.28)), ref2)
+
+
+def test_losses_masked_entries_contribute_exactly_zero(tp):
+    b = synth.make_batch("small", with_head=False)
+    a, keep = loss_inputs(b)
+    clean = run_losses(tp, a, b, keep)
+    pol, val = ofast.loss_masks(b["resp_off"], keep, b["done"])
+    p = {k: v.copy() for k, v in a.items()}
+    for k in ("logp_new", "logp_old", "adv"):
+        p[k][~pol] = np.nan
+    for k in ("v_new", "v_old", "ret"):
+        p[k][~val] = np.inf
+    assert run_losses(tp, p, b, keep) == clean            # bit-identical
+
+
+def test_losses_halves_and_empty_sets(tp):
+    b = synth.make_batch("small", with_head=False)
+    a, keep = loss_inputs(b)
+    full = run_losses(tp, a, b, keep)
+    only_v = run_losses(tp, a, b, keep, skip="policy")
+    only_p = run_losses(tp, a, b, keep, skip="value")
+    assert only_v["value_loss"] == full["value_loss"] and only_v["policy_loss"] == 0.0 and only_v["n_policy"] == 0
+    assert only_p["policy_loss"] == full["policy_loss"] and only_p["value_loss"] == 0.0 and only_p["n_value"] == 0
+    # nothing kept and nothing finished
+    none_done = dict(b, done=np.zeros_like(b["done"]))
+    got = run_losses(tp, a, none_done, np.zeros_like(keep))
+    assert got["policy_loss"] == 0.0 and got["value_loss"] == 0.0 and got["n_policy"] == 0 and got["n_value"] == 0
+
+
+def test_losses_split_batch_additivity(tp):
+    b = synth.make_batch("small", with_head=False)
+    a, keep = loss_inputs(b)
+    full = run_losses(tp, a, b, keep)
+    k = 13
+    cut = int(b["resp_off"][k])
+    first = dict(b, resp_off=b["resp_off"][:k + 1], done=b["done"][:k])
+    second = dict(b, resp_off=(b["resp_off"][k:] - cut).astype(np.int32), done=b["done"][k:])
+    g1 = run_losses(tp, {n: v[:cut] for n, v in a.items()}, first, keep[:k])
+    g2 = run_losses(tp, {n: v[cut:] for n, v in a.items()}, second, keep[k:])
+    assert abs(g1["policy_sum"] + g2["policy_sum"] - full["policy_sum"]) <= 1e-4 * abs(full["policy_sum"])
+    assert abs(g1["value_sum"] + g2["value_sum"] - full["value_sum"]) <= 1e-4 * abs(full["value_sum"])
+    assert g1["n_policy"] + g2["n_policy"] == full["n_policy"]
+    assert g1["n_value"] + g2["n_value"] == full["n_value"]
+
+
+# ------------------------------------------------------------------ whole path
+def test_whole_path_tiny(tp):
+    """select -> log-probs -> EGAE -> losses chained on device buffers, against
+    the same chain in the oracle (config 1, both clip settings)."""
+    import torch
+    b = synth.make_batch("tiny")
+    sel = tp.tppo_select(dev(b["cu_seqlens"]), dev(b["ctx_len"]), dev(b["done"]), dev(b["input_ids"]),
+                         b["tail_drop"])
+    n_resp = b["n_resp"]
+    logp, _ = tp.tppo_token_logprobs(dev(b["hidden"]), dev(b["w_head"]), sel["sel_rows"],
+                                     sel["sel_targets"], M=b["n_tok"], m_actual=sel["counts"],
+                                     out_index=sel["sel_resp_idx"], out_size=n_resp)
+    adv, ret = tp.tppo_egae(dev(b["rewards"]), dev(b["values"]), sel["resp_off"], dev(b["done"]),
+                            b["gamma"], b["lam"])
+    # oracle chain
+    osel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    olp, _ = ofast.token_logprobs(b["hidden"], b["w_head"], osel["sel_rows"], osel["sel_targets"])
+    o_new = np.zeros(n_resp); o_new[osel["sel_resp_idx"]] = olp
+    o_old = o_new + b["logp_gap"]
+    oadv, oret = ofast.egae(b["rewards"], b["values"], osel["resp_off"], b["done"], b["gamma"], b["lam"])
+    logp_old = dev(o_old.astype(np.float32))
+    for eps in ((0.2, 0.2), (0.2, 0.28)):
+        res = tp.tppo_ppo_losses(logp, logp_old, adv, dev(b["v_new"]), dev(b["values"]), ret,
+                                 sel["resp_off"], sel["keep_len"], dev(b["done"]), eps[0], eps[1],
+                                 b["xi_low"], b["xi_high"])
+        got = tp.read_loss_out(res)
+        ref = ofast.ppo_losses(o_new, o_old.astype(np.float32), oadv, b["v_new"], b["values"], oret,
+                               osel["resp_off"], osel["keep_len"], b["done"], eps[0], eps[1],
+                               b["xi_low"], b["xi_high"])
+        assert_loss_close(got, ref)
+    torch.cuda.synchronize()
