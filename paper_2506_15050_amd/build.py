@@ -14,7 +14,7 @@ LIB = os.path.join(HERE, "libtppo.so")
 SOURCES = ["select.hip", "egae.hip", "losses.hip", "head.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function"]
+         "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 
 
 def build(verbose=False, extra=()):

@@ -18,6 +18,8 @@
 // layout the MFMA wants for both, so tiles are staged into LDS as 16-byte
 // chunks with an XOR swizzle of the chunk index (conflict-free ds_read_b128)
 // and read back as operand fragments directly.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace tppo {
@@ -97,11 +99,9 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int kTileV = 256;            // vocabulary rows per workgroup tile
 constexpr int kTileT = 256;            // tokens per workgroup tile
-constexpr int kBK = 64;                // K elements per LDS stage
-constexpr int kRowBytes = kBK * 2;     // 128 B per staged row
-constexpr int kStageBytes = (kTileV + kTileT) * kRowBytes;   // 64 KiB
-constexpr int kStages = 2;
-constexpr int kHeadLds = kStages * kStageBytes;              // 128 KiB of the 160 KiB LDS
+constexpr int kTileRows = kTileV + kTileT;
+constexpr int kHeadThreads = 512;      // 8 wavefronts: 2 (vocabulary) x 4 (tokens)
+constexpr int kWavesV = 2, kWavesT = 4;
 constexpr int kMaxSplits = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -118,10 +118,38 @@ struct HeadParams {
     int H, V, row_tiles, splits, vocab_tiles;
 };
 
-// byte offset of 16-byte chunk `c` (0..7) of staged row `r`
-__device__ __forceinline__ int lds_chunk_off(int r, int c) {
-    return r * kRowBytes + ((c ^ (r & 7)) << 4);
+// LDS staging layout.  A stage holds kTileRows rows of kBK bf16 (W rows first,
+// then token rows), each row as kBK/8 chunks of 16 bytes.  Chunk c of row r
+// sits in slot c ^ swz(r), so the 8 lanes that read the same chunk of 8
+// consecutive rows with one ds_read_b128 hit 8 different 16-byte bank groups.
+template <int kBK>
+struct StageLayout {
+    static constexpr int kRowBytes = kBK * 2;
+    static constexpr int kChunks = kBK / 8;
+    static constexpr int kStageBytes = kTileRows * kRowBytes;
+    static constexpr int kRowsPerDma = 1024 / kRowBytes;      // one wave-wide 16 B/lane transfer
+    __device__ static __forceinline__ int swz(int r) {
+        return kBK == 64 ? (r & 7) : ((r >> 1) & 3);
+    }
+    __device__ static __forceinline__ int chunk_off(int r, int c) {
+        return r * kRowBytes + ((c ^ swz(r)) << 4);
+    }
+};
+
+// One wave-wide global -> LDS transfer without a register round trip: lane l's
+// 16 bytes at `src` land at LDS byte address lds_base + 16*l (lds_base is
+// wave-uniform and goes through M0).  Written as inline assembly so that the
+// transfer stays asynchronous: completion is awaited by hand (vmcnt) right
+// before the workgroup barrier that publishes the stage.
+__device__ __forceinline__ void dma_16b_per_lane(const void* src, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_base), "v"(src)
+                 : "memory", "m0");
 }
+
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding)
+constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
 
 // Workgroup id -> (token tile, vocabulary split).  Consecutive hardware ids go
 // round-robin over the 8 XCDs, so ids are first regrouped into 8 contiguous
@@ -139,14 +167,15 @@ __device__ __forceinline__ void decode_block(int bid, int grid, int row_tiles, i
     rt = group * 8 + (in_group - sp * rows_here);
 }
 
-template <int kWavesV, int kWavesT>
-__global__ __launch_bounds__(kWavesV* kWavesT * 64) void head_mfma_kernel(HeadParams p) {
-    constexpr int kThreads = kWavesV * kWavesT * 64;
-    constexpr int kWaveV = kTileV / kWavesV, kWaveT = kTileT / kWavesT;   // wave tile
+template <int kBK, int kStages>
+__global__ __launch_bounds__(kHeadThreads) void head_mfma_kernel(HeadParams p) {
+    using L = StageLayout<kBK>;
+    constexpr int kWaveV = kTileV / kWavesV, kWaveT = kTileT / kWavesT;   // 128 x 64 wave tile
     constexpr int kVB = kWaveV / 32, kTB = kWaveT / 32;                   // 32x32 blocks per wave
-    constexpr int kRowsPerPass = kThreads / 8;                            // 8 chunks per row
-    constexpr int kPasses = kTileV / kRowsPerPass;
-    static_assert(kTileV == kTileT, "loader assumes square tiles");
+    constexpr int kDmaPerWave = kTileRows / L::kRowsPerDma / (kHeadThreads / 64);
+    constexpr int kRowsPerWave = kDmaPerWave * L::kRowsPerDma;            // 64: waves 0-3 load W, 4-7 tokens
+    constexpr int kKSteps = kBK / 16;
+    static_assert(kRowsPerWave * 4 == kTileV && kTileV == kTileT, "loader split assumes 4+4 waves");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     int rt, sp;
@@ -155,24 +184,59 @@ __global__ __launch_bounds__(kWavesV* kWavesT * 64) void head_mfma_kernel(HeadPa
     const int64_t tok0 = (int64_t)rt * kTileT;
     if (tok0 >= m_eff) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wv = wave / kWavesT, wt = wave % kWavesT;
     const int vt_begin = (int)((int64_t)p.vocab_tiles * sp / p.splits);
     const int vt_end = (int)((int64_t)p.vocab_tiles * (sp + 1) / p.splits);
     const int k_tiles = p.H / kBK;
     const int total_iters = (vt_end - vt_begin) * k_tiles;
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-    // ---- loader role: chunk c of rows r0 + pass*kRowsPerPass
-    const int ld_c = tid & 7, ld_r0 = tid >> 3;
-    const uint16_t* b_ptr[kPasses];                    // gathered hidden rows (fixed for the sweep)
+    // ---- loader role: kDmaPerWave transfers of kRowsPerDma rows each
+    const bool loads_w = wave < 4;
+    const int ld_row = (wave & 3) * kRowsPerWave + lane / L::kChunks;     // + q * kRowsPerDma
+    const int ld_slot = lane % L::kChunks;
+    const uint16_t* src[kDmaPerWave];
+    int src_chunk[kDmaPerWave];
+    int issue_vt = vt_begin, issue_kt = 0;
+    auto point_at_tile = [&](int vt) {
 #pragma unroll
-    for (int q = 0; q < kPasses; ++q) {
-        int64_t t = tok0 + ld_r0 + q * kRowsPerPass;
-        t = min(t, m_eff - 1);
-        int64_t row = p.sel_rows[t];
-        row = min(max(row, (int64_t)0), p.n_rows - 1);
-        b_ptr[q] = p.hidden + row * p.ld_h + ld_c * 8;
-    }
+        for (int q = 0; q < kDmaPerWave; ++q) {
+            const int r = ld_row + q * L::kRowsPerDma;
+            src_chunk[q] = (ld_slot ^ L::swz(r)) * 8;
+            if (loads_w) {
+                const int64_t v = min((int64_t)vt * kTileV + r, (int64_t)p.V - 1);
+                src[q] = p.w + v * p.ld_w + src_chunk[q];
+            } else {
+                const int64_t t = min(tok0 + r, m_eff - 1);
+                int64_t row = p.sel_rows[t];
+                row = min(max(row, (int64_t)0), p.n_rows - 1);
+                src[q] = p.hidden + row * p.ld_h + src_chunk[q];
+            }
+        }
+    };
+    point_at_tile(vt_begin);
+    auto issue = [&]() {                // next (vocabulary tile, k tile) in sweep order
+        const int stage = (issue_vt - vt_begin) * k_tiles + issue_kt;
+        const unsigned dst = lds_base + (stage % kStages) * L::kStageBytes +
+                             ((loads_w ? 0 : kTileV) + (wave & 3) * kRowsPerWave) * L::kRowBytes;
+#pragma unroll
+        for (int q = 0; q < kDmaPerWave; ++q) {
+            dma_16b_per_lane(src[q], dst + q * 1024);
+            src[q] += kBK;
+        }
+        if (++issue_kt == k_tiles) {
+            issue_kt = 0;
+            ++issue_vt;
+            if (loads_w) {
+                point_at_tile(min(issue_vt, vt_end - 1));
+            } else {
+#pragma unroll
+                for (int q = 0; q < kDmaPerWave; ++q) src[q] -= p.H;
+            }
+        }
+    };
 
     // ---- per-lane softmax state for my kTB token columns
     float run_max[kTB], run_sum[kTB], tgt_logit[kTB];
@@ -194,62 +258,49 @@ __global__ __launch_bounds__(kWavesV* kWavesT * 64) void head_mfma_kernel(HeadPa
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
 
-    uint4 stage_a[kPasses], stage_b[kPasses];
-    auto load_global = [&](int it) {
-        const int vt = vt_begin + it / k_tiles, kt = it - (it / k_tiles) * k_tiles;
-        const int64_t k_off = (int64_t)kt * kBK;
+    // ---- fill the ring
 #pragma unroll
-        for (int q = 0; q < kPasses; ++q) {
-            int64_t v = (int64_t)vt * kTileV + ld_r0 + q * kRowsPerPass;
-            v = min(v, (int64_t)p.V - 1);
-            stage_a[q] = *reinterpret_cast<const uint4*>(p.w + v * p.ld_w + k_off + ld_c * 8);
-            stage_b[q] = *reinterpret_cast<const uint4*>(b_ptr[q] + k_off);
-        }
-    };
-    auto store_lds = [&](int buf) {
-        unsigned char* base = smem + buf * kStageBytes;
-#pragma unroll
-        for (int q = 0; q < kPasses; ++q) {
-            const int r = ld_r0 + q * kRowsPerPass;
-            *reinterpret_cast<uint4*>(base + lds_chunk_off(r, ld_c)) = stage_a[q];
-            *reinterpret_cast<uint4*>(base + kTileV * kRowBytes + lds_chunk_off(r, ld_c)) = stage_b[q];
-        }
-    };
-
-    if (total_iters > 0) {
-        load_global(0);
-        store_lds(0);
-    }
-    __syncthreads();
+    for (int s = 0; s < kStages - 1; ++s)
+        if (s < total_iters) issue();
 
     const int frag_row = lane & 31, frag_half = lane >> 5;
+    int kt = 0, vt = vt_begin;
     for (int it = 0; it < total_iters; ++it) {
-        const int buf = it & 1;
-        if (it + 1 < total_iters) load_global(it + 1);
+        // my transfers for stage `it` are done when at most the younger ones are in flight
+        if (total_iters - it >= kStages - 1)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kDmaPerWave));
+        else
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __syncthreads();                // everyone's transfers landed; everyone left stage it-1
+        if (it + kStages - 1 < total_iters) issue();
 
-        const unsigned char* a_base = smem + buf * kStageBytes + (wv * kWaveV) * kRowBytes;
-        const unsigned char* b_base = smem + buf * kStageBytes + kTileV * kRowBytes + (wt * kWaveT) * kRowBytes;
-#pragma unroll
-        for (int ks = 0; ks < kBK / 16; ++ks) {
+        const unsigned char* st = smem + (it % kStages) * L::kStageBytes;
+        const unsigned char* a_base = st + (wv * kWaveV) * L::kRowBytes;
+        const unsigned char* b_base = st + (kTileV + wt * kWaveT) * L::kRowBytes;
+        bf16x8 fa[2][kVB], fb[2][kTB];
+        auto load_frags = [&](int ks, int buf) {
             const int c = ks * 2 + frag_half;
-            bf16x8 fa[kVB], fb[kTB];
 #pragma unroll
             for (int vb = 0; vb < kVB; ++vb)
-                fa[vb] = *reinterpret_cast<const bf16x8*>(a_base + lds_chunk_off(vb * 32 + frag_row, c));
+                fa[buf][vb] = *reinterpret_cast<const bf16x8*>(a_base + L::chunk_off(vb * 32 + frag_row, c));
 #pragma unroll
             for (int tb = 0; tb < kTB; ++tb)
-                fb[tb] = *reinterpret_cast<const bf16x8*>(b_base + lds_chunk_off(tb * 32 + frag_row, c));
+                fb[buf][tb] = *reinterpret_cast<const bf16x8*>(b_base + L::chunk_off(tb * 32 + frag_row, c));
+        };
+        load_frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks) {
+            if (ks + 1 < kKSteps) load_frags(ks + 1, (ks + 1) & 1);
 #pragma unroll
             for (int vb = 0; vb < kVB; ++vb)
 #pragma unroll
                 for (int tb = 0; tb < kTB; ++tb)
-                    acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[vb], fb[tb], acc[vb][tb], 0, 0, 0);
+                    acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][vb], fb[ks & 1][tb],
+                                                                          acc[vb][tb], 0, 0, 0);
         }
 
-        const int kt = it % k_tiles;
-        if (kt == k_tiles - 1) {
+        if (++kt == k_tiles) {
             // ---- a vocabulary tile is complete: fold it into the running softmax
-            const int vt = vt_begin + it / k_tiles;
             const int v_wave = vt * kTileV + wv * kWaveV;          // first vocabulary id of my wave tile
             const int v_lane = v_wave + frag_half * 4;              // + vb*32 + (e/4)*8 + e%4
             if (vt * kTileV + kTileV > p.V) {                       // ragged last tile: mask ids >= V
@@ -315,11 +366,11 @@ __global__ __launch_bounds__(kWavesV* kWavesT * 64) void head_mfma_kernel(HeadPa
                 for (int tb = 0; tb < kTB; ++tb)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
+            kt = 0;
+            ++vt;
         }
-
-        if (it + 1 < total_iters) store_lds(buf ^ 1);
-        __syncthreads();
     }
+    __syncthreads();                    // all fragment reads done before the stages are reused
 
     // ---- merge the two lane halves (same token, different vocabulary rows),
     // then the kWavesV waves that share a token, and write the split's triple
@@ -332,7 +383,7 @@ __global__ __launch_bounds__(kWavesV* kWavesT * 64) void head_mfma_kernel(HeadPa
         run_max[tb] = nm;
         tgt_logit[tb] += ot;
     }
-    float* s_merge = reinterpret_cast<float*>(smem);   // [kWavesV][3][kTileT]; stages are idle now
+    float* s_merge = reinterpret_cast<float*>(smem);   // [kWavesV][3][kTileT]
     if (lane < 32) {
 #pragma unroll
         for (int tb = 0; tb < kTB; ++tb) {
@@ -343,7 +394,7 @@ __global__ __launch_bounds__(kWavesV* kWavesT * 64) void head_mfma_kernel(HeadPa
         }
     }
     __syncthreads();
-    for (int col = tid; col < kTileT; col += kThreads) {
+    for (int col = tid; col < kTileT; col += kHeadThreads) {
         const int64_t t = tok0 + col;
         if (t >= m_eff) continue;
         float gm = kNegBig, gs = 0.f, gt = 0.f;
@@ -413,7 +464,7 @@ static int choose_splits(int64_t M, int64_t V) {
 
 static bool mfma_eligible(const void* hidden, int64_t H, int64_t ld_h, const void* w, int64_t ld_w,
                           tppo_dtype dt) {
-    return dt == TPPO_BF16 && H >= kBK && H % kBK == 0 && ld_h % 8 == 0 && ld_w % 8 == 0 &&
+    return dt == TPPO_BF16 && H >= 64 && H % 64 == 0 && ld_h % 8 == 0 && ld_w % 8 == 0 &&
            is_aligned(hidden, 16) && is_aligned(w, 16);
 }
 
@@ -475,16 +526,16 @@ extern "C" int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H
     p.vocab_tiles = (int)((V + kTileV - 1) / kTileV);
     p.splits = choose_splits(M, V);
 
-    auto kernel = head_mfma_kernel<2, 4>;
-    static bool attr_set = false;   // raising the dynamic-LDS limit is idempotent; races are benign
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kHeadLds) != hipSuccess)
-            return TPPO_ERR_LAUNCH;
-        attr_set = true;
-    }
+    // two staging shapes: 4 stages of 32 K-elements (default) or 2 stages of 64
+    const char* variant = getenv("TPPO_HEAD_VARIANT");
+    const bool wide = variant && variant[0] == '1';
+    auto kernel = wide ? head_mfma_kernel<64, 2> : head_mfma_kernel<32, 4>;
+    const int lds_bytes = wide ? 2 * StageLayout<64>::kStageBytes : 4 * StageLayout<32>::kStageBytes;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+        return TPPO_ERR_LAUNCH;
     const int grid = p.row_tiles * p.splits;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(512), kHeadLds, s, p);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kHeadThreads), lds_bytes, s, p);
     if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
     hipLaunchKernelGGL(head_combine_kernel, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, s, p.part,
                        p.splits, M, m_actual, sel_rows, sel_targets, n_rows, (int)V, out_index, logp,
