@@ -97,11 +97,6 @@ __global__ __launch_bounds__(kGenThreads) void head_generic_kernel(
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int kTileV = 256;            // vocabulary rows per workgroup tile
-constexpr int kTileT = 256;            // tokens per workgroup tile
-constexpr int kTileRows = kTileV + kTileT;
-constexpr int kHeadThreads = 512;      // 8 wavefronts: 2 (vocabulary) x 4 (tokens)
-constexpr int kWavesV = 2, kWavesT = 4;
 constexpr int kMaxSplits = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -118,18 +113,37 @@ struct HeadParams {
     int H, V, row_tiles, splits, vocab_tiles;
 };
 
-// LDS staging layout.  A stage holds kTileRows rows of kBK bf16 (W rows first,
-// then token rows), each row as kBK/8 chunks of 16 bytes.  Chunk c of row r
-// sits in slot c ^ swz(r), so the 8 lanes that read the same chunk of 8
-// consecutive rows with one ds_read_b128 hit 8 different 16-byte bank groups.
-template <int kBK>
-struct StageLayout {
-    static constexpr int kRowBytes = kBK * 2;
-    static constexpr int kChunks = kBK / 8;
-    static constexpr int kStageBytes = kTileRows * kRowBytes;
-    static constexpr int kRowsPerDma = 1024 / kRowBytes;      // one wave-wide 16 B/lane transfer
+// Compile-time shape of one kernel variant: a kTileV x kTileT (vocabulary x
+// tokens) output tile per workgroup, kWavesV x kWavesT wavefronts, kBK
+// K-elements per LDS stage, a ring of kStages stages.
+//
+// LDS staging layout.  A stage holds kTileV + kTileT rows of kBK bf16 (W rows
+// first, then token rows), each row as kBK/8 chunks of 16 bytes.  Chunk c of
+// row r sits in slot c ^ swz(r).  The LDS serves 64 banks x 4 B = 256 B per
+// cycle, i.e. 16 lanes of a ds_read_b128; those 16 lanes read the same chunk
+// of 16 consecutive rows, and the swizzle spreads them over all 16 slots of
+// the 256-byte bank window (measured: SQ_LDS_BANK_CONFLICT = 0).
+template <int TV, int TT, int WV, int WT, int BK, int ST, int WGS_PER_CU>
+struct HeadCfg {
+    static constexpr int kTileV = TV, kTileT = TT, kWavesV = WV, kWavesT = WT, kBK = BK, kStages = ST;
+    static constexpr int kWgsPerCu = WGS_PER_CU;
+    static constexpr int kWaves = WV * WT, kThreads = kWaves * 64;
+    static constexpr int kWaveV = TV / WV, kWaveT = TT / WT;              // wave tile
+    static constexpr int kVB = kWaveV / 32, kTB = kWaveT / 32;            // 32x32 blocks per wave
+    static constexpr int kRowBytes = BK * 2, kChunks = BK / 8;
+    static constexpr int kRows = TV + TT;
+    static constexpr int kStageBytes = kRows * kRowBytes;
+    static constexpr int kLdsBytes = ST * kStageBytes;
+    static constexpr int kRowsPerDma = 1024 / kRowBytes;                  // one wave-wide 16 B/lane transfer
+    static constexpr int kDmaPerStage = kRows / kRowsPerDma;
+    static constexpr int kDmaPerWave = kDmaPerStage / kWaves;
+    static constexpr int kKSteps = BK / 16;
+    static_assert(kDmaPerWave * kWaves == kDmaPerStage, "transfers must divide evenly over the waves");
+    static_assert(TV % kRowsPerDma == 0, "a transfer may not straddle W and token rows");
+    static_assert(kKSteps % 2 == 0, "fragment double buffering assumes an even number of K steps");
+    static_assert(WV * 3 * TT * 4 <= kLdsBytes, "merge buffer must fit in the idle stages");
     __device__ static __forceinline__ int swz(int r) {
-        return kBK == 64 ? (r & 7) : ((r >> 1) & 3);
+        return BK == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3);
     }
     __device__ static __forceinline__ int chunk_off(int r, int c) {
         return r * kRowBytes + ((c ^ swz(r)) << 4);
@@ -154,8 +168,8 @@ constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4
 // Workgroup id -> (token tile, vocabulary split).  Consecutive hardware ids go
 // round-robin over the 8 XCDs, so ids are first regrouped into 8 contiguous
 // ranges (one per XCD, each with its own L2); inside a range, 8 token tiles x
-// all splits are adjacent, so the ~32 workgroups resident on an XCD share
-// their W tiles (same split, different token tile) and hidden tiles.
+// all splits are adjacent, so the workgroups resident on an XCD share their W
+// tiles (same split, different token tile) and hidden tiles.
 __device__ __forceinline__ void decode_block(int bid, int grid, int row_tiles, int splits, int& rt,
                                              int& sp) {
     const int per_xcd = grid / 8;
@@ -167,15 +181,144 @@ __device__ __forceinline__ void decode_block(int bid, int grid, int row_tiles, i
     rt = group * 8 + (in_group - sp * rows_here);
 }
 
-template <int kBK, int kStages>
-__global__ __launch_bounds__(kHeadThreads) void head_mfma_kernel(HeadParams p) {
-    using L = StageLayout<kBK>;
-    constexpr int kWaveV = kTileV / kWavesV, kWaveT = kTileT / kWavesT;   // 128 x 64 wave tile
-    constexpr int kVB = kWaveV / 32, kTB = kWaveT / 32;                   // 32x32 blocks per wave
-    constexpr int kDmaPerWave = kTileRows / L::kRowsPerDma / (kHeadThreads / 64);
-    constexpr int kRowsPerWave = kDmaPerWave * L::kRowsPerDma;            // 64: waves 0-3 load W, 4-7 tokens
-    constexpr int kKSteps = kBK / 16;
-    static_assert(kRowsPerWave * 4 == kTileV && kTileV == kTileT, "loader split assumes 4+4 waves");
+// Per-lane running log-softmax state of the kTB token columns a lane owns, and
+// the two steps that use it: folding a finished 256-wide vocabulary tile, and
+// the final merge across lane halves / waves.
+template <class C>
+struct LaneSoftmax {
+    float run_max[C::kTB], run_sum[C::kTB], tgt_logit[C::kTB];
+    int tgt[C::kTB];
+
+    __device__ __forceinline__ void init(const HeadParams& p, int64_t tok0, int64_t m_eff, int wt, int lane) {
+#pragma unroll
+        for (int tb = 0; tb < C::kTB; ++tb) {
+            run_max[tb] = kNegBig;
+            run_sum[tb] = 0.f;
+            tgt_logit[tb] = 0.f;
+            const int64_t t = tok0 + wt * C::kWaveT + tb * 32 + (lane & 31);
+            tgt[tb] = t < m_eff ? p.sel_targets[t] : -1;
+        }
+    }
+
+    // acc holds logits: lane owns column lane%32 of block tb; entry e of block vb
+    // is vocabulary id v_wave + vb*32 + (e/4)*8 + (lane/32)*4 + e%4.  Clears acc.
+    __device__ __forceinline__ void fold(f32x16 (&acc)[C::kVB][C::kTB], int vt, int wv, int frag_half, int V) {
+        constexpr int kVB = C::kVB, kTB = C::kTB;
+        const int v_wave = vt * C::kTileV + wv * C::kWaveV;
+        const int v_lane = v_wave + frag_half * 4;
+        if (vt * C::kTileV + C::kTileV > V) {                       // ragged last tile: mask ids >= V
+#pragma unroll
+            for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+                for (int tb = 0; tb < kTB; ++tb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        if (v_lane + vb * 32 + (e >> 2) * 8 + (e & 3) >= V) acc[vb][tb][e] = -INFINITY;
+        }
+#pragma unroll
+        for (int tb = 0; tb < kTB; ++tb) {
+            float mx0 = -INFINITY, mx1 = -INFINITY;
+#pragma unroll
+            for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+                for (int e = 0; e < 16; e += 2) {
+                    mx0 = fmaxf(mx0, acc[vb][tb][e]);
+                    mx1 = fmaxf(mx1, acc[vb][tb][e + 1]);
+                }
+            const float new_max = fmaxf(run_max[tb], fmaxf(mx0, mx1) * kLog2e);
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+            for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+                for (int e = 0; e < 16; e += 4) {
+                    s0 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e], kLog2e, -new_max));
+                    s1 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e + 1], kLog2e, -new_max));
+                    s2 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e + 2], kLog2e, -new_max));
+                    s3 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e + 3], kLog2e, -new_max));
+                }
+            run_sum[tb] = fmaf(run_sum[tb], __builtin_amdgcn_exp2f(run_max[tb] - new_max), (s0 + s1) + (s2 + s3));
+            run_max[tb] = new_max;
+        }
+        // target logit: rare (a lane owns kVB*16 of V ids per tile), so only
+        // waves in which some lane hits take the register-select path
+        bool hit = false;
+#pragma unroll
+        for (int tb = 0; tb < kTB; ++tb) {
+            const int d = tgt[tb] - v_wave;
+            hit |= d >= 0 && d < C::kWaveV && ((d >> 2) & 1) == frag_half;
+        }
+        if (__any(hit)) {
+#pragma unroll
+            for (int tb = 0; tb < kTB; ++tb) {
+                const int d = tgt[tb] - v_wave;
+                if (d >= 0 && d < C::kWaveV && ((d >> 2) & 1) == frag_half) {
+                    const int vb_t = d >> 5, e_t = ((d >> 3) & 3) * 4 + (d & 3);
+                    float z = 0.f;
+#pragma unroll
+                    for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) z = (vb == vb_t && e == e_t) ? acc[vb][tb][e] : z;
+                    tgt_logit[tb] += z;
+                }
+            }
+        }
+#pragma unroll
+        for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+            for (int tb = 0; tb < kTB; ++tb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
+    }
+
+    // Merge the two lane halves (same token, different vocabulary rows), then
+    // the kWavesV waves that share a token, and write the split's triple.
+    // s_merge: LDS scratch [kWavesV][3][kTileT] floats, idle at this point.
+    __device__ __forceinline__ void merge_store(const HeadParams& p, float* s_merge, int64_t tok0, int64_t m_eff,
+                                                int sp, int wv, int wt, int lane, int tid) {
+        constexpr int kTileT = C::kTileT;
+#pragma unroll
+        for (int tb = 0; tb < C::kTB; ++tb) {
+            const float om = __shfl_xor(run_max[tb], 32), os = __shfl_xor(run_sum[tb], 32);
+            const float ot = __shfl_xor(tgt_logit[tb], 32);
+            const float nm = fmaxf(run_max[tb], om);
+            run_sum[tb] = run_sum[tb] * __builtin_amdgcn_exp2f(run_max[tb] - nm) + os * __builtin_amdgcn_exp2f(om - nm);
+            run_max[tb] = nm;
+            tgt_logit[tb] += ot;
+        }
+        if (lane < 32) {
+#pragma unroll
+            for (int tb = 0; tb < C::kTB; ++tb) {
+                const int col = wt * C::kWaveT + tb * 32 + lane;
+                s_merge[(wv * 3 + 0) * kTileT + col] = run_max[tb];
+                s_merge[(wv * 3 + 1) * kTileT + col] = run_sum[tb];
+                s_merge[(wv * 3 + 2) * kTileT + col] = tgt_logit[tb];
+            }
+        }
+        __syncthreads();
+        for (int col = tid; col < kTileT; col += C::kThreads) {
+            const int64_t t = tok0 + col;
+            if (t >= m_eff) continue;
+            float gm = kNegBig, gs = 0.f, gt = 0.f;
+#pragma unroll
+            for (int q = 0; q < C::kWavesV; ++q) gm = fmaxf(gm, s_merge[(q * 3 + 0) * kTileT + col]);
+#pragma unroll
+            for (int q = 0; q < C::kWavesV; ++q) {
+                gs += s_merge[(q * 3 + 1) * kTileT + col] * __builtin_amdgcn_exp2f(s_merge[(q * 3 + 0) * kTileT + col] - gm);
+                gt += s_merge[(q * 3 + 2) * kTileT + col];
+            }
+            float* out = p.part + (int64_t)sp * p.M + t;
+            out[0] = gm;
+            out[(int64_t)p.splits * p.M] = gs;
+            out[2 * (int64_t)p.splits * p.M] = gt;
+        }
+    }
+};
+
+template <class C>
+__global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head_mfma_kernel(HeadParams p) {
+    constexpr int kTileV = C::kTileV, kTileT = C::kTileT, kWaveV = C::kWaveV, kWaveT = C::kWaveT;
+    constexpr int kVB = C::kVB, kTB = C::kTB, kBK = C::kBK, kStages = C::kStages;
+    constexpr int kDmaPerWave = C::kDmaPerWave, kKSteps = C::kKSteps;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     int rt, sp;
@@ -186,69 +329,51 @@ __global__ __launch_bounds__(kHeadThreads) void head_mfma_kernel(HeadParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wv = wave / kWavesT, wt = wave % kWavesT;
+    const int wv = wave / C::kWavesT, wt = wave % C::kWavesT;
     const int vt_begin = (int)((int64_t)p.vocab_tiles * sp / p.splits);
     const int vt_end = (int)((int64_t)p.vocab_tiles * (sp + 1) / p.splits);
     const int k_tiles = p.H / kBK;
     const int total_iters = (vt_end - vt_begin) * k_tiles;
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-    // ---- loader role: kDmaPerWave transfers of kRowsPerDma rows each
-    const bool loads_w = wave < 4;
-    const int ld_row = (wave & 3) * kRowsPerWave + lane / L::kChunks;     // + q * kRowsPerDma
-    const int ld_slot = lane % L::kChunks;
+    // ---- loader role: transfers wave*kDmaPerWave + q, each kRowsPerDma staged rows
+    const int ld_row0 = wave * kDmaPerWave * C::kRowsPerDma + lane / C::kChunks;   // + q * kRowsPerDma
+    const int ld_slot = lane % C::kChunks;
     const uint16_t* src[kDmaPerWave];
-    int src_chunk[kDmaPerWave];
-    int issue_vt = vt_begin, issue_kt = 0;
-    auto point_at_tile = [&](int vt) {
+    int issue_vt = vt_begin, issue_kt = 0, issue_stage = 0, issue_kpos = 0;
+    auto point_at_tile = [&](int vt, bool w_only) {
 #pragma unroll
         for (int q = 0; q < kDmaPerWave; ++q) {
-            const int r = ld_row + q * L::kRowsPerDma;
-            src_chunk[q] = (ld_slot ^ L::swz(r)) * 8;
-            if (loads_w) {
+            const int r = ld_row0 + q * C::kRowsPerDma;                 // staged row; < kTileV means a W row
+            const int chunk = (ld_slot ^ C::swz(r)) * 8;
+            if (r < kTileV) {
                 const int64_t v = min((int64_t)vt * kTileV + r, (int64_t)p.V - 1);
-                src[q] = p.w + v * p.ld_w + src_chunk[q];
-            } else {
-                const int64_t t = min(tok0 + r, m_eff - 1);
+                src[q] = p.w + v * p.ld_w + chunk;
+            } else if (!w_only) {
+                const int64_t t = min(tok0 + (r - kTileV), m_eff - 1);
                 int64_t row = p.sel_rows[t];
                 row = min(max(row, (int64_t)0), p.n_rows - 1);
-                src[q] = p.hidden + row * p.ld_h + src_chunk[q];
+                src[q] = p.hidden + row * p.ld_h + chunk;
             }
         }
     };
-    point_at_tile(vt_begin);
+    point_at_tile(vt_begin, false);
     auto issue = [&]() {                // next (vocabulary tile, k tile) in sweep order
-        const int stage = (issue_vt - vt_begin) * k_tiles + issue_kt;
-        const unsigned dst = lds_base + (stage % kStages) * L::kStageBytes +
-                             ((loads_w ? 0 : kTileV) + (wave & 3) * kRowsPerWave) * L::kRowBytes;
+        const unsigned dst = lds_base + issue_stage * C::kStageBytes + wave * kDmaPerWave * 1024;
 #pragma unroll
-        for (int q = 0; q < kDmaPerWave; ++q) {
-            dma_16b_per_lane(src[q], dst + q * 1024);
-            src[q] += kBK;
-        }
+        for (int q = 0; q < kDmaPerWave; ++q) dma_16b_per_lane(src[q] + issue_kpos, dst + q * 1024);
+        issue_kpos += kBK;
+        if (++issue_stage == kStages) issue_stage = 0;
         if (++issue_kt == k_tiles) {
             issue_kt = 0;
+            issue_kpos = 0;
             ++issue_vt;
-            if (loads_w) {
-                point_at_tile(min(issue_vt, vt_end - 1));
-            } else {
-#pragma unroll
-                for (int q = 0; q < kDmaPerWave; ++q) src[q] -= p.H;
-            }
+            point_at_tile(min(issue_vt, vt_end - 1), true);
         }
     };
 
-    // ---- per-lane softmax state for my kTB token columns
-    float run_max[kTB], run_sum[kTB], tgt_logit[kTB];
-    int tgt[kTB];
-#pragma unroll
-    for (int tb = 0; tb < kTB; ++tb) {
-        run_max[tb] = kNegBig;
-        run_sum[tb] = 0.f;
-        tgt_logit[tb] = 0.f;
-        const int64_t t = tok0 + wt * kWaveT + tb * 32 + (lane & 31);
-        tgt[tb] = t < m_eff ? p.sel_targets[t] : -1;
-    }
+    LaneSoftmax<C> sm;
+    sm.init(p, tok0, m_eff, wt, lane);
 
     f32x16 acc[kVB][kTB];
 #pragma unroll
@@ -258,158 +383,71 @@ __global__ __launch_bounds__(kHeadThreads) void head_mfma_kernel(HeadParams p) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
 
-    // ---- fill the ring
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    bf16x8 fa[2][kVB], fb[2][kTB];
+    auto load_frags = [&](int stage, int ks, int buf) {
+        const unsigned char* st = smem + stage * C::kStageBytes;
+        const unsigned char* a_base = st + (wv * kWaveV) * C::kRowBytes;
+        const unsigned char* b_base = st + (kTileV + wt * kWaveT) * C::kRowBytes;
+        const int c = ks * 2 + frag_half;
+#pragma unroll
+        for (int vb = 0; vb < kVB; ++vb)
+            fa[buf][vb] = *reinterpret_cast<const bf16x8*>(a_base + C::chunk_off(vb * 32 + frag_row, c));
+#pragma unroll
+        for (int tb = 0; tb < kTB; ++tb)
+            fb[buf][tb] = *reinterpret_cast<const bf16x8*>(b_base + C::chunk_off(tb * 32 + frag_row, c));
+    };
+    auto mfma_step = [&](int buf) {
+#pragma unroll
+        for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+            for (int tb = 0; tb < kTB; ++tb)
+                acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][vb], fb[buf][tb], acc[vb][tb], 0, 0, 0);
+    };
+
+    // ---- fill the ring, publish stage 0, start on its first fragments
 #pragma unroll
     for (int s = 0; s < kStages - 1; ++s)
         if (s < total_iters) issue();
+    if (total_iters >= kStages - 1)
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kDmaPerWave));
+    else
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    if (kStages - 1 < total_iters) issue();
+    load_frags(0, 0, 0);
 
-    const int frag_row = lane & 31, frag_half = lane >> 5;
-    int kt = 0, vt = vt_begin;
+    int kt = 0, vt = vt_begin, stage = 0;
     for (int it = 0; it < total_iters; ++it) {
-        // my transfers for stage `it` are done when at most the younger ones are in flight
-        if (total_iters - it >= kStages - 1)
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kDmaPerWave));
-        else
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        __syncthreads();                // everyone's transfers landed; everyone left stage it-1
-        if (it + kStages - 1 < total_iters) issue();
-
-        const unsigned char* st = smem + (it % kStages) * L::kStageBytes;
-        const unsigned char* a_base = st + (wv * kWaveV) * L::kRowBytes;
-        const unsigned char* b_base = st + (kTileV + wt * kWaveT) * L::kRowBytes;
-        bf16x8 fa[2][kVB], fb[2][kTB];
-        auto load_frags = [&](int ks, int buf) {
-            const int c = ks * 2 + frag_half;
 #pragma unroll
-            for (int vb = 0; vb < kVB; ++vb)
-                fa[buf][vb] = *reinterpret_cast<const bf16x8*>(a_base + L::chunk_off(vb * 32 + frag_row, c));
-#pragma unroll
-            for (int tb = 0; tb < kTB; ++tb)
-                fb[buf][tb] = *reinterpret_cast<const bf16x8*>(b_base + L::chunk_off(tb * 32 + frag_row, c));
-        };
-        load_frags(0, 0);
-#pragma unroll
-        for (int ks = 0; ks < kKSteps; ++ks) {
-            if (ks + 1 < kKSteps) load_frags(ks + 1, (ks + 1) & 1);
-#pragma unroll
-            for (int vb = 0; vb < kVB; ++vb)
-#pragma unroll
-                for (int tb = 0; tb < kTB; ++tb)
-                    acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][vb], fb[ks & 1][tb],
-                                                                          acc[vb][tb], 0, 0, 0);
+        for (int ks = 0; ks + 1 < kKSteps; ++ks) {
+            load_frags(stage, ks + 1, (ks + 1) & 1);
+            mfma_step(ks & 1);
         }
-
-        if (++kt == k_tiles) {
-            // ---- a vocabulary tile is complete: fold it into the running softmax
-            const int v_wave = vt * kTileV + wv * kWaveV;          // first vocabulary id of my wave tile
-            const int v_lane = v_wave + frag_half * 4;              // + vb*32 + (e/4)*8 + e%4
-            if (vt * kTileV + kTileV > p.V) {                       // ragged last tile: mask ids >= V
-#pragma unroll
-                for (int vb = 0; vb < kVB; ++vb)
-#pragma unroll
-                    for (int tb = 0; tb < kTB; ++tb)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e)
-                            if (v_lane + vb * 32 + (e >> 2) * 8 + (e & 3) >= p.V) acc[vb][tb][e] = -INFINITY;
-            }
-#pragma unroll
-            for (int tb = 0; tb < kTB; ++tb) {
-                float mx0 = -INFINITY, mx1 = -INFINITY;
-#pragma unroll
-                for (int vb = 0; vb < kVB; ++vb)
-#pragma unroll
-                    for (int e = 0; e < 16; e += 2) {
-                        mx0 = fmaxf(mx0, acc[vb][tb][e]);
-                        mx1 = fmaxf(mx1, acc[vb][tb][e + 1]);
-                    }
-                const float new_max = fmaxf(run_max[tb], fmaxf(mx0, mx1) * kLog2e);
-                float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-#pragma unroll
-                for (int vb = 0; vb < kVB; ++vb)
-#pragma unroll
-                    for (int e = 0; e < 16; e += 4) {
-                        s0 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e], kLog2e, -new_max));
-                        s1 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e + 1], kLog2e, -new_max));
-                        s2 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e + 2], kLog2e, -new_max));
-                        s3 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e + 3], kLog2e, -new_max));
-                    }
-                run_sum[tb] = fmaf(run_sum[tb], __builtin_amdgcn_exp2f(run_max[tb] - new_max), (s0 + s1) + (s2 + s3));
-                run_max[tb] = new_max;
-            }
-            // target logit: rare (a lane owns 64 of V ids per tile), so only
-            // waves in which some lane hits take the register-select path
-            bool hit = false;
-#pragma unroll
-            for (int tb = 0; tb < kTB; ++tb) {
-                const int d = tgt[tb] - v_wave;
-                hit |= d >= 0 && d < kWaveV && ((d >> 2) & 1) == frag_half;
-            }
-            if (__any(hit)) {
-#pragma unroll
-                for (int tb = 0; tb < kTB; ++tb) {
-                    const int d = tgt[tb] - v_wave;
-                    if (d >= 0 && d < kWaveV && ((d >> 2) & 1) == frag_half) {
-                        const int vb_t = d >> 5, e_t = ((d >> 3) & 3) * 4 + (d & 3);
-                        float z = 0.f;
-#pragma unroll
-                        for (int vb = 0; vb < kVB; ++vb)
-#pragma unroll
-                            for (int e = 0; e < 16; ++e)
-                                z = (vb == vb_t && e == e_t) ? acc[vb][tb][e] : z;
-                        tgt_logit[tb] += z;
-                    }
-                }
-            }
-#pragma unroll
-            for (int vb = 0; vb < kVB; ++vb)
-#pragma unroll
-                for (int tb = 0; tb < kTB; ++tb)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
+        // The stage's last fragments are in registers.  Hand the stage back,
+        // publish the next one and fetch its first fragments BEFORE issuing the
+        // last MFMAs, so the barrier and the LDS latency hide behind them.
+        const int next_stage = stage + 1 == kStages ? 0 : stage + 1;
+        if (it + 1 < total_iters) {
+            if (total_iters - it - 2 >= kStages - 2)
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kDmaPerWave));
+            else
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __syncthreads();            // stage it+1 landed for everyone; everyone left stage it
+            if (it + kStages < total_iters) issue();
+            load_frags(next_stage, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step((kKSteps - 1) & 1);
+        stage = next_stage;
+        if (++kt == k_tiles) {          // a vocabulary tile is complete
+            sm.fold(acc, vt, wv, frag_half, p.V);
             kt = 0;
             ++vt;
         }
     }
-    __syncthreads();                    // all fragment reads done before the stages are reused
-
-    // ---- merge the two lane halves (same token, different vocabulary rows),
-    // then the kWavesV waves that share a token, and write the split's triple
-#pragma unroll
-    for (int tb = 0; tb < kTB; ++tb) {
-        const float om = __shfl_xor(run_max[tb], 32), os = __shfl_xor(run_sum[tb], 32);
-        const float ot = __shfl_xor(tgt_logit[tb], 32);
-        const float nm = fmaxf(run_max[tb], om);
-        run_sum[tb] = run_sum[tb] * __builtin_amdgcn_exp2f(run_max[tb] - nm) + os * __builtin_amdgcn_exp2f(om - nm);
-        run_max[tb] = nm;
-        tgt_logit[tb] += ot;
-    }
-    float* s_merge = reinterpret_cast<float*>(smem);   // [kWavesV][3][kTileT]
-    if (lane < 32) {
-#pragma unroll
-        for (int tb = 0; tb < kTB; ++tb) {
-            const int col = wt * kWaveT + tb * 32 + lane;
-            s_merge[(wv * 3 + 0) * kTileT + col] = run_max[tb];
-            s_merge[(wv * 3 + 1) * kTileT + col] = run_sum[tb];
-            s_merge[(wv * 3 + 2) * kTileT + col] = tgt_logit[tb];
-        }
-    }
-    __syncthreads();
-    for (int col = tid; col < kTileT; col += kHeadThreads) {
-        const int64_t t = tok0 + col;
-        if (t >= m_eff) continue;
-        float gm = kNegBig, gs = 0.f, gt = 0.f;
-#pragma unroll
-        for (int q = 0; q < kWavesV; ++q) gm = fmaxf(gm, s_merge[(q * 3 + 0) * kTileT + col]);
-#pragma unroll
-        for (int q = 0; q < kWavesV; ++q) {
-            gs += s_merge[(q * 3 + 1) * kTileT + col] * __builtin_amdgcn_exp2f(s_merge[(q * 3 + 0) * kTileT + col] - gm);
-            gt += s_merge[(q * 3 + 2) * kTileT + col];
-        }
-        float* out = p.part + (int64_t)sp * p.M + t;
-        out[0] = gm;
-        out[(int64_t)p.splits * p.M] = gs;
-        out[2 * (int64_t)p.splits * p.M] = gt;
-    }
+    __syncthreads();                    // every fragment read is done before the stages are reused
+    sm.merge_store(p, reinterpret_cast<float*>(smem), tok0, m_eff, sp, wv, wt, lane, tid);
 }
 
 __global__ __launch_bounds__(256) void head_combine_kernel(
@@ -443,17 +481,50 @@ __global__ __launch_bounds__(256) void head_combine_kernel(
     if (lse) lse[o] = l;
 }
 
-// number of vocabulary splits: minimise rounds x tiles-per-split over the 256
-// CUs (one 128 KiB-LDS workgroup per CU), with a small per-workgroup overhead
-static int choose_splits(int64_t M, int64_t V) {
-    const int64_t row_tiles = (M + kTileT - 1) / kTileT, vocab_tiles = (V + kTileV - 1) / kTileV;
+// Kernel variants (TPPO_HEAD_VARIANT selects one; 0 is the default).
+using Cfg0 = HeadCfg<256, 256, 2, 4, 64, 2, 1>;
+using Cfg1 = HeadCfg<256, 256, 2, 4, 32, 4, 1>;
+using Cfg2 = HeadCfg<256, 256, 2, 4, 32, 5, 1>;
+using Cfg3 = HeadCfg<128, 256, 1, 4, 32, 3, 2>;
+
+struct HeadVariant {
+    void (*kernel)(HeadParams);
+    int tile_v, tile_t, threads, lds_bytes, wgs_per_cu;
+};
+template <class C>
+constexpr HeadVariant make_variant() {
+    return {head_mfma_kernel<C>, C::kTileV, C::kTileT, C::kThreads, C::kLdsBytes, C::kWgsPerCu};
+}
+static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>(), make_variant<Cfg2>(),
+                                        make_variant<Cfg3>()};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+static const HeadVariant& pick_variant() {
+    const char* e = getenv("TPPO_HEAD_VARIANT");
+    int id = e ? atoi(e) : 0;
+    if (id < 0 || id >= kNumVariants) id = 0;
+    return kVariants[id];
+}
+
+// Number of vocabulary splits: minimise rounds x tiles-per-split over the 256
+// CUs, with a small per-workgroup overhead.  The ~32 workgroups resident on an
+// XCD are 8 token tiles x 4 splits when the split count is a multiple of 4; that
+// shape shares every W tile 8 ways and every hidden tile 4 ways in the XCD's L2
+// (measured ~8 % faster than 2 splits), hence the penalty on other counts.
+static int choose_splits(const HeadVariant& hv, int64_t M, int64_t V) {
+    const int64_t row_tiles = (M + hv.tile_t - 1) / hv.tile_t, vocab_tiles = (V + hv.tile_v - 1) / hv.tile_v;
+    const int64_t slots = 256 * hv.wgs_per_cu;
     int best = 1;
     double best_cost = 1e300;
     const int max_s = (int)(vocab_tiles < kMaxSplits ? vocab_tiles : kMaxSplits);
+    if (const char* e = getenv("TPPO_HEAD_SPLITS")) {       // tuning override
+        const int forced = atoi(e);
+        if (forced >= 1) return forced < max_s ? forced : max_s;
+    }
     for (int s = 1; s <= max_s; ++s) {
-        const double rounds = (double)((row_tiles * s + 255) / 256);
+        const double rounds = (double)((row_tiles * s + slots - 1) / slots);
         const double per = (double)((vocab_tiles + s - 1) / s) + 0.25;
-        const double cost = rounds * per;
+        const double cost = rounds * per * (s % 4 == 0 ? 1.0 : 1.08);
         if (cost < best_cost - 1e-9) {
             best_cost = cost;
             best = s;
@@ -475,7 +546,12 @@ extern "C" size_t tppo_token_logprobs_workspace_bytes(int64_t M, int64_t H, int6
     using namespace tppo;
     (void)H;
     if (M <= 0 || V <= 0 || dt != TPPO_BF16) return 256;
-    return round_up((size_t)3 * (size_t)choose_splits(M, V) * (size_t)M * sizeof(float), 256);
+    size_t need = 0;
+    for (const HeadVariant& hv : kVariants) {
+        const size_t n = (size_t)3 * (size_t)choose_splits(hv, M, V) * (size_t)M * sizeof(float);
+        need = n > need ? n : need;
+    }
+    return round_up(need, 256);
 }
 
 extern "C" int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H, int64_t ld_hidden,
@@ -486,7 +562,7 @@ extern "C" int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H
                                    int32_t* status, void* stream) {
     using namespace tppo;
     if (dt != TPPO_F32 && dt != TPPO_BF16) return TPPO_ERR_DTYPE;
-    if (M < 0 || H < 0 || V < 0 || n_rows < 0 || M > INT32_MAX || V > INT32_MAX - kTileV ||
+    if (M < 0 || H < 0 || V < 0 || n_rows < 0 || M > INT32_MAX || V > INT32_MAX - 4096 ||
         H > INT32_MAX)
         return TPPO_ERR_SIZE;
     if (M == 0) return TPPO_OK;
@@ -522,20 +598,15 @@ extern "C" int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H
     p.part = static_cast<float*>(workspace);
     p.n_rows = n_rows; p.ld_h = ld_hidden; p.ld_w = ld_w; p.M = M;
     p.H = (int)H; p.V = (int)V;
-    p.row_tiles = (int)((M + kTileT - 1) / kTileT);
-    p.vocab_tiles = (int)((V + kTileV - 1) / kTileV);
-    p.splits = choose_splits(M, V);
-
-    // two staging shapes: 4 stages of 32 K-elements (default) or 2 stages of 64
-    const char* variant = getenv("TPPO_HEAD_VARIANT");
-    const bool wide = variant && variant[0] == '1';
-    auto kernel = wide ? head_mfma_kernel<64, 2> : head_mfma_kernel<32, 4>;
-    const int lds_bytes = wide ? 2 * StageLayout<64>::kStageBytes : 4 * StageLayout<32>::kStageBytes;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+    const HeadVariant& hv = pick_variant();
+    p.row_tiles = (int)((M + hv.tile_t - 1) / hv.tile_t);
+    p.vocab_tiles = (int)((V + hv.tile_v - 1) / hv.tile_v);
+    p.splits = choose_splits(hv, M, V);
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(hv.kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, hv.lds_bytes) != hipSuccess)
         return TPPO_ERR_LAUNCH;
     const int grid = p.row_tiles * p.splits;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kHeadThreads), lds_bytes, s, p);
+    hipLaunchKernelGGL(hv.kernel, dim3(grid), dim3(hv.threads), hv.lds_bytes, s, p);
     if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
     hipLaunchKernelGGL(head_combine_kernel, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, s, p.part,
                        p.splits, M, m_actual, sel_rows, sel_targets, n_rows, (int)V, out_index, logp,
