@@ -1,0 +1,91 @@
+// Work list shared by the EGAE scan and the loss reductions.
+//
+// The response-packed token array is cut into chunks of at most kChunkTokens
+// tokens that never straddle two sequences.  A chunk is described by 16 bytes,
+// so a workgroup learns everything about its tokens (which sequence, where the
+// sequence ends, how far into the sequence it is) from ONE load instead of a
+// chain of dependent look-ups in the offset arrays.  Chunks are listed in
+// processing order: last sequence first and, inside a sequence, last chunk
+// first -- the order in which a right-to-left scan can consume them.
+#pragma once
+#include "common.h"
+
+namespace tppo {
+
+constexpr int kChunkThreads = 256;
+constexpr int kChunkTpt = 8;                                   // tokens per thread
+constexpr int kChunkTokens = kChunkThreads * kChunkTpt;        // 2048
+constexpr int kBuildThreads = 1024;
+
+static_assert(kChunkTokens == 2048, "Chunk::pos_len packs the length in 11 bits");
+
+struct Chunk {
+    int32_t start;     // response-packed index of the chunk's first token
+    int32_t pos_len;   // (chunk number inside the sequence << 11) | (tokens in the chunk - 1)
+    int32_t seg;       // sequence the chunk belongs to
+    int32_t after;     // chunks after it in the same sequence (0: it holds the sequence's last token)
+    __device__ __forceinline__ int len() const { return (pos_len & (kChunkTokens - 1)) + 1; }
+    __device__ __forceinline__ int number() const { return pos_len >> 11; }
+};
+
+static inline int64_t max_chunks(int64_t n_resp, int64_t B) { return n_resp / kChunkTokens + B + 1; }
+
+// One workgroup: chunk counts per sequence, their prefix sums in reverse
+// sequence order, then every sequence writes its own descriptors.  Sequences
+// with a bad layout (negative length, out of range) contribute no chunk and set
+// the status bit.  n_chunks[0] receives the total.
+__device__ __forceinline__ void build_chunks(const int32_t* __restrict__ resp_off, int B, int n_resp,
+                                             Chunk* __restrict__ chunks, int cap,
+                                             int32_t* __restrict__ n_chunks, int32_t* status) {
+    __shared__ int s_wave[kBuildThreads / kWave];
+    __shared__ int s_carry;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) {
+        s_carry = 0;
+        if (resp_off[0] != 0 || resp_off[B] != n_resp) set_status(status, TPPO_STATUS_BAD_LAYOUT);
+    }
+    __syncthreads();
+    for (int base = 0; base < B; base += kBuildThreads) {
+        const int i = B - 1 - (base + tid);                    // reverse sequence order
+        int lo = 0, len = 0, cnt = 0;
+        if (i >= 0) {
+            lo = resp_off[i];
+            const int hi = resp_off[i + 1];
+            if (lo < 0 || hi < lo || hi > n_resp) {
+                set_status(status, TPPO_STATUS_BAD_LAYOUT);
+            } else {
+                len = hi - lo;
+                cnt = (len + kChunkTokens - 1) / kChunkTokens;
+            }
+        }
+        int inc = cnt;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int y = __shfl_up(inc, off);
+            if (lane >= off) inc += y;
+        }
+        if (lane == kWave - 1) s_wave[wave] = inc;
+        __syncthreads();
+        int pre = s_carry;
+        for (int w = 0; w < wave; ++w) pre += s_wave[w];
+        const int first = pre + inc - cnt;                      // processing index of my last chunk
+        for (int c = cnt - 1; c >= 0; --c) {
+            Chunk d;
+            d.start = lo + c * kChunkTokens;
+            d.pos_len = (c << 11) | (min(kChunkTokens, len - c * kChunkTokens) - 1);
+            d.seg = i;
+            d.after = cnt - 1 - c;
+            const int w = first + (cnt - 1 - c);
+            if (w < cap) chunks[w] = d;                         // overlapping sequences cannot overflow the list
+        }
+        __syncthreads();
+        if (tid == kBuildThreads - 1) s_carry = pre + inc;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        if (s_carry > cap) set_status(status, TPPO_STATUS_BAD_LAYOUT);
+        n_chunks[0] = min(s_carry, cap);
+    }
+}
+
+}  // namespace tppo

@@ -4,74 +4,69 @@
 // Both recurrences are affine in the value carried in from the right:
 //   A_t = delta_t + (gamma*lambda) A_{t+1},   R_t = r_t + gamma R_{t+1},
 // and restart at the last token of every sequence (where the bootstrap value of
-// Sec. 3.1 enters delta).  The array is cut into fixed tiles of kTile tokens,
-// one workgroup each, independent of sequence boundaries.  A tile
-//   1. loads r, V (8 B/token), composes its tokens' affine maps per thread,
-//      then across the wavefront with shuffles and across wavefronts via LDS;
+// Sec. 3.1 enters delta).  The tokens are cut into chunks of <= 2048 tokens that
+// never straddle two sequences (chunks.h); a small kernel lists them in
+// right-to-left processing order.  A persistent grid of workgroups then walks
+// the list; for each chunk a workgroup
+//   1. loads r, V (8 B/token; the loads of its NEXT chunk are already in flight
+//      while it works on this one), composes its tokens' affine maps per
+//      thread, across the wavefront with shuffles, across wavefronts via LDS;
 //   2. publishes "value at my first token if nothing is carried in" for A and
-//      R as one 64-bit {flag, float} word each;
-//   3. if its last token is not the end of a sequence, sums the published words
-//      of the following tiles of that sequence, weighted by (gamma*lambda)^n
-//      resp. gamma^n -- these words depend on no other tile, so there is no
-//      chain of waits; tiles to the right have lower workgroup ids and were
-//      dispatched earlier, and the wait is bounded;
+//      R ({flag, float} words, two per quantity: hi + lo of an fp64);
+//   3. if the sequence continues to its right, sums the published words of the
+//      following chunks of the sequence, weighted by (gamma*lambda)^n resp.
+//      gamma^n.  Those words depend on no other chunk, so there is no chain of
+//      waits; the chunks to the right come earlier in the list, so they were
+//      started earlier by a co-resident workgroup; the wait is bounded anyway;
 //   4. replays its tokens with the carry and stores A, R (8 B/token).
-// HBM traffic is the algorithmic 16 B/token plus O(tiles) metadata.
+// HBM traffic is the algorithmic 16 B/token plus 16 B per chunk of metadata.
 //
 // Arithmetic: inputs and outputs are fp32; the TD residuals, the affine maps and
 // every partial sum are fp64.  With gamma*lambda close to 1 a sequence sums up
 // to tens of thousands of residuals whose individual fp32 rounding errors would
 // add up (random walk) beyond 1e-5; the kernel is bound by HBM, not by the ALUs,
 // so fp64 costs nothing measurable.
-#include "common.h"
+#include <math.h>
+
+#include "chunks.h"
 
 namespace tppo {
 
-constexpr int kEgaeThreads = 256;
-constexpr int kTpt = 8;                               // tokens per thread
-constexpr int kTile = kEgaeThreads * kTpt;            // tokens per workgroup
 constexpr int kSpinLimit = 1 << 22;
 
 struct EgaeWs {
-    int32_t* tile_seg;                // [tiles + 1] sequence that owns a tile's first token
-    unsigned long long* agg;          // [tiles][4] {flag << 32 | float bits}: A hi, A lo, R hi, R lo
+    Chunk* chunks;                    // [cap]
+    unsigned long long* agg;          // [cap][4] {flag << 32 | float bits}: A hi, A lo, R hi, R lo
+    int32_t* n_chunks;                // [1]
 };
 
-static inline size_t egae_ws_bytes(int64_t tiles) {
-    return round_up((size_t)(tiles + 1) * 4, 256) + (size_t)tiles * 32;
+static inline size_t egae_ws_bytes(int64_t cap) {
+    return round_up((size_t)cap * sizeof(Chunk), 256) + round_up((size_t)cap * 32, 256) + 256;
 }
 
-__device__ __forceinline__ EgaeWs egae_ws(void* ws, int64_t tiles) {
+__host__ __device__ __forceinline__ EgaeWs egae_ws(void* ws, int64_t cap) {
+    char* p = static_cast<char*>(ws);
     EgaeWs w;
-    w.tile_seg = static_cast<int32_t*>(ws);
-    w.agg = reinterpret_cast<unsigned long long*>(static_cast<char*>(ws) +
-                                                  ((size_t)(tiles + 1) * 4 + 255) / 256 * 256);
+    w.chunks = reinterpret_cast<Chunk*>(p);
+    p += ((size_t)cap * sizeof(Chunk) + 255) / 256 * 256;
+    w.agg = reinterpret_cast<unsigned long long*>(p);
+    p += ((size_t)cap * 32 + 255) / 256 * 256;
+    w.n_chunks = reinterpret_cast<int32_t*>(p);
     return w;
 }
 
-// Clears the published words and records, for every tile, the sequence that
-// contains its first token (written by that sequence's thread: no search).
-__global__ __launch_bounds__(256) void egae_init_kernel(const int32_t* __restrict__ resp_off, int B,
-                                                        int n_resp, int tiles, void* ws_raw,
-                                                        int32_t* status) {
-    EgaeWs ws = egae_ws(ws_raw, tiles);
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < tiles) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) ws.agg[4 * i + q] = 0ull;
-    }
-    if (i == 0) {
-        ws.tile_seg[tiles] = B - 1;
-        if (resp_off[0] != 0 || resp_off[B] != n_resp) set_status(status, TPPO_STATUS_BAD_LAYOUT);
-    }
-    if (i < B) {
-        const int lo = resp_off[i], hi = resp_off[i + 1];
-        if (lo < 0 || hi < lo || hi > n_resp) {
-            set_status(status, TPPO_STATUS_BAD_LAYOUT);
-        } else if (hi > lo) {
-            for (int j = (lo + kTile - 1) / kTile; j < tiles && (int64_t)j * kTile < hi; ++j)
-                ws.tile_seg[j] = i;
-        }
+// workgroup 0 builds the chunk list; the others clear the published words
+__global__ __launch_bounds__(kBuildThreads) void egae_init_kernel(const int32_t* __restrict__ resp_off,
+                                                                  int B, int n_resp, int cap, void* ws_raw,
+                                                                  int32_t* status) {
+    EgaeWs ws = egae_ws(ws_raw, cap);
+    if (blockIdx.x == 0) {
+        build_chunks(resp_off, B, n_resp, ws.chunks, cap, ws.n_chunks, status);
+    } else {
+        const int64_t words = (int64_t)cap * 4;
+        for (int64_t i = (int64_t)(blockIdx.x - 1) * kBuildThreads + threadIdx.x; i < words;
+             i += (int64_t)(gridDim.x - 1) * kBuildThreads)
+            ws.agg[i] = 0ull;
     }
 }
 
@@ -97,173 +92,212 @@ __device__ __forceinline__ void publish(unsigned long long* p, double x) {
     __hip_atomic_store(p + 1, pack_word(lo), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// bounded wait for a published word; returns its float payload
-__device__ __forceinline__ float wait_word(unsigned long long* p, int32_t* status) {
-    unsigned long long w = 0;
+// Bounded wait for the four words of one chunk (A hi, A lo, R hi, R lo).  All
+// four loads of a poll are issued together, so a poll costs one memory round
+// trip, not four.
+__device__ __forceinline__ void wait_words(unsigned long long* p, double& a, double& r, int32_t* status) {
     for (int spin = 0; spin < kSpinLimit; ++spin) {
-        w = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (w >> 32) return __uint_as_float((unsigned)w);
-        __builtin_amdgcn_s_sleep(2);
+        const unsigned long long w0 = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long w1 = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long w2 = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long w3 = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((w0 >> 32) && (w1 >> 32) && (w2 >> 32) && (w3 >> 32)) {
+            a = (double)__uint_as_float((unsigned)w0) + (double)__uint_as_float((unsigned)w1);
+            r = (double)__uint_as_float((unsigned)w2) + (double)__uint_as_float((unsigned)w3);
+            return;
+        }
+        __builtin_amdgcn_s_sleep(1);
     }
     set_status(status, TPPO_STATUS_TIMEOUT);
-    return 0.f;
+    a = 0.0;
+    r = 0.0;
 }
 
-template <bool kVec>
-__global__ __launch_bounds__(kEgaeThreads) void egae_scan_kernel(
-    const float* __restrict__ rewards, const float* __restrict__ values,
-    const int32_t* __restrict__ resp_off, const int32_t* __restrict__ done,
-    const float* __restrict__ bootstrap, int B, int n_resp, int tiles, double gamma, double c,
-    double log2_gamma, double log2_c, float* __restrict__ adv, float* __restrict__ ret,
-    void* ws_raw, int32_t* status) {
-    __shared__ float s_v0[kEgaeThreads + 1];
-    __shared__ Affine s_wave[2][kEgaeThreads / kWave];
-    __shared__ double s_carry[2];
+typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte access, 4-byte aligned
 
-    EgaeWs ws = egae_ws(ws_raw, tiles);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int j = tiles - 1 - (int)blockIdx.x;        // right-most tile first
-    const int tile_start = j * kTile;
-    const int tile_end = min(n_resp, tile_start + kTile);
-    const int p0 = tile_start + tid * kTpt;
+constexpr int kEgaeThreads = 128;                       // 2 wavefronts, 16 tokens per thread:
+constexpr int kTpt = kChunkTokens / kEgaeThreads;       // the per-wavefront scan is paid once per 1024 tokens
+constexpr int kEgaeWaves = kEgaeThreads / kWave;
+constexpr int kEgaeMaxGroups = 1536;                    // 6 workgroups per CU: all co-resident (<= 168 VGPRs)
 
-    // ---- loads (issued first; everything below overlaps their latency)
-    float r[kTpt], v[kTpt];
-    if (kVec && p0 + kTpt <= n_resp) {
+struct TokenRegs { float r[kTpt], v[kTpt], v_after; };
+
+// the kTpt tokens of thread `tid` in a chunk (chunk starts are only 4-byte aligned)
+__device__ __forceinline__ void load_tokens(TokenRegs& t, const float* __restrict__ rewards,
+                                            const float* __restrict__ values, int start, int len, int tid) {
+    const int k0 = tid * kTpt;
+    if (k0 + kTpt <= len) {
 #pragma unroll
         for (int q = 0; q < kTpt / 4; ++q) {
-            const float4 rr = reinterpret_cast<const float4*>(rewards + p0)[q];
-            const float4 vv = reinterpret_cast<const float4*>(values + p0)[q];
-            r[4 * q] = rr.x; r[4 * q + 1] = rr.y; r[4 * q + 2] = rr.z; r[4 * q + 3] = rr.w;
-            v[4 * q] = vv.x; v[4 * q + 1] = vv.y; v[4 * q + 2] = vv.z; v[4 * q + 3] = vv.w;
+            const float4u rr = *reinterpret_cast<const float4u*>(rewards + start + k0 + 4 * q);
+            const float4u vv = *reinterpret_cast<const float4u*>(values + start + k0 + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                t.r[4 * q + e] = rr[e];
+                t.v[4 * q + e] = vv[e];
+            }
         }
     } else {
 #pragma unroll
         for (int k = 0; k < kTpt; ++k) {
-            const bool ok = p0 + k < n_resp;
-            r[k] = ok ? rewards[p0 + k] : 0.f;
-            v[k] = ok ? values[p0 + k] : 0.f;
+            const bool ok = k0 + k < len;
+            t.r[k] = ok ? rewards[start + k0 + k] : 0.f;
+            t.v[k] = ok ? values[start + k0 + k] : 0.f;
         }
     }
-    float v_after_tile = 0.f;                          // V of the token right of the tile
-    if (tid == kEgaeThreads - 1 && tile_end < n_resp)
-        v_after_tile = values[tile_end];
+}
 
-    // ---- which sequence owns each of my tokens; where sequences end
-    int seg_first = ws.tile_seg[j];
-    int seg_last = ws.tile_seg[j + 1];
-    seg_first = min(max(seg_first, 0), B - 1);
-    seg_last = min(max(seg_last, seg_first), B - 1);
-    unsigned end_mask = 0;                             // bit k: token k is the last of its sequence
-    float v_end[kTpt];                                 // V(s_l) to use at such a token
-#pragma unroll
-    for (int k = 0; k < kTpt; ++k) v_end[k] = 0.f;
-    int seg = seg_first;
-    if (p0 < tile_end) {
-        seg = find_segment(resp_off, seg_first, seg_last, p0);
-        int seg_end = resp_off[seg + 1];
-        if (seg_end <= p0 || resp_off[seg] > p0) {     // metadata does not cover this token
-            set_status(status, TPPO_STATUS_BAD_LAYOUT);
-            seg_end = INT32_MAX;
-        }
-#pragma unroll
-        for (int k = 0; k < kTpt; ++k) {
-            const int p = p0 + k;
-            if (p < tile_end) {
-                while (p >= seg_end && seg < B - 1) {  // step over finished / empty sequences
-                    ++seg;
-                    seg_end = resp_off[seg + 1];
-                }
-                if (p == seg_end - 1) {
-                    end_mask |= 1u << k;
-                    v_end[k] = done[seg] != 0 ? 0.f : (bootstrap ? bootstrap[seg] : v[k]);
-                }
-            }
-        }
+// V(s_{t+1}) for a chunk's last token (held by the last thread only): the next
+// chunk's first value, or the value of the state after the sequence -- 0 for a
+// finished one, else the bootstrap value, by default V(s_{l-1}) (Sec. 3.1)
+__device__ __forceinline__ float load_v_after(const Chunk& ch, const float* __restrict__ values,
+                                              const int32_t* __restrict__ done,
+                                              const float* __restrict__ bootstrap, int tid) {
+    float v = 0.f;
+    if (tid == kEgaeThreads - 1) {
+        const int end = ch.start + ch.len();
+        if (ch.after != 0) v = values[end];
+        else if (done[ch.seg] == 0) v = bootstrap ? bootstrap[ch.seg] : values[end - 1];
     }
+    return v;
+}
 
-    // ---- V(s_{t+1}) of my last token comes from my right neighbour
-    s_v0[tid] = v[0];
-    if (tid == kEgaeThreads - 1) s_v0[kEgaeThreads] = v_after_tile;
-    __syncthreads();
-    const float v_right = s_v0[tid + 1];
+// x^n for a small non-negative integer n (0^0 = 1)
+__device__ __forceinline__ double powi(double x, int n) {
+    double r = 1.0;
+    while (n > 0) {
+        if (n & 1) r *= x;
+        x *= x;
+        n >>= 1;
+    }
+    return r;
+}
 
-    // ---- my tokens as one affine map of the value carried in from the right
-    Affine fa = {1.0, 0.0}, fr = {1.0, 0.0};
+// One thread's tokens.  kFull: all kTpt tokens exist (no per-token guards).
+//   pass 1 (kStore = false): the affine maps value-to-my-right -> value-at-my-first-token
+//   pass 2 (kStore = true):  the values themselves, from the true value to my right
+// The sequence's last token needs no special case: nothing follows it in its
+// chunk, its map starts from a = 0 (set by the caller) and its V(s_{t+1}) is v_right.
+template <bool kFull, bool kStore>
+__device__ __forceinline__ void walk_tokens(const TokenRegs& tk, int n_mine, float v_right, double gamma,
+                                            double c, Affine& fa, Affine& fr, float (&out_a)[kTpt],
+                                            float (&out_r)[kTpt]) {
+    double v_next = (double)v_right;
 #pragma unroll
     for (int k = kTpt - 1; k >= 0; --k) {
-        if (p0 + k < tile_end) {
-            const bool is_end = (end_mask >> k) & 1u;
-            const float v_next = is_end ? v_end[k] : (k == kTpt - 1 ? v_right : v[k == kTpt - 1 ? k : k + 1]);
-            const double delta = fma(gamma, (double)v_next, (double)r[k]) - (double)v[k];
-            if (is_end) {
-                fa = {0.0, delta};
-                fr = {0.0, (double)r[k]};
-            } else {
-                fa = {c * fa.a, fma(c, fa.b, delta)};
-                fr = {gamma * fr.a, fma(gamma, fr.b, (double)r[k])};
+        if (kFull || k < n_mine) {
+            const double vk = (double)tk.v[k], rk = (double)tk.r[k];
+            const double delta = fma(gamma, v_next, rk) - vk;
+            fa.b = fma(c, fa.b, delta);
+            fr.b = fma(gamma, fr.b, rk);
+            if (!kStore) {
+                fa.a *= c;
+                fr.a *= gamma;
             }
+            v_next = vk;
+        }
+        if (kStore) {
+            out_a[k] = (float)fa.b;
+            out_r[k] = (float)fr.b;
         }
     }
+}
 
-    // ---- suffix composition across the wavefront (inclusive), then wavefronts
-    Affine sa = fa, sr = fr;
+__global__ __launch_bounds__(kEgaeThreads, 3) void egae_scan_kernel(
+    const float* __restrict__ rewards, const float* __restrict__ values,
+    const int32_t* __restrict__ done, const float* __restrict__ bootstrap, int n_resp, int cap,
+    double gamma, double c, double gamma_pow_chunk, double c_pow_chunk, float* __restrict__ adv,
+    float* __restrict__ ret, void* ws_raw, int32_t* status) {
+    __shared__ float s_v0[kEgaeThreads + 1];
+    __shared__ Affine s_wave[2][kEgaeWaves];
+    __shared__ double s_carry[2];
+
+    EgaeWs ws = egae_ws(ws_raw, cap);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int count = *ws.n_chunks;
+    int w = blockIdx.x;
+    if (w >= count) return;
+
+    Chunk cur = ws.chunks[w];
+    TokenRegs tk;
+    load_tokens(tk, rewards, values, cur.start, cur.len(), tid);
+    tk.v_after = load_v_after(cur, values, done, bootstrap, tid);
+
+    for (; w < count; w += gridDim.x) {
+        const int start = cur.start, len = cur.len(), k0 = tid * kTpt;
+        const int n_mine = min(max(len - k0, 0), kTpt);          // my tokens that exist
+        // ---- start the next chunk's loads before touching this one's data
+        const int w_next = w + gridDim.x;
+        Chunk nxt = cur;
+        TokenRegs tn;
+        if (w_next < count) {
+            nxt = ws.chunks[w_next];
+            load_tokens(tn, rewards, values, nxt.start, nxt.len(), tid);
+            tn.v_after = load_v_after(nxt, values, done, bootstrap, tid);
+        }
+
+        // ---- V(s_{t+1}) of my last token: my right neighbour's first value, or for
+        // the owner of the chunk's last token the value after the chunk
+        s_v0[tid] = tk.v[0];
+        if (tid == kEgaeThreads - 1) s_v0[kEgaeThreads] = tk.v_after;
+        __syncthreads();
+        const bool owns_last = n_mine > 0 && k0 + n_mine == len;
+        const float v_right = owns_last ? s_v0[kEgaeThreads] : s_v0[tid + 1];
+
+        // ---- pass 1: my tokens as one affine map of the value carried in from the right
+        const double a0 = (owns_last && cur.after == 0) ? 0.0 : 1.0;   // nothing is carried past a sequence's end
+        Affine fa = {a0, 0.0}, fr = {a0, 0.0};
+        float out_a[kTpt], out_r[kTpt];
+        if (len == kChunkTokens) walk_tokens<true, false>(tk, n_mine, v_right, gamma, c, fa, fr, out_a, out_r);
+        else walk_tokens<false, false>(tk, n_mine, v_right, gamma, c, fa, fr, out_a, out_r);
+
+        // ---- suffix composition across the wavefront (inclusive), then wavefronts
+        Affine sa = fa, sr = fr;
 #pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const Affine ga = shfl_down(sa, off), gr = shfl_down(sr, off);
-        if (lane + off < kWave) {
-            sa = compose(sa, ga);
-            sr = compose(sr, gr);
-        }
-    }
-    if (lane == 0) {
-        s_wave[0][wave] = sa;
-        s_wave[1][wave] = sr;
-    }
-    // exclusive suffix inside the wavefront: the inclusive one of my right neighbour
-    Affine ea = shfl_down(sa, 1), er = shfl_down(sr, 1);
-    if (lane == kWave - 1) {
-        ea = {1.0, 0.0};
-        er = {1.0, 0.0};
-    }
-    __syncthreads();
-    constexpr int kWaves = kEgaeThreads / kWave;
-    for (int w = wave + 1; w < kWaves; ++w) {
-        ea = compose(ea, s_wave[0][w]);
-        er = compose(er, s_wave[1][w]);
-    }
-
-    // ---- publish the tile's own contribution, then collect the carry
-    if (wave == 0) {
-        if (lane == 0) {
-            Affine ta = s_wave[0][0], tr = s_wave[1][0];
-            for (int w = 1; w < kWaves; ++w) {
-                ta = compose(ta, s_wave[0][w]);
-                tr = compose(tr, s_wave[1][w]);
+        for (int off = 1; off < kWave; off <<= 1) {
+            const Affine ga = shfl_down(sa, off), gr = shfl_down(sr, off);
+            if (lane + off < kWave) {
+                sa = compose(sa, ga);
+                sr = compose(sr, gr);
             }
-            publish(&ws.agg[4 * j], ta.b);
-            publish(&ws.agg[4 * j + 2], tr.b);
         }
-        // sequence of the tile's last token; does it run on into the next tile?
-        const int s_last = find_segment(resp_off, seg_first, seg_last, tile_end - 1);
-        const int s_end = resp_off[s_last + 1];
-        double carry_a = 0.0, carry_r = 0.0;
-        if (s_end > tile_end && s_end <= n_resp && j + 1 < tiles) {
-            const int k_end = (s_end - 1) / kTile;     // tile holding the sequence's last token
-            for (int k0 = j + 1; k0 <= k_end; k0 += kWave) {
-                const int k = k0 + lane;
+        if (lane == 0) {
+            s_wave[0][wave] = sa;
+            s_wave[1][wave] = sr;
+        }
+        Affine ea = shfl_down(sa, 1), er = shfl_down(sr, 1);      // exclusive: my right neighbour's inclusive
+        if (lane == kWave - 1) {
+            ea = {1.0, 0.0};
+            er = {1.0, 0.0};
+        }
+        __syncthreads();
+        for (int q = wave + 1; q < kEgaeWaves; ++q) {
+            ea = compose(ea, s_wave[0][q]);
+            er = compose(er, s_wave[1][q]);
+        }
+
+        // ---- publish the chunk's own contribution, then collect the carry
+        if (wave == 0) {
+            if (lane == 0 && cur.number() > 0) {                  // somebody to my left will ask for it
+                Affine ta = s_wave[0][0], tr = s_wave[1][0];
+                for (int q = 1; q < kEgaeWaves; ++q) {
+                    ta = compose(ta, s_wave[0][q]);
+                    tr = compose(tr, s_wave[1][q]);
+                }
+                publish(&ws.agg[4 * (int64_t)w], ta.b);
+                publish(&ws.agg[4 * (int64_t)w + 2], tr.b);
+            }
+            double carry_a = 0.0, carry_r = 0.0;
+            const int after = min(cur.after, w);                 // chunks to the right: list entries w-1 .. w-after
+            for (int j0 = 1; j0 <= after; j0 += kWave) {
+                const int j = j0 + lane;
                 double ta = 0.0, tr = 0.0;
-                if (k <= k_end) {
-                    const double n = (double)(k - j - 1) * (double)kTile;
-                    // weight of the adjacent tile is 1 (also when the factor is 0)
-                    const double wa = k == j + 1 ? 1.0 : exp2(n * log2_c);
-                    const double wr = k == j + 1 ? 1.0 : exp2(n * log2_gamma);
-                    const double ba = (double)wait_word(&ws.agg[4 * k], status) +
-                                      (double)wait_word(&ws.agg[4 * k + 1], status);
-                    const double br = (double)wait_word(&ws.agg[4 * k + 2], status) +
-                                      (double)wait_word(&ws.agg[4 * k + 3], status);
-                    ta = wa * ba;
-                    tr = wr * br;
+                if (j <= after) {
+                    // j-1 full chunks lie in between
+                    double ba, br;
+                    wait_words(&ws.agg[4 * (int64_t)(w - j)], ba, br, status);
+                    ta = powi(c_pow_chunk, j - 1) * ba;
+                    tr = powi(gamma_pow_chunk, j - 1) * br;
                 }
 #pragma unroll
                 for (int off = 32; off >= 1; off >>= 1) {
@@ -273,56 +307,52 @@ __global__ __launch_bounds__(kEgaeThreads) void egae_scan_kernel(
                 carry_a += ta;
                 carry_r += tr;
             }
-        }
-        if (lane == 0) {
-            s_carry[0] = carry_a;
-            s_carry[1] = carry_r;
-        }
-    }
-    __syncthreads();
-
-    // ---- replay my tokens with the true carry and store
-    double a_next = fma(ea.a, s_carry[0], ea.b);
-    double r_next = fma(er.a, s_carry[1], er.b);
-    float out_a[kTpt], out_r[kTpt];
-#pragma unroll
-    for (int k = kTpt - 1; k >= 0; --k) {
-        if (p0 + k < tile_end) {
-            const bool is_end = (end_mask >> k) & 1u;
-            const float v_next = is_end ? v_end[k] : (k == kTpt - 1 ? v_right : v[k == kTpt - 1 ? k : k + 1]);
-            const double delta = fma(gamma, (double)v_next, (double)r[k]) - (double)v[k];
-            a_next = is_end ? delta : fma(c, a_next, delta);
-            r_next = is_end ? (double)r[k] : fma(gamma, r_next, (double)r[k]);
-        }
-        out_a[k] = (float)a_next;
-        out_r[k] = (float)r_next;
-    }
-    if (kVec && p0 + kTpt <= n_resp) {
-#pragma unroll
-        for (int q = 0; q < kTpt / 4; ++q) {
-            reinterpret_cast<float4*>(adv + p0)[q] =
-                make_float4(out_a[4 * q], out_a[4 * q + 1], out_a[4 * q + 2], out_a[4 * q + 3]);
-            reinterpret_cast<float4*>(ret + p0)[q] =
-                make_float4(out_r[4 * q], out_r[4 * q + 1], out_r[4 * q + 2], out_r[4 * q + 3]);
-        }
-    } else {
-#pragma unroll
-        for (int k = 0; k < kTpt; ++k) {
-            if (p0 + k < n_resp) {
-                adv[p0 + k] = out_a[k];
-                ret[p0 + k] = out_r[k];
+            if (lane == 0) {
+                s_carry[0] = carry_a;
+                s_carry[1] = carry_r;
             }
         }
+        __syncthreads();
+
+        // ---- pass 2: replay my tokens from the true value to my right and store
+        Affine va = {0.0, fma(ea.a, s_carry[0], ea.b)}, vr = {0.0, fma(er.a, s_carry[1], er.b)};
+        if (a0 == 0.0) {                                         // past a sequence's end there is nothing
+            va.b = 0.0;
+            vr.b = 0.0;
+        }
+        if (len == kChunkTokens) walk_tokens<true, true>(tk, n_mine, v_right, gamma, c, va, vr, out_a, out_r);
+        else walk_tokens<false, true>(tk, n_mine, v_right, gamma, c, va, vr, out_a, out_r);
+        if (n_mine == kTpt) {
+#pragma unroll
+            for (int q = 0; q < kTpt / 4; ++q) {
+                float4u oa, orr;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    oa[e] = out_a[4 * q + e];
+                    orr[e] = out_r[4 * q + e];
+                }
+                *reinterpret_cast<float4u*>(adv + start + k0 + 4 * q) = oa;
+                *reinterpret_cast<float4u*>(ret + start + k0 + 4 * q) = orr;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < kTpt; ++k) {
+                if (k < n_mine) {
+                    adv[start + k0 + k] = out_a[k];
+                    ret[start + k0 + k] = out_r[k];
+                }
+            }
+        }
+        cur = nxt;
+        tk = tn;
     }
 }
 
 }  // namespace tppo
 
 extern "C" size_t tppo_egae_workspace_bytes(int64_t n_resp, int64_t B) {
-    (void)B;
-    if (n_resp <= 0) return 256;
-    const int64_t tiles = (n_resp + tppo::kTile - 1) / tppo::kTile;
-    return tppo::egae_ws_bytes(tiles);
+    if (n_resp <= 0 || B <= 0) return 256;
+    return tppo::egae_ws_bytes(tppo::max_chunks(n_resp, B));
 }
 
 extern "C" int tppo_egae(const float* rewards, const float* values, const int32_t* resp_off,
@@ -330,7 +360,7 @@ extern "C" int tppo_egae(const float* rewards, const float* values, const int32_
                          float gamma, float lambda, float* adv, float* ret, void* workspace,
                          size_t workspace_bytes, int32_t* status, void* stream) {
     using namespace tppo;
-    if (B < 0 || n_resp < 0 || n_resp > INT32_MAX - kTile || B > INT32_MAX - 1) return TPPO_ERR_SIZE;
+    if (B < 0 || n_resp < 0 || n_resp > INT32_MAX - kChunkTokens || B > INT32_MAX / 4) return TPPO_ERR_SIZE;
     if (!(gamma >= 0.f && gamma <= 1.f) || !(lambda >= 0.f && lambda <= 1.f)) return TPPO_ERR_PARAM;
     if (n_resp == 0) return TPPO_OK;
     if (B == 0) return TPPO_ERR_SIZE;
@@ -339,23 +369,18 @@ extern "C" int tppo_egae(const float* rewards, const float* values, const int32_
         workspace_bytes < tppo_egae_workspace_bytes(n_resp, B))
         return TPPO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int tiles = (int)((n_resp + kTile - 1) / kTile);
-    const int init_threads = (int)(B > tiles ? B : tiles);
-    hipLaunchKernelGGL(egae_init_kernel, dim3((init_threads + 255) / 256), dim3(256), 0, s, resp_off,
-                       (int)B, (int)n_resp, tiles, workspace, status);
+    const int64_t cap64 = max_chunks(n_resp, B);
+    if (cap64 > INT32_MAX / 4) return TPPO_ERR_SIZE;
+    const int cap = (int)cap64;
+    const int clear_groups = (int)((cap64 * 4 + kBuildThreads * 8 - 1) / (kBuildThreads * 8));
+    hipLaunchKernelGGL(egae_init_kernel, dim3(1 + (clear_groups < 1 ? 1 : clear_groups)), dim3(kBuildThreads),
+                       0, s, resp_off, (int)B, (int)n_resp, cap, workspace, status);
     if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
     const double g = (double)gamma, c = (double)gamma * (double)lambda;
-    // log2(0) = -inf makes every weight beyond the next tile exactly 0
-    const double log2_gamma = log2(g), log2_c = log2(c);
-    const bool vec = is_aligned(rewards, 16) && is_aligned(values, 16) && is_aligned(adv, 16) &&
-                     is_aligned(ret, 16);
-    if (vec)
-        hipLaunchKernelGGL(egae_scan_kernel<true>, dim3(tiles), dim3(kEgaeThreads), 0, s, rewards,
-                           values, resp_off, done, bootstrap, (int)B, (int)n_resp, tiles, g, c,
-                           log2_gamma, log2_c, adv, ret, workspace, status);
-    else
-        hipLaunchKernelGGL(egae_scan_kernel<false>, dim3(tiles), dim3(kEgaeThreads), 0, s, rewards,
-                           values, resp_off, done, bootstrap, (int)B, (int)n_resp, tiles, g, c,
-                           log2_gamma, log2_c, adv, ret, workspace, status);
+    // weight of a whole chunk in the carry: (gamma*lambda)^2048 resp. gamma^2048
+    const double gamma_pow_chunk = pow(g, (double)kChunkTokens), c_pow_chunk = pow(c, (double)kChunkTokens);
+    const int groups = cap < kEgaeMaxGroups ? cap : kEgaeMaxGroups;
+    hipLaunchKernelGGL(egae_scan_kernel, dim3(groups), dim3(kEgaeThreads), 0, s, rewards, values, done,
+                       bootstrap, (int)n_resp, cap, g, c, gamma_pow_chunk, c_pow_chunk, adv, ret, workspace, status);
     return launch_result();
 }

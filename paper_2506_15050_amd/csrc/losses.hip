@@ -2,28 +2,55 @@
 // (Eqs. (valueclip), (valueloss)) as masked streaming reductions over the
 // response-packed arrays.  Token sets follow Sec. 3.2: policy tokens are the
 // first keep_len[i] window tokens of each sequence, value tokens all window
-// tokens of finished sequences; membership is derived from the per-sequence
-// metadata (held in LDS), so no mask array is read, and 16-byte groups with no
-// member of a set are not loaded for that set.  Sums are token-level
-// (Sec. 4.1.1): fp32 per thread over a few tokens, fp64 across threads and
-// workgroups, fixed order, no atomics -> bit-identical reruns.
-#include "common.h"
+// tokens of finished sequences.  The tokens are cut into chunks that never
+// straddle two sequences (chunks.h), so set membership is one comparison per
+// token for the policy set and one flag per chunk for the value set: no mask
+// array is read, and a chunk outside a set issues no loads for that set.  Sums
+// are token-level (Sec. 4.1.1): fp32 per thread over a few tokens, fp64 across
+// threads and workgroups, fixed order, no atomics -> bit-identical reruns.
+#include "chunks.h"
 
 namespace tppo {
 
-constexpr int kLossThreads = 256;
-constexpr int kLossTpt = 4;
-constexpr int kLossTile = kLossThreads * kLossTpt;
 constexpr int kLossMaxGroups = 2048;
-constexpr int kLossMaxLdsBytes = 60 * 1024;
+constexpr int kLossTpt = kChunkTpt;
+
+struct LossWs {
+    Chunk* chunks;        // [cap]
+    double* partials;     // [kLossMaxGroups][2]
+    int32_t* n_chunks;    // [1]
+};
+
+static inline size_t loss_ws_bytes(int64_t cap) {
+    return round_up((size_t)cap * sizeof(Chunk), 256) + (size_t)kLossMaxGroups * 2 * sizeof(double) + 256;
+}
+
+__host__ __device__ __forceinline__ LossWs loss_ws(void* ws, int64_t cap) {
+    char* p = static_cast<char*>(ws);
+    LossWs w;
+    w.chunks = reinterpret_cast<Chunk*>(p);
+    p += ((size_t)cap * sizeof(Chunk) + 255) / 256 * 256;
+    w.partials = reinterpret_cast<double*>(p);
+    p += (size_t)kLossMaxGroups * 2 * sizeof(double);
+    w.n_chunks = reinterpret_cast<int32_t*>(p);
+    return w;
+}
 
 struct LossParams {
     const float *logp_new, *logp_old, *adv, *v_new, *v_old, *ret;
-    const int32_t *resp_off, *keep_len, *done;
-    int B, n_resp, tiles;
+    const int32_t *keep_len, *done;
+    int cap;
     float ratio_lo, ratio_hi, xi_low, xi_high;
-    int use_lds, vec;
 };
+
+__global__ __launch_bounds__(kBuildThreads) void loss_init_kernel(const int32_t* __restrict__ resp_off, int B,
+                                                                  int n_resp, int cap, void* ws_raw,
+                                                                  int32_t* status) {
+    LossWs ws = loss_ws(ws_raw, cap);
+    build_chunks(resp_off, B, n_resp, ws.chunks, cap, ws.n_chunks, status);
+}
+
+typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte access, 4-byte aligned
 
 __device__ __forceinline__ float clampf(float x, float lo, float hi) {
     return fminf(fmaxf(x, lo), hi);
@@ -53,131 +80,106 @@ __device__ __forceinline__ double block_sum(double x, double* s_red) {
     return t;   // valid in thread 0
 }
 
-__global__ __launch_bounds__(kLossThreads) void loss_partial_kernel(LossParams p,
-                                                                    double* __restrict__ partials) {
-    extern __shared__ int32_t s_meta[];                // [B+1] offsets, then [B] keep | done << 31
-    __shared__ double s_red[kLossThreads / kWave];
-    const int tid = threadIdx.x;
-    const bool has_pol = p.logp_new != nullptr, has_val = p.v_new != nullptr;
-
-    const int32_t* off = p.resp_off;
-    if (p.use_lds) {
-        for (int i = tid; i <= p.B; i += kLossThreads) s_meta[i] = p.resp_off[i];
-        for (int i = tid; i < p.B; i += kLossThreads) {
-            const unsigned keep = (unsigned)max(p.keep_len[i], 0);
-            s_meta[p.B + 1 + i] = (int32_t)(keep | (p.done[i] != 0 ? 0x80000000u : 0u));
+// `n` tokens of `src` starting at `first` into x[]; only if the thread has any
+__device__ __forceinline__ void load_span(float (&x)[kLossTpt], const float* __restrict__ src, int first,
+                                          int n) {
+    if (n >= kLossTpt) {
+#pragma unroll
+        for (int q = 0; q < kLossTpt / 4; ++q) {
+            const float4u t = *reinterpret_cast<const float4u*>(src + first + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[4 * q + e] = t[e];
         }
-        __syncthreads();
-        off = s_meta;
+    } else {
+#pragma unroll
+        for (int k = 0; k < kLossTpt; ++k) x[k] = k < n ? src[first + k] : 0.f;
     }
+}
+
+__global__ __launch_bounds__(kChunkThreads) void loss_partial_kernel(LossParams p, void* ws_raw) {
+    __shared__ double s_red[kChunkThreads / kWave];
+    LossWs ws = loss_ws(ws_raw, p.cap);
+    const int tid = threadIdx.x, k0 = tid * kLossTpt;
+    const bool has_pol = p.logp_new != nullptr, has_val = p.v_new != nullptr;
+    const int count = *ws.n_chunks;
 
     float pol_acc = 0.f, val_acc = 0.f;
-    for (int j = blockIdx.x; j < p.tiles; j += gridDim.x) {
-        const int p0 = j * kLossTile + tid * kLossTpt;
-        if (p0 >= p.n_resp) continue;
-        int seg = find_segment(off, 0, p.B - 1, p0);
-        int seg_lo = off[seg], seg_hi = off[seg + 1];
-        bool in_pol[kLossTpt], in_val[kLossTpt];
-        bool any_pol = false, any_val = false;
-        unsigned kd = 0;
-        bool have_kd = false;
-#pragma unroll
-        for (int k = 0; k < kLossTpt; ++k) {
-            const int q = p0 + k;
-            in_pol[k] = in_val[k] = false;
-            if (q < p.n_resp) {
-                while (q >= seg_hi && seg < p.B - 1) {
-                    ++seg;
-                    seg_lo = off[seg];
-                    seg_hi = off[seg + 1];
-                    have_kd = false;
-                }
-                if (q >= seg_lo && q < seg_hi) {
-                    if (!have_kd) {
-                        kd = p.use_lds ? (unsigned)s_meta[p.B + 1 + seg]
-                                       : ((unsigned)max(p.keep_len[seg], 0) |
-                                          (p.done[seg] != 0 ? 0x80000000u : 0u));
-                        have_kd = true;
-                    }
-                    in_pol[k] = has_pol && (unsigned)(q - seg_lo) < (kd & 0x7fffffffu);
-                    in_val[k] = has_val && (kd >> 31) != 0;
-                    any_pol |= in_pol[k];
-                    any_val |= in_val[k];
-                }
-            }
+    int w = blockIdx.x;
+    Chunk cur = ws.chunks[w < count ? w : 0];
+    int keep = 0, fin = 0;
+    if (w < count) {
+        keep = p.keep_len[cur.seg];
+        fin = p.done[cur.seg];
+    }
+    for (; w < count; w += gridDim.x) {
+        const int start = cur.start, len = cur.len();
+        // tokens of this chunk in the policy set: window positions below keep_len
+        const int pol_in_chunk = has_pol ? min(max(keep - cur.number() * kChunkTokens, 0), len) : 0;
+        const int val_in_chunk = (has_val && fin != 0) ? len : 0;
+        const int my_pol = min(max(pol_in_chunk - k0, 0), kLossTpt);
+        const int my_val = min(max(val_in_chunk - k0, 0), kLossTpt);
+        // metadata of the next chunk: in flight while this one streams
+        const int w_next = w + gridDim.x;
+        Chunk nxt = cur;
+        int keep_n = 0, fin_n = 0;
+        if (w_next < count) {
+            nxt = ws.chunks[w_next];
+            keep_n = p.keep_len[nxt.seg];
+            fin_n = p.done[nxt.seg];
         }
-        const bool full = p.vec && p0 + kLossTpt <= p.n_resp;
-        if (any_pol) {
-            float ln[kLossTpt], lo[kLossTpt], a[kLossTpt];
-            if (full) {
-                const float4 x = *reinterpret_cast<const float4*>(p.logp_new + p0);
-                const float4 y = *reinterpret_cast<const float4*>(p.logp_old + p0);
-                const float4 z = *reinterpret_cast<const float4*>(p.adv + p0);
-                ln[0] = x.x; ln[1] = x.y; ln[2] = x.z; ln[3] = x.w;
-                lo[0] = y.x; lo[1] = y.y; lo[2] = y.z; lo[3] = y.w;
-                a[0] = z.x; a[1] = z.y; a[2] = z.z; a[3] = z.w;
-            } else {
-#pragma unroll
-                for (int k = 0; k < kLossTpt; ++k) {
-                    ln[k] = in_pol[k] ? p.logp_new[p0 + k] : 0.f;
-                    lo[k] = in_pol[k] ? p.logp_old[p0 + k] : 0.f;
-                    a[k] = in_pol[k] ? p.adv[p0 + k] : 0.f;
-                }
-            }
+        float ln[kLossTpt], lo[kLossTpt], a[kLossTpt], v[kLossTpt], vo[kLossTpt], r[kLossTpt];
+        if (my_pol > 0) {
+            load_span(ln, p.logp_new, start + k0, my_pol);
+            load_span(lo, p.logp_old, start + k0, my_pol);
+            load_span(a, p.adv, start + k0, my_pol);
+        }
+        if (my_val > 0) {
+            load_span(v, p.v_new, start + k0, my_val);
+            load_span(vo, p.v_old, start + k0, my_val);
+            load_span(r, p.ret, start + k0, my_val);
+        }
+        if (my_pol > 0) {
 #pragma unroll
             for (int k = 0; k < kLossTpt; ++k) {
                 const float t = surrogate(ln[k], lo[k], a[k], p.ratio_lo, p.ratio_hi);
-                pol_acc += in_pol[k] ? t : 0.f;        // select, never multiply by a mask
+                pol_acc += k < my_pol ? t : 0.f;       // select, never multiply by a mask
             }
         }
-        if (any_val) {
-            float v[kLossTpt], vo[kLossTpt], r[kLossTpt];
-            if (full) {
-                const float4 x = *reinterpret_cast<const float4*>(p.v_new + p0);
-                const float4 y = *reinterpret_cast<const float4*>(p.v_old + p0);
-                const float4 z = *reinterpret_cast<const float4*>(p.ret + p0);
-                v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
-                vo[0] = y.x; vo[1] = y.y; vo[2] = y.z; vo[3] = y.w;
-                r[0] = z.x; r[1] = z.y; r[2] = z.z; r[3] = z.w;
-            } else {
-#pragma unroll
-                for (int k = 0; k < kLossTpt; ++k) {
-                    v[k] = in_val[k] ? p.v_new[p0 + k] : 0.f;
-                    vo[k] = in_val[k] ? p.v_old[p0 + k] : 0.f;
-                    r[k] = in_val[k] ? p.ret[p0 + k] : 0.f;
-                }
-            }
+        if (my_val > 0) {
 #pragma unroll
             for (int k = 0; k < kLossTpt; ++k) {
                 const float t = value_term(v[k], vo[k], r[k], p.xi_low, p.xi_high);
-                val_acc += in_val[k] ? t : 0.f;
+                val_acc += k < my_val ? t : 0.f;
             }
         }
+        cur = nxt;
+        keep = keep_n;
+        fin = fin_n;
     }
     const double ps = block_sum((double)pol_acc, s_red);
     const double vs = block_sum((double)val_acc, s_red);
     if (tid == 0) {
-        partials[2 * blockIdx.x] = ps;
-        partials[2 * blockIdx.x + 1] = vs;
+        ws.partials[2 * blockIdx.x] = ps;
+        ws.partials[2 * blockIdx.x + 1] = vs;
     }
 }
 
-__global__ __launch_bounds__(kLossThreads) void loss_final_kernel(
+__global__ __launch_bounds__(kChunkThreads) void loss_final_kernel(
     const double* __restrict__ partials, int groups, const int32_t* __restrict__ resp_off,
     const int32_t* __restrict__ keep_len, const int32_t* __restrict__ done, int B, int has_pol,
     int has_val, tppo_loss_out* __restrict__ out) {
-    __shared__ double s_red[kLossThreads / kWave];
-    __shared__ long long s_cnt[2][kLossThreads / kWave];
+    __shared__ double s_red[kChunkThreads / kWave];
+    __shared__ long long s_cnt[2][kChunkThreads / kWave];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     double ps = 0.0, vs = 0.0;
-    for (int g = tid; g < groups; g += kLossThreads) {
+    for (int g = tid; g < groups; g += kChunkThreads) {
         ps += partials[2 * g];
         vs += partials[2 * g + 1];
     }
     ps = block_sum(ps, s_red);
     vs = block_sum(vs, s_red);
     long long np = 0, nv = 0;
-    for (int i = tid; i < B; i += kLossThreads) {
+    for (int i = tid; i < B; i += kChunkThreads) {
         const int win = max(resp_off[i + 1] - resp_off[i], 0);
         np += min(max(keep_len[i], 0), win);
         nv += done[i] != 0 ? win : 0;
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(kLossThreads) void loss_final_kernel(
     __syncthreads();
     if (tid == 0) {
         np = nv = 0;
-        for (int w = 0; w < kLossThreads / kWave; ++w) {
+        for (int w = 0; w < kChunkThreads / kWave; ++w) {
             np += s_cnt[0][w];
             nv += s_cnt[1][w];
         }
@@ -213,9 +215,8 @@ __global__ __launch_bounds__(kLossThreads) void loss_final_kernel(
 }  // namespace tppo
 
 extern "C" size_t tppo_ppo_losses_workspace_bytes(int64_t n_resp, int64_t B) {
-    (void)n_resp;
-    (void)B;
-    return (size_t)tppo::kLossMaxGroups * 2 * sizeof(double);
+    if (n_resp < 0 || B < 0) return 256;
+    return tppo::loss_ws_bytes(tppo::max_chunks(n_resp, B));
 }
 
 extern "C" int tppo_ppo_losses(const float* logp_new, const float* logp_old, const float* adv,
@@ -226,8 +227,7 @@ extern "C" int tppo_ppo_losses(const float* logp_new, const float* logp_old, con
                                void* workspace, size_t workspace_bytes, int32_t* status,
                                void* stream) {
     using namespace tppo;
-    (void)status;
-    if (B < 0 || n_resp < 0 || n_resp > INT32_MAX - kLossTile || B > INT32_MAX / 2 - 2) return TPPO_ERR_SIZE;
+    if (B < 0 || n_resp < 0 || n_resp > INT32_MAX - kChunkTokens || B > INT32_MAX / 4) return TPPO_ERR_SIZE;
     if (!(eps_low >= 0.f) || !(eps_high >= 0.f) || !(xi_low >= 0.f) || !(xi_high >= 0.f))
         return TPPO_ERR_PARAM;
     if (!out) return TPPO_ERR_NULL;
@@ -240,31 +240,28 @@ extern "C" int tppo_ppo_losses(const float* logp_new, const float* logp_old, con
         workspace_bytes < tppo_ppo_losses_workspace_bytes(n_resp, B))
         return TPPO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    double* partials = static_cast<double*>(workspace);
-
-    LossParams p;
-    p.logp_new = logp_new; p.logp_old = logp_old; p.adv = adv;
-    p.v_new = v_new; p.v_old = v_old; p.ret = ret;
-    p.resp_off = resp_off; p.keep_len = keep_len; p.done = done;
-    p.B = (int)B; p.n_resp = (int)n_resp;
-    p.tiles = (int)((n_resp + kLossTile - 1) / kLossTile);
-    p.ratio_lo = 1.f - eps_low; p.ratio_hi = 1.f + eps_high;
-    p.xi_low = xi_low; p.xi_high = xi_high;
-    const size_t lds_bytes = (size_t)(2 * B + 1) * sizeof(int32_t);
-    p.use_lds = lds_bytes <= (size_t)kLossMaxLdsBytes;
-    p.vec = 1;
-    const float* arrs[6] = {logp_new, logp_old, adv, v_new, v_old, ret};
-    for (const float* a : arrs)
-        if (a && !is_aligned(a, 16)) p.vec = 0;
+    const int64_t cap64 = max_chunks(n_resp, B);
+    if (cap64 > INT32_MAX / 4) return TPPO_ERR_SIZE;
+    const int cap = (int)cap64;
+    LossWs ws = loss_ws(workspace, cap);
 
     int groups = 0;
-    if (p.tiles > 0 && (n_pol_ptr || n_val_ptr)) {
-        groups = p.tiles < kLossMaxGroups ? p.tiles : kLossMaxGroups;
-        hipLaunchKernelGGL(loss_partial_kernel, dim3(groups), dim3(kLossThreads),
-                           p.use_lds ? lds_bytes : 0, s, p, partials);
+    if (n_resp > 0 && (n_pol_ptr || n_val_ptr)) {
+        hipLaunchKernelGGL(loss_init_kernel, dim3(1), dim3(kBuildThreads), 0, s, resp_off, (int)B,
+                           (int)n_resp, cap, workspace, status);
+        if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
+        LossParams p;
+        p.logp_new = logp_new; p.logp_old = logp_old; p.adv = adv;
+        p.v_new = v_new; p.v_old = v_old; p.ret = ret;
+        p.keep_len = keep_len; p.done = done;
+        p.cap = cap;
+        p.ratio_lo = 1.f - eps_low; p.ratio_hi = 1.f + eps_high;
+        p.xi_low = xi_low; p.xi_high = xi_high;
+        groups = cap < kLossMaxGroups ? cap : kLossMaxGroups;
+        hipLaunchKernelGGL(loss_partial_kernel, dim3(groups), dim3(kChunkThreads), 0, s, p, workspace);
         if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
     }
-    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(kLossThreads), 0, s, partials, groups,
+    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(kChunkThreads), 0, s, ws.partials, groups,
                        resp_off, keep_len, done, (int)B, n_pol_ptr ? 1 : 0, n_val_ptr ? 1 : 0, out);
     return launch_result();
 }
