@@ -28,6 +28,20 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload`, from the committed
+    rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, calibrated on a copy
+    kernel); None when no such summary exists."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -37,6 +51,9 @@ def parse():
                     choices=["small", "head7b", "head32b", "longcot", "longcot5x"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=3072)
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="only run a plain device copy of this many MiB (reference for the "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     return ap.parse_args()
 
 
@@ -50,6 +67,16 @@ def main():
     from paper_2506_15050_amd import binding as tp, synth
 
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        nbytes = args.calibrate_copy << 20
+        src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": nbytes, "calibrate_copy_bytes_written": nbytes,
+                          "launches": 5}))
+        return
     tp.load()
     name = args.workload
     has_head = synth.CONFIGS[name]["V"] > 0
@@ -144,13 +171,15 @@ def main():
         achieved = flops / (stage_ms["logprobs"] * 1e-3) / 1e12
         roofline = dict(bound="mfma", kernel="head_mfma_kernel", achieved=achieved,
                         peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
-                        frac=achieved / MFMA_BF16_PEAK_TFLOPS, traffic=None,
+                        frac=achieved / MFMA_BF16_PEAK_TFLOPS,
+                        traffic=measured_traffic(name, "head_mfma_kernel"),
                         flops_per_launch=flops, avg_ms=stage_ms["logprobs"])
     else:
         nbytes = 16.0 * n_resp
         achieved = nbytes / (stage_ms["egae"] * 1e-3) / 1e9
         roofline = dict(bound="hbm", kernel="egae_scan_kernel", achieved=achieved, peak=HBM_PEAK_GBS,
-                        unit="GB/s", frac=achieved / HBM_PEAK_GBS, traffic=None,
+                        unit="GB/s", frac=achieved / HBM_PEAK_GBS,
+                        traffic=measured_traffic(name, "egae_scan_kernel"),
                         bytes_per_launch=nbytes, avg_ms=stage_ms["egae"])
 
     cpu = None

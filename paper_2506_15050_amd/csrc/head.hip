@@ -111,6 +111,8 @@ struct HeadParams {
     float* part;                       // [3][splits][M]: max (log2 domain), sumexp, target logit
     int64_t n_rows, ld_h, ld_w, M;
     int H, V, row_tiles, splits, vocab_tiles;
+    int unit_splits, unit_cols, n_units;   // persistent schedule, see head_mfma_kernel
+    int32_t* unit_arrivals;                // [n_units] zeroed before the launch
 };
 
 // Compile-time shape of one kernel variant: a kTileV x kTileT (vocabulary x
@@ -165,22 +167,29 @@ __device__ __forceinline__ void dma_16b_per_lane(const void* src, unsigned lds_b
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding)
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
 
-// Workgroup id -> (token tile, vocabulary split).  Consecutive hardware ids go
-// round-robin over the 8 XCDs, so ids are first regrouped into 8 contiguous
-// ranges (one per XCD, each with its own L2); inside a range, 8 token tiles x
-// all splits are adjacent, so the workgroups resident on an XCD share their W
-// tiles (same split, different token tile) and hidden tiles.
-__device__ __forceinline__ void decode_block(int bid, int grid, int row_tiles, int splits, int& rt,
-                                             int& sp) {
-    const int per_xcd = grid / 8;
-    int l = bid;
-    if (bid < per_xcd * 8) l = (bid & 7) * per_xcd + (bid >> 3);
-    const int group = l / (8 * splits), in_group = l - group * 8 * splits;
-    const int rows_here = min(8, row_tiles - group * 8);
-    sp = in_group / rows_here;
-    rt = group * 8 + (in_group - sp * rows_here);
+// Schedule.  The grid is persistent: 256 workgroups, one per CU, hardware id
+// b runs on XCD b % 8 (ids go round-robin over the 8 XCDs, each with its own
+// L2).  The work is cut into units of 8 token tiles x unit_splits (<= 4)
+// vocabulary splits; the 32 workgroups of an XCD take one unit together, one
+// (token tile, split) pair each, then the XCD's next unit.  Inside a unit every
+// W tile is wanted by 8 workgroups and every hidden tile by up to 4 at the same
+// step of the same sweep, so one of them pays the L2 miss and the others hit;
+// equal work per pair keeps them in step for the whole sweep, which a
+// free-running grid of independent workgroups does not.  The splits of a unit
+// may differ by one vocabulary tile, so the workgroups of an XCD re-align at
+// every unit boundary with an arrival counter.  That wait is only a hint for
+// the caches: it is bounded and falls through, and nothing depends on it.
+constexpr int kAlignSpins = 4096;
+__device__ __forceinline__ void align_unit(int32_t* arrivals, int expected) {
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(arrivals, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int spin = 0; spin < kAlignSpins; ++spin) {
+            if (__hip_atomic_load(arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= expected) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+    }
+    __syncthreads();
 }
-
 // Per-lane running log-softmax state of the kTB token columns a lane owns, and
 // the two steps that use it: folding a finished 256-wide vocabulary tile, and
 // the final merge across lane halves / waves.
@@ -321,20 +330,26 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
     constexpr int kDmaPerWave = C::kDmaPerWave, kKSteps = C::kKSteps;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-    int rt, sp;
-    decode_block(blockIdx.x, gridDim.x, p.row_tiles, p.splits, rt, sp);
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int tile_in_unit = slot & 7, split_in_unit = slot >> 3;
+    if (split_in_unit >= p.unit_splits) return;
     const int64_t m_eff = p.m_actual ? min(p.M, *p.m_actual) : p.M;
-    const int64_t tok0 = (int64_t)rt * kTileT;
-    if (tok0 >= m_eff) return;
-
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wv = wave / C::kWavesT, wt = wave % C::kWavesT;
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+
+    for (int unit = xcd; unit < p.n_units; unit += 8) {
+    const int unit_row = unit / p.unit_cols, unit_col = unit - unit_row * p.unit_cols;
+    const int rt = unit_row * 8 + tile_in_unit, sp = unit_col * p.unit_splits + split_in_unit;
+    const int64_t tok0 = (int64_t)rt * kTileT;
+    if (unit >= 8) align_unit(p.unit_arrivals + unit, 8 * p.unit_splits);   // the first unit starts aligned
+    if (rt >= p.row_tiles || tok0 >= m_eff) continue;       // uniform over the workgroup
     const int vt_begin = (int)((int64_t)p.vocab_tiles * sp / p.splits);
     const int vt_end = (int)((int64_t)p.vocab_tiles * (sp + 1) / p.splits);
     const int k_tiles = p.H / kBK;
     const int total_iters = (vt_end - vt_begin) * k_tiles;
-    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
     // ---- loader role: transfers wave*kDmaPerWave + q, each kRowsPerDma staged rows
     const int ld_row0 = wave * kDmaPerWave * C::kRowsPerDma + lane / C::kChunks;   // + q * kRowsPerDma
@@ -383,7 +398,6 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
 
-    const int frag_row = lane & 31, frag_half = lane >> 5;
     bf16x8 fa[2][kVB], fb[2][kTB];
     auto load_frags = [&](int stage, int ks, int buf) {
         const unsigned char* st = smem + stage * C::kStageBytes;
@@ -448,6 +462,13 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
     }
     __syncthreads();                    // every fragment read is done before the stages are reused
     sm.merge_store(p, reinterpret_cast<float*>(smem), tok0, m_eff, sp, wv, wt, lane, tid);
+    __syncthreads();                    // merge buffer is read before the next unit's transfers land
+    }
+}
+
+__global__ __launch_bounds__(256) void head_clear_kernel(int32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
 }
 
 __global__ __launch_bounds__(256) void head_combine_kernel(
@@ -485,7 +506,6 @@ __global__ __launch_bounds__(256) void head_combine_kernel(
 using Cfg0 = HeadCfg<256, 256, 2, 4, 64, 2, 1>;
 using Cfg1 = HeadCfg<256, 256, 2, 4, 32, 4, 1>;
 using Cfg2 = HeadCfg<256, 256, 2, 4, 32, 5, 1>;
-using Cfg3 = HeadCfg<128, 256, 1, 4, 32, 3, 2>;
 
 struct HeadVariant {
     void (*kernel)(HeadParams);
@@ -495,8 +515,7 @@ template <class C>
 constexpr HeadVariant make_variant() {
     return {head_mfma_kernel<C>, C::kTileV, C::kTileT, C::kThreads, C::kLdsBytes, C::kWgsPerCu};
 }
-static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>(), make_variant<Cfg2>(),
-                                        make_variant<Cfg3>()};
+static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>(), make_variant<Cfg2>()};
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 static const HeadVariant& pick_variant() {
@@ -506,25 +525,27 @@ static const HeadVariant& pick_variant() {
     return kVariants[id];
 }
 
-// Number of vocabulary splits: minimise rounds x tiles-per-split over the 256
-// CUs, with a small per-workgroup overhead.  The ~32 workgroups resident on an
-// XCD are 8 token tiles x 4 splits when the split count is a multiple of 4; that
-// shape shares every W tile 8 ways and every hidden tile 4 ways in the XCD's L2
-// (measured ~8 % faster than 2 splits), hence the penalty on other counts.
+// Number of vocabulary splits.  A unit is 8 token tiles x min(splits, 4) splits
+// and every XCD works through ceil(units / 8) units of ceil(vocab_tiles /
+// splits) vocabulary tiles each; pick the count (1, 2, 3 or a multiple of 4)
+// that minimises that product, with a small per-unit overhead.
 static int choose_splits(const HeadVariant& hv, int64_t M, int64_t V) {
     const int64_t row_tiles = (M + hv.tile_t - 1) / hv.tile_t, vocab_tiles = (V + hv.tile_v - 1) / hv.tile_v;
-    const int64_t slots = 256 * hv.wgs_per_cu;
-    int best = 1;
-    double best_cost = 1e300;
+    const int64_t unit_rows = (row_tiles + 7) / 8;
     const int max_s = (int)(vocab_tiles < kMaxSplits ? vocab_tiles : kMaxSplits);
     if (const char* e = getenv("TPPO_HEAD_SPLITS")) {       // tuning override
         const int forced = atoi(e);
-        if (forced >= 1) return forced < max_s ? forced : max_s;
+        if (forced >= 1 && (forced < 4 || forced % 4 == 0)) return forced < max_s ? forced : max_s < 4 ? max_s : max_s / 4 * 4;
     }
+    int best = 1;
+    double best_cost = 1e300;
     for (int s = 1; s <= max_s; ++s) {
-        const double rounds = (double)((row_tiles * s + slots - 1) / slots);
+        if (s > 4 && s % 4 != 0) continue;
+        const int64_t units = unit_rows * (s <= 4 ? 1 : s / 4);
+        const double rounds = (double)((units + 7) / 8);
         const double per = (double)((vocab_tiles + s - 1) / s) + 0.25;
-        const double cost = rounds * per * (s % 4 == 0 ? 1.0 : 1.08);
+        // fewer than 4 splits leave CUs idle: 8*s of the 32 workgroups of an XCD work
+        const double cost = rounds * per;
         if (cost < best_cost - 1e-9) {
             best_cost = cost;
             best = s;
@@ -532,6 +553,9 @@ static int choose_splits(const HeadVariant& hv, int64_t M, int64_t V) {
     }
     return best;
 }
+
+// arrival counters of the persistent schedule: one per unit, at the end of the workspace
+static size_t arrivals_bytes(int64_t M) { return round_up((size_t)((M / 256 / 8 + 2) * (kMaxSplits / 4)) * 4, 256); }
 
 static bool mfma_eligible(const void* hidden, int64_t H, int64_t ld_h, const void* w, int64_t ld_w,
                           tppo_dtype dt) {
@@ -551,7 +575,7 @@ extern "C" size_t tppo_token_logprobs_workspace_bytes(int64_t M, int64_t H, int6
         const size_t n = (size_t)3 * (size_t)choose_splits(hv, M, V) * (size_t)M * sizeof(float);
         need = n > need ? n : need;
     }
-    return round_up(need, 256);
+    return round_up(need, 256) + arrivals_bytes(M);
 }
 
 extern "C" int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H, int64_t ld_hidden,
@@ -586,8 +610,8 @@ extern "C" int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H
         return launch_result();
     }
 
-    if (!workspace || !is_aligned(workspace, 256) ||
-        workspace_bytes < tppo_token_logprobs_workspace_bytes(M, H, V, dt))
+    const size_t workspace_bytes_needed = tppo_token_logprobs_workspace_bytes(M, H, V, dt);
+    if (!workspace || !is_aligned(workspace, 256) || workspace_bytes < workspace_bytes_needed)
         return TPPO_ERR_WORKSPACE;
     HeadParams p;
     p.hidden = static_cast<const uint16_t*>(hidden);
@@ -602,10 +626,16 @@ extern "C" int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H
     p.row_tiles = (int)((M + hv.tile_t - 1) / hv.tile_t);
     p.vocab_tiles = (int)((V + hv.tile_v - 1) / hv.tile_v);
     p.splits = choose_splits(hv, M, V);
+    p.unit_splits = p.splits < 4 ? p.splits : 4;
+    p.unit_cols = p.splits / p.unit_splits;
+    p.n_units = ((p.row_tiles + 7) / 8) * p.unit_cols;
+    p.unit_arrivals = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + workspace_bytes_needed - arrivals_bytes(M));
+    hipLaunchKernelGGL(head_clear_kernel, dim3((p.n_units + 255) / 256), dim3(256), 0, s, p.unit_arrivals, p.n_units);
+    if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(hv.kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, hv.lds_bytes) != hipSuccess)
         return TPPO_ERR_LAUNCH;
-    const int grid = p.row_tiles * p.splits;
+    const int grid = 256;                                   // persistent: one workgroup per CU
     hipLaunchKernelGGL(hv.kernel, dim3(grid), dim3(hv.threads), hv.lds_bytes, s, p);
     if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
     hipLaunchKernelGGL(head_combine_kernel, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, s, p.part,
