@@ -93,16 +93,20 @@ int tppo_version(void);
  *      sel_resp_idx: `capacity` int32 each (each may be NULL = not wanted;
  *      n_tok is always a sufficient capacity); counts[3] int64 =
  *      { M = sel_off[B], n_resp = resp_off[B], N_val = number of value tokens }.
+ *      workspace: tppo_select_workspace_bytes(B, max(capacity, n_tok)) bytes; only
+ *      needed (may be NULL otherwise) when one of the three index arrays is wanted.
  * Errors: NULL required pointer, B < 0, n_tok < 0, capacity < 0 ->
  *      TPPO_ERR_NULL / TPPO_ERR_SIZE; tail_drop < 0 -> TPPO_ERR_PARAM.
  *      B = 0 is valid (counts = 0).  Sequences with a bad layout set
  *      TPPO_STATUS_BAD_LAYOUT and are treated as having an empty window.
  */
+size_t tppo_select_workspace_bytes(int64_t B, int64_t capacity);
 int tppo_select(const int32_t* cu_seqlens, const int32_t* ctx_len, const int32_t* done,
                 const int32_t* input_ids, int64_t B, int64_t n_tok, int32_t tail_drop,
                 int32_t* resp_off, int32_t* sel_off, int32_t* keep_len,
                 int32_t* sel_rows, int32_t* sel_targets, int32_t* sel_resp_idx,
-                int64_t capacity, int64_t* counts, int32_t* status, void* stream);
+                int64_t capacity, int64_t* counts, void* workspace, size_t workspace_bytes,
+                int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------
  * tppo_token_logprobs -- log-probability of each kept token under the current

@@ -21,8 +21,9 @@ _c_i64, _c_i32, _c_f32, _c_ptr, _c_size = (ctypes.c_int64, ctypes.c_int32, ctype
                                             ctypes.c_void_p, ctypes.c_size_t)
 _SIGNATURES = {
     "tppo_version": (ctypes.c_int, []),
+    "tppo_select_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
     "tppo_select": (ctypes.c_int, [_c_ptr] * 4 + [_c_i64, _c_i64, _c_i32] + [_c_ptr] * 6 +
-                    [_c_i64, _c_ptr, _c_ptr, _c_ptr]),
+                    [_c_i64, _c_ptr, _c_ptr, _c_size, _c_ptr, _c_ptr]),
     "tppo_token_logprobs_workspace_bytes": (_c_size, [_c_i64, _c_i64, _c_i64, ctypes.c_int]),
     "tppo_token_logprobs": (ctypes.c_int, [_c_ptr, _c_i64, _c_i64, _c_i64, _c_ptr, _c_i64, _c_i64,
                                            ctypes.c_int, _c_ptr, _c_ptr, _c_i64, _c_ptr, _c_ptr,
@@ -85,7 +86,7 @@ def new_status(device):
 
 
 def tppo_select(cu_seqlens, ctx_len, done, input_ids, tail_drop, capacity=None, status=None,
-                want_indices=True, n_tok=None):
+                want_indices=True, n_tok=None, workspace=None):
     """Token filter.  Returns a dict of device tensors: resp_off, sel_off, keep_len,
     sel_rows, sel_targets, sel_resp_idx (capacity-sized) and counts (int64[3] =
     M, n_resp, N_val)."""
@@ -105,12 +106,15 @@ def tppo_select(cu_seqlens, ctx_len, done, input_ids, tail_drop, capacity=None, 
             out[k] = torch.empty(cap, dtype=torch.int32, device=dev)
         if input_ids is None:
             out["sel_targets"] = None
+    ws = workspace
+    if ws is None and want_indices:
+        ws = _workspace(lib.tppo_select_workspace_bytes(B, max(cap, n_tok)), dev)
     rc = lib.tppo_select(_ptr(_dev_i32(cu_seqlens)), _ptr(_dev_i32(ctx_len)), _ptr(_dev_i32(done)),
                          _ptr(input_ids), B, n_tok, int(tail_drop),
                          _ptr(out["resp_off"]), _ptr(out["sel_off"]), _ptr(out["keep_len"]),
                          _ptr(out.get("sel_rows")), _ptr(out.get("sel_targets")),
-                         _ptr(out.get("sel_resp_idx")), cap, _ptr(out["counts"]), _ptr(status),
-                         _stream())
+                         _ptr(out.get("sel_resp_idx")), cap, _ptr(out["counts"]), _ptr(ws),
+                         0 if ws is None else ws.numel(), _ptr(status), _stream())
     _check(rc, "tppo_select")
     return out
 

@@ -120,30 +120,58 @@ constexpr int kTpt = kChunkTokens / kEgaeThreads;       // the per-wavefront sca
 constexpr int kEgaeWaves = kEgaeThreads / kWave;
 constexpr int kEgaeMaxGroups = 1536;                    // 6 workgroups per CU: all co-resident (<= 168 VGPRs)
 
-struct TokenRegs { float r[kTpt], v[kTpt], v_after; };
+struct TokenRegs { float r[kTpt], v[kTpt]; };
 
-// the kTpt tokens of thread `tid` in a chunk (chunk starts are only 4-byte aligned)
-__device__ __forceinline__ void load_tokens(TokenRegs& t, const float* __restrict__ rewards,
-                                            const float* __restrict__ values, int start, int len, int tid) {
-    const int k0 = tid * kTpt;
-    if (k0 + kTpt <= len) {
+// Global memory is streamed with consecutive lanes on consecutive 16 bytes (the
+// shape that runs at copy speed); the scan wants kTpt consecutive tokens per
+// thread.  The two layouts are exchanged through LDS.  A thread's kTpt floats
+// occupy 80 bytes there (64 + 16 of padding), which makes both the 16-byte
+// writes in token order and the 16-byte reads in thread order conflict-free.
+constexpr int kLdsRun = kTpt + 4;                          // floats per thread run, padded
+constexpr int kLdsArray = kEgaeThreads * kLdsRun;          // floats per staged array
+constexpr int kGroups = kChunkTokens / (4 * kEgaeThreads); // 16-byte groups per thread and array: 4
+
+__device__ __forceinline__ int lds_slot(int token) { return (token / kTpt) * kLdsRun + (token % kTpt); }
+
+struct Raw { float4u r[kGroups], v[kGroups]; float v_after; };
+
+// issue the global loads of a chunk: group g of thread tid = tokens g*512 + tid*4 .. +3
+__device__ __forceinline__ void load_raw(Raw& x, const float* __restrict__ rewards,
+                                         const float* __restrict__ values, int start, int len, int tid) {
 #pragma unroll
-        for (int q = 0; q < kTpt / 4; ++q) {
-            const float4u rr = *reinterpret_cast<const float4u*>(rewards + start + k0 + 4 * q);
-            const float4u vv = *reinterpret_cast<const float4u*>(values + start + k0 + 4 * q);
+    for (int g = 0; g < kGroups; ++g) {
+        const int k0 = g * 4 * kEgaeThreads + tid * 4;
+        if (k0 + 4 <= len) {
+            x.r[g] = *reinterpret_cast<const float4u*>(rewards + start + k0);
+            x.v[g] = *reinterpret_cast<const float4u*>(values + start + k0);
+        } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                t.r[4 * q + e] = rr[e];
-                t.v[4 * q + e] = vv[e];
+                const bool ok = k0 + e < len;
+                x.r[g][e] = ok ? rewards[start + k0 + e] : 0.f;
+                x.v[g][e] = ok ? values[start + k0 + e] : 0.f;
             }
         }
-    } else {
+    }
+}
+
+// token order -> LDS (call, then __syncthreads, then read_runs)
+__device__ __forceinline__ void stage_raw(const Raw& x, float* s_r, float* s_v, int tid) {
 #pragma unroll
-        for (int k = 0; k < kTpt; ++k) {
-            const bool ok = k0 + k < len;
-            t.r[k] = ok ? rewards[start + k0 + k] : 0.f;
-            t.v[k] = ok ? values[start + k0 + k] : 0.f;
-        }
+    for (int g = 0; g < kGroups; ++g) {
+        const int slot = lds_slot(g * 4 * kEgaeThreads + tid * 4);
+        *reinterpret_cast<float4*>(s_r + slot) = make_float4(x.r[g][0], x.r[g][1], x.r[g][2], x.r[g][3]);
+        *reinterpret_cast<float4*>(s_v + slot) = make_float4(x.v[g][0], x.v[g][1], x.v[g][2], x.v[g][3]);
+    }
+}
+
+__device__ __forceinline__ void read_runs(TokenRegs& t, const float* s_r, const float* s_v, int tid) {
+#pragma unroll
+    for (int q = 0; q < kTpt / 4; ++q) {
+        const float4 rr = *reinterpret_cast<const float4*>(s_r + tid * kLdsRun + 4 * q);
+        const float4 vv = *reinterpret_cast<const float4*>(s_v + tid * kLdsRun + 4 * q);
+        t.r[4 * q] = rr.x; t.r[4 * q + 1] = rr.y; t.r[4 * q + 2] = rr.z; t.r[4 * q + 3] = rr.w;
+        t.v[4 * q] = vv.x; t.v[4 * q + 1] = vv.y; t.v[4 * q + 2] = vv.z; t.v[4 * q + 3] = vv.w;
     }
 }
 
@@ -180,8 +208,7 @@ __device__ __forceinline__ double powi(double x, int n) {
 // chunk, its map starts from a = 0 (set by the caller) and its V(s_{t+1}) is v_right.
 template <bool kFull, bool kStore>
 __device__ __forceinline__ void walk_tokens(const TokenRegs& tk, int n_mine, float v_right, double gamma,
-                                            double c, Affine& fa, Affine& fr, float (&out_a)[kTpt],
-                                            float (&out_r)[kTpt]) {
+                                            double c, Affine& fa, Affine& fr, float* out_a, float* out_r) {
     double v_next = (double)v_right;
 #pragma unroll
     for (int k = kTpt - 1; k >= 0; --k) {
@@ -208,6 +235,8 @@ __global__ __launch_bounds__(kEgaeThreads, 3) void egae_scan_kernel(
     const int32_t* __restrict__ done, const float* __restrict__ bootstrap, int n_resp, int cap,
     double gamma, double c, double gamma_pow_chunk, double c_pow_chunk, float* __restrict__ adv,
     float* __restrict__ ret, void* ws_raw, int32_t* status) {
+    __shared__ __attribute__((aligned(16))) float s_r[kLdsArray];      // rewards in, advantages out
+    __shared__ __attribute__((aligned(16))) float s_v[kLdsArray];      // values in, returns out
     __shared__ float s_v0[kEgaeThreads + 1];
     __shared__ Affine s_wave[2][kEgaeWaves];
     __shared__ double s_carry[2];
@@ -219,27 +248,31 @@ __global__ __launch_bounds__(kEgaeThreads, 3) void egae_scan_kernel(
     if (w >= count) return;
 
     Chunk cur = ws.chunks[w];
-    TokenRegs tk;
-    load_tokens(tk, rewards, values, cur.start, cur.len(), tid);
-    tk.v_after = load_v_after(cur, values, done, bootstrap, tid);
+    Raw raw;
+    load_raw(raw, rewards, values, cur.start, cur.len(), tid);
+    raw.v_after = load_v_after(cur, values, done, bootstrap, tid);
 
     for (; w < count; w += gridDim.x) {
         const int start = cur.start, len = cur.len(), k0 = tid * kTpt;
         const int n_mine = min(max(len - k0, 0), kTpt);          // my tokens that exist
-        // ---- start the next chunk's loads before touching this one's data
+        // ---- this chunk's data: token order -> LDS -> kTpt consecutive tokens per thread
+        stage_raw(raw, s_r, s_v, tid);
+        if (tid == kEgaeThreads - 1) s_v0[kEgaeThreads] = raw.v_after;
+        __syncthreads();
+        TokenRegs tk;
+        read_runs(tk, s_r, s_v, tid);
+        // ---- start the next chunk's loads before working on this one
         const int w_next = w + gridDim.x;
         Chunk nxt = cur;
-        TokenRegs tn;
         if (w_next < count) {
             nxt = ws.chunks[w_next];
-            load_tokens(tn, rewards, values, nxt.start, nxt.len(), tid);
-            tn.v_after = load_v_after(nxt, values, done, bootstrap, tid);
+            load_raw(raw, rewards, values, nxt.start, nxt.len(), tid);
+            raw.v_after = load_v_after(nxt, values, done, bootstrap, tid);
         }
 
         // ---- V(s_{t+1}) of my last token: my right neighbour's first value, or for
         // the owner of the chunk's last token the value after the chunk
         s_v0[tid] = tk.v[0];
-        if (tid == kEgaeThreads - 1) s_v0[kEgaeThreads] = tk.v_after;
         __syncthreads();
         const bool owns_last = n_mine > 0 && k0 + n_mine == len;
         const float v_right = owns_last ? s_v0[kEgaeThreads] : s_v0[tid + 1];
@@ -247,7 +280,8 @@ __global__ __launch_bounds__(kEgaeThreads, 3) void egae_scan_kernel(
         // ---- pass 1: my tokens as one affine map of the value carried in from the right
         const double a0 = (owns_last && cur.after == 0) ? 0.0 : 1.0;   // nothing is carried past a sequence's end
         Affine fa = {a0, 0.0}, fr = {a0, 0.0};
-        float out_a[kTpt], out_r[kTpt];
+        float* out_a = s_r + tid * kLdsRun;                      // my run in LDS: inputs are in registers by now
+        float* out_r = s_v + tid * kLdsRun;
         if (len == kChunkTokens) walk_tokens<true, false>(tk, n_mine, v_right, gamma, c, fa, fr, out_a, out_r);
         else walk_tokens<false, false>(tk, n_mine, v_right, gamma, c, fa, fr, out_a, out_r);
 
@@ -322,29 +356,33 @@ __global__ __launch_bounds__(kEgaeThreads, 3) void egae_scan_kernel(
         }
         if (len == kChunkTokens) walk_tokens<true, true>(tk, n_mine, v_right, gamma, c, va, vr, out_a, out_r);
         else walk_tokens<false, true>(tk, n_mine, v_right, gamma, c, va, vr, out_a, out_r);
-        if (n_mine == kTpt) {
+        // ---- results (written to my LDS run by pass 2): thread order -> token order -> global
+        __syncthreads();
 #pragma unroll
-            for (int q = 0; q < kTpt / 4; ++q) {
-                float4u oa, orr;
+        for (int g = 0; g < kGroups; ++g) {
+            const int k0 = g * 4 * kEgaeThreads + tid * 4;
+            const int slot = lds_slot(k0);
+            const float4 oa = *reinterpret_cast<const float4*>(s_r + slot);
+            const float4 orr = *reinterpret_cast<const float4*>(s_v + slot);
+            if (k0 + 4 <= len) {
+                float4u ua, ur;
+                ua[0] = oa.x; ua[1] = oa.y; ua[2] = oa.z; ua[3] = oa.w;
+                ur[0] = orr.x; ur[1] = orr.y; ur[2] = orr.z; ur[3] = orr.w;
+                *reinterpret_cast<float4u*>(adv + start + k0) = ua;
+                *reinterpret_cast<float4u*>(ret + start + k0) = ur;
+            } else {
+                const float ea_[4] = {oa.x, oa.y, oa.z, oa.w}, er_[4] = {orr.x, orr.y, orr.z, orr.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    oa[e] = out_a[4 * q + e];
-                    orr[e] = out_r[4 * q + e];
-                }
-                *reinterpret_cast<float4u*>(adv + start + k0 + 4 * q) = oa;
-                *reinterpret_cast<float4u*>(ret + start + k0 + 4 * q) = orr;
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < kTpt; ++k) {
-                if (k < n_mine) {
-                    adv[start + k0 + k] = out_a[k];
-                    ret[start + k0 + k] = out_r[k];
+                    if (k0 + e < len) {
+                        adv[start + k0 + e] = ea_[e];
+                        ret[start + k0 + e] = er_[e];
+                    }
                 }
             }
         }
+        __syncthreads();                                        // s_r / s_v are refilled by the next chunk
         cur = nxt;
-        tk = tn;
     }
 }
 

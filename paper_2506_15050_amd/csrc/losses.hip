@@ -13,7 +13,6 @@
 namespace tppo {
 
 constexpr int kLossMaxGroups = 2048;
-constexpr int kLossTpt = kChunkTpt;
 
 struct LossWs {
     Chunk* chunks;        // [cap]
@@ -80,28 +79,27 @@ __device__ __forceinline__ double block_sum(double x, double* s_red) {
     return t;   // valid in thread 0
 }
 
-// `n` tokens of `src` starting at `first` into x[]; only if the thread has any
-__device__ __forceinline__ void load_span(float (&x)[kLossTpt], const float* __restrict__ src, int first,
-                                          int n) {
-    if (n >= kLossTpt) {
+// Four consecutive tokens per access, consecutive lanes on consecutive 16 bytes
+// (the access shape that streams at copy speed).  `n` = how many of the four are
+// in the set; nothing is loaded for n = 0.
+__device__ __forceinline__ void load4(float (&x)[4], const float* __restrict__ src, int first, int n) {
+    if (n >= 4) {
+        const float4u t = *reinterpret_cast<const float4u*>(src + first);
 #pragma unroll
-        for (int q = 0; q < kLossTpt / 4; ++q) {
-            const float4u t = *reinterpret_cast<const float4u*>(src + first + 4 * q);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) x[4 * q + e] = t[e];
-        }
+        for (int e = 0; e < 4; ++e) x[e] = t[e];
     } else {
 #pragma unroll
-        for (int k = 0; k < kLossTpt; ++k) x[k] = k < n ? src[first + k] : 0.f;
+        for (int e = 0; e < 4; ++e) x[e] = e < n ? src[first + e] : 0.f;
     }
 }
 
 __global__ __launch_bounds__(kChunkThreads) void loss_partial_kernel(LossParams p, void* ws_raw) {
     __shared__ double s_red[kChunkThreads / kWave];
     LossWs ws = loss_ws(ws_raw, p.cap);
-    const int tid = threadIdx.x, k0 = tid * kLossTpt;
+    const int tid = threadIdx.x;
     const bool has_pol = p.logp_new != nullptr, has_val = p.v_new != nullptr;
     const int count = *ws.n_chunks;
+    constexpr int kGroups = kChunkTokens / (4 * kChunkThreads);      // 16-byte groups per thread: 2
 
     float pol_acc = 0.f, val_acc = 0.f;
     int w = blockIdx.x;
@@ -116,8 +114,6 @@ __global__ __launch_bounds__(kChunkThreads) void loss_partial_kernel(LossParams 
         // tokens of this chunk in the policy set: window positions below keep_len
         const int pol_in_chunk = has_pol ? min(max(keep - cur.number() * kChunkTokens, 0), len) : 0;
         const int val_in_chunk = (has_val && fin != 0) ? len : 0;
-        const int my_pol = min(max(pol_in_chunk - k0, 0), kLossTpt);
-        const int my_val = min(max(val_in_chunk - k0, 0), kLossTpt);
         // metadata of the next chunk: in flight while this one streams
         const int w_next = w + gridDim.x;
         Chunk nxt = cur;
@@ -127,29 +123,39 @@ __global__ __launch_bounds__(kChunkThreads) void loss_partial_kernel(LossParams 
             keep_n = p.keep_len[nxt.seg];
             fin_n = p.done[nxt.seg];
         }
-        float ln[kLossTpt], lo[kLossTpt], a[kLossTpt], v[kLossTpt], vo[kLossTpt], r[kLossTpt];
-        if (my_pol > 0) {
-            load_span(ln, p.logp_new, start + k0, my_pol);
-            load_span(lo, p.logp_old, start + k0, my_pol);
-            load_span(a, p.adv, start + k0, my_pol);
-        }
-        if (my_val > 0) {
-            load_span(v, p.v_new, start + k0, my_val);
-            load_span(vo, p.v_old, start + k0, my_val);
-            load_span(r, p.ret, start + k0, my_val);
-        }
-        if (my_pol > 0) {
+        float ln[kGroups][4], lo[kGroups][4], a[kGroups][4], v[kGroups][4], vo[kGroups][4], r[kGroups][4];
+        int n_pol[kGroups], n_val[kGroups];
 #pragma unroll
-            for (int k = 0; k < kLossTpt; ++k) {
-                const float t = surrogate(ln[k], lo[k], a[k], p.ratio_lo, p.ratio_hi);
-                pol_acc += k < my_pol ? t : 0.f;       // select, never multiply by a mask
+        for (int g = 0; g < kGroups; ++g) {
+            const int k0 = g * 4 * kChunkThreads + tid * 4;
+            n_pol[g] = min(max(pol_in_chunk - k0, 0), 4);
+            n_val[g] = min(max(val_in_chunk - k0, 0), 4);
+            if (n_pol[g] > 0) {
+                load4(ln[g], p.logp_new, start + k0, n_pol[g]);
+                load4(lo[g], p.logp_old, start + k0, n_pol[g]);
+                load4(a[g], p.adv, start + k0, n_pol[g]);
+            }
+            if (n_val[g] > 0) {
+                load4(v[g], p.v_new, start + k0, n_val[g]);
+                load4(vo[g], p.v_old, start + k0, n_val[g]);
+                load4(r[g], p.ret, start + k0, n_val[g]);
             }
         }
-        if (my_val > 0) {
 #pragma unroll
-            for (int k = 0; k < kLossTpt; ++k) {
-                const float t = value_term(v[k], vo[k], r[k], p.xi_low, p.xi_high);
-                val_acc += k < my_val ? t : 0.f;
+        for (int g = 0; g < kGroups; ++g) {
+            if (n_pol[g] > 0) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float t = surrogate(ln[g][e], lo[g][e], a[g][e], p.ratio_lo, p.ratio_hi);
+                    pol_acc += e < n_pol[g] ? t : 0.f;     // select, never multiply by a mask
+                }
+            }
+            if (n_val[g] > 0) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float t = value_term(v[g][e], vo[g][e], r[g][e], p.xi_low, p.xi_high);
+                    val_acc += e < n_val[g] ? t : 0.f;
+                }
             }
         }
         cur = nxt;

@@ -1,37 +1,44 @@
 // tppo_select: token filter of Sec. 3.2 as a segmented compaction.
-//   kernel 1 (one workgroup): per-sequence window / keep lengths and their
-//            prefix sums (resp_off, sel_off), counts;
-//   kernel 2: one thread per compact slot m: locate its sequence in sel_off
-//            and emit (row, target id, response-packed index).
-#include "common.h"
+//   kernel 1 (one workgroup): per-sequence window / keep lengths, their prefix
+//            sums (resp_off, sel_off), the counts, and a list of chunks of the
+//            compact output (<= 2048 kept tokens of one sequence each);
+//   kernel 2 (persistent grid): walks the chunk list; a chunk's descriptor says
+//            which sequence and which window positions it covers, so every
+//            thread emits (row, target id, response-packed index) for 8
+//            consecutive kept tokens without searching the offset arrays.
+#include "chunks.h"
 
 namespace tppo {
 
 constexpr int kScanThreads = 1024;
+constexpr int kFillMaxGroups = 2048;
 
-struct Triple { int win, keep, val; };
+struct Quad { int win, keep, val, chunks; };
 
-__device__ __forceinline__ Triple add3(Triple a, Triple b) {
-    return {a.win + b.win, a.keep + b.keep, a.val + b.val};
+__device__ __forceinline__ Quad add4(Quad a, Quad b) {
+    return {a.win + b.win, a.keep + b.keep, a.val + b.val, a.chunks + b.chunks};
 }
+
+static inline int64_t select_max_chunks(int64_t capacity, int64_t B) { return capacity / kChunkTokens + B + 1; }
 
 __global__ __launch_bounds__(kScanThreads) void select_scan_kernel(
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ ctx_len,
     const int32_t* __restrict__ done, int B, int n_tok, int tail_drop,
     int32_t* __restrict__ resp_off, int32_t* __restrict__ sel_off,
-    int32_t* __restrict__ keep_len, int64_t* __restrict__ counts, int32_t* status) {
-    __shared__ Triple wave_tot[kScanThreads / kWave];
-    __shared__ Triple carry_s;
+    int32_t* __restrict__ keep_len, int64_t* __restrict__ counts, Chunk* __restrict__ chunks,
+    int chunk_cap, int32_t* __restrict__ n_chunks, int32_t* status) {
+    __shared__ Quad wave_tot[kScanThreads / kWave];
+    __shared__ Quad carry_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) {
-        carry_s = {0, 0, 0};
+        carry_s = {0, 0, 0, 0};
         resp_off[0] = 0;
         sel_off[0] = 0;
     }
     __syncthreads();
     for (int base = 0; base < B; base += kScanThreads) {
         const int i = base + tid;
-        Triple x = {0, 0, 0};
+        Quad x = {0, 0, 0, 0};
         if (i < B) {
             const int lo = cu_seqlens[i], hi = cu_seqlens[i + 1], ctx = ctx_len[i];
             int win = hi - lo - ctx;
@@ -42,23 +49,35 @@ __global__ __launch_bounds__(kScanThreads) void select_scan_kernel(
             const bool fin = done[i] != 0;
             const int keep = fin ? win : max(win - tail_drop, 0);
             keep_len[i] = keep;
-            x = {win, keep, fin ? win : 0};
+            x = {win, keep, fin ? win : 0, (keep + kChunkTokens - 1) / kChunkTokens};
         }
         // inclusive scan inside the wave
-        Triple inc = x;
+        Quad inc = x;
 #pragma unroll
         for (int off = 1; off < kWave; off <<= 1) {
-            Triple y = {__shfl_up(inc.win, off), __shfl_up(inc.keep, off), __shfl_up(inc.val, off)};
-            if (lane >= off) inc = add3(inc, y);
+            Quad y = {__shfl_up(inc.win, off), __shfl_up(inc.keep, off), __shfl_up(inc.val, off),
+                      __shfl_up(inc.chunks, off)};
+            if (lane >= off) inc = add4(inc, y);
         }
         if (lane == kWave - 1) wave_tot[wave] = inc;
         __syncthreads();
-        Triple pre = carry_s;
-        for (int w = 0; w < wave; ++w) pre = add3(pre, wave_tot[w]);
-        inc = add3(inc, pre);
+        Quad pre = carry_s;
+        for (int w = 0; w < wave; ++w) pre = add4(pre, wave_tot[w]);
+        inc = add4(inc, pre);
         if (i < B) {
             resp_off[i + 1] = inc.win;
             sel_off[i + 1] = inc.keep;
+            if (chunks) {
+                const int first = inc.chunks - x.chunks, m0 = inc.keep - x.keep;
+                for (int c = 0; c < x.chunks; ++c) {
+                    Chunk d;
+                    d.start = m0 + c * kChunkTokens;
+                    d.pos_len = (c << 11) | (min(kChunkTokens, x.keep - c * kChunkTokens) - 1);
+                    d.seg = i;
+                    d.after = x.chunks - 1 - c;
+                    if (first + c < chunk_cap) chunks[first + c] = d;
+                }
+            }
         }
         __syncthreads();
         if (tid == kScanThreads - 1) carry_s = inc;
@@ -68,54 +87,81 @@ __global__ __launch_bounds__(kScanThreads) void select_scan_kernel(
         counts[0] = carry_s.keep;
         counts[1] = carry_s.win;
         counts[2] = carry_s.val;
+        if (n_chunks) n_chunks[0] = min(carry_s.chunks, chunk_cap);
     }
 }
 
-__global__ __launch_bounds__(256) void select_fill_kernel(
+__global__ __launch_bounds__(kChunkThreads) void select_fill_kernel(
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ ctx_len,
-    const int32_t* __restrict__ input_ids, int B, int n_tok,
-    const int32_t* __restrict__ resp_off, const int32_t* __restrict__ sel_off,
+    const int32_t* __restrict__ input_ids, int n_tok, const int32_t* __restrict__ resp_off,
+    const Chunk* __restrict__ chunks, const int32_t* __restrict__ n_chunks,
     int32_t* __restrict__ sel_rows, int32_t* __restrict__ sel_targets,
     int32_t* __restrict__ sel_resp_idx, int64_t capacity, int32_t* status) {
-    const int64_t m = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int M = sel_off[B];
-    if (m >= M) return;
-    if (m >= capacity) {
-        if (m == capacity) set_status(status, TPPO_STATUS_CAPACITY);
-        return;
+    const int count = *n_chunks;
+    const int tid = threadIdx.x;
+    for (int w = blockIdx.x; w < count; w += gridDim.x) {
+        const Chunk ch = chunks[w];
+        const int i = ch.seg, len = ch.len(), t0 = ch.number() * kChunkTokens;
+        const int first_pos = cu_seqlens[i] + ctx_len[i] + t0;      // packed position of the chunk's first token
+        const int first_resp = resp_off[i] + t0;
+#pragma unroll
+        for (int q = 0; q < kChunkTpt; ++q) {
+            const int k = q * kChunkThreads + tid;                   // lane-consecutive: coalesced stores
+            const int64_t m = (int64_t)ch.start + k;
+            if (k < len) {
+                if (m >= capacity) {
+                    if (m == capacity) set_status(status, TPPO_STATUS_CAPACITY);
+                } else {
+                    const int pos = first_pos + k;
+                    if (sel_rows) sel_rows[m] = pos - 1;
+                    if (sel_targets) sel_targets[m] = (pos >= 0 && pos < n_tok) ? input_ids[pos] : -1;
+                    if (sel_resp_idx) sel_resp_idx[m] = first_resp + k;
+                }
+            }
+        }
     }
-    const int i = find_segment(sel_off, 0, B - 1, (int)m);
-    const int t = (int)m - sel_off[i];
-    const int pos = cu_seqlens[i] + ctx_len[i] + t;
-    if (sel_rows) sel_rows[m] = pos - 1;
-    if (sel_targets) sel_targets[m] = (pos >= 0 && pos < n_tok) ? input_ids[pos] : -1;
-    if (sel_resp_idx) sel_resp_idx[m] = resp_off[i] + t;
 }
 
 }  // namespace tppo
+
+extern "C" size_t tppo_select_workspace_bytes(int64_t B, int64_t capacity) {
+    if (B < 0 || capacity < 0) return 256;
+    return tppo::round_up((size_t)tppo::select_max_chunks(capacity, B) * sizeof(tppo::Chunk), 256) + 256;
+}
 
 extern "C" int tppo_select(const int32_t* cu_seqlens, const int32_t* ctx_len, const int32_t* done,
                            const int32_t* input_ids, int64_t B, int64_t n_tok, int32_t tail_drop,
                            int32_t* resp_off, int32_t* sel_off, int32_t* keep_len,
                            int32_t* sel_rows, int32_t* sel_targets, int32_t* sel_resp_idx,
-                           int64_t capacity, int64_t* counts, int32_t* status, void* stream) {
+                           int64_t capacity, int64_t* counts, void* workspace, size_t workspace_bytes,
+                           int32_t* status, void* stream) {
     using namespace tppo;
-    if (B < 0 || n_tok < 0 || capacity < 0 || B > INT32_MAX - 1 || n_tok > INT32_MAX) return TPPO_ERR_SIZE;
+    if (B < 0 || n_tok < 0 || capacity < 0 || B > INT32_MAX / 4 || n_tok > INT32_MAX) return TPPO_ERR_SIZE;
     if (tail_drop < 0) return TPPO_ERR_PARAM;
     if (!cu_seqlens || !resp_off || !sel_off || !counts) return TPPO_ERR_NULL;
     if (B > 0 && (!ctx_len || !done || !keep_len)) return TPPO_ERR_NULL;
     if (sel_targets && !input_ids) return TPPO_ERR_NULL;
+    const bool want_fill = (sel_rows || sel_targets || sel_resp_idx) && B > 0 && capacity > 0;
+    // the list covers every kept token, also those beyond `capacity` (they are reported, not written)
+    const int64_t list_tokens = capacity < n_tok ? n_tok : capacity;
+    const int64_t cap64 = select_max_chunks(list_tokens, B);
+    if (cap64 > INT32_MAX / 4) return TPPO_ERR_SIZE;
+    if (want_fill && (!workspace || !is_aligned(workspace, 256) ||
+                      workspace_bytes < tppo_select_workspace_bytes(B, list_tokens)))
+        return TPPO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    Chunk* chunks = want_fill ? static_cast<Chunk*>(workspace) : nullptr;
+    int32_t* n_chunks = want_fill ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) +
+                                                               round_up((size_t)cap64 * sizeof(Chunk), 256))
+                                  : nullptr;
     hipLaunchKernelGGL(select_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, cu_seqlens, ctx_len,
                        done, (int)B, (int)n_tok, (int)tail_drop, resp_off, sel_off, keep_len, counts,
-                       status);
+                       chunks, (int)cap64, n_chunks, status);
     if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
-    const bool want_fill = sel_rows || sel_targets || sel_resp_idx;
-    const int64_t slots = capacity < n_tok ? capacity + 1 : n_tok;   // +1: lets the overflow be reported
-    if (want_fill && B > 0 && slots > 0) {
-        const int64_t blocks = (slots + 255) / 256;
-        hipLaunchKernelGGL(select_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, s, cu_seqlens,
-                           ctx_len, input_ids, (int)B, (int)n_tok, resp_off, sel_off, sel_rows,
+    if (want_fill) {
+        const int groups = (int)(cap64 < kFillMaxGroups ? cap64 : kFillMaxGroups);
+        hipLaunchKernelGGL(select_fill_kernel, dim3(groups), dim3(kChunkThreads), 0, s, cu_seqlens,
+                           ctx_len, input_ids, (int)n_tok, resp_off, chunks, n_chunks, sel_rows,
                            sel_targets, sel_resp_idx, capacity, status);
         if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
     }

@@ -52,10 +52,11 @@ def test_host_side_argument_errors(lib):
     assert lib.tppo_egae(256, 256, 256, 256, None, 1, 10, 1.0, 0.5, 256, 256, None, 0, None, None) == W
     assert lib.tppo_egae(256, 256, 256, 256, None, 1, 10, 1.0, 0.5, 256, 256, 128, 1 << 20, None, None) == W  # misaligned
     # select
-    assert lib.tppo_select(None, None, None, None, 1, 1, 0, None, None, None, None, None, None, 0, None, None, None) == N
-    assert lib.tppo_select(256, 256, 256, None, 1, 1, -1, 256, 256, 256, None, None, None, 0, 256, None, None) == P
-    assert lib.tppo_select(256, 256, 256, None, -1, 1, 0, 256, 256, 256, None, None, None, 0, 256, None, None) == S
-    assert lib.tppo_select(256, 256, 256, None, 1, 1, 0, 256, 256, 256, None, 256, None, 4, 256, None, None) == N  # targets without ids
+    assert lib.tppo_select(None, None, None, None, 1, 1, 0, None, None, None, None, None, None, 0, None, None, 0, None, None) == N
+    assert lib.tppo_select(256, 256, 256, None, 1, 1, -1, 256, 256, 256, None, None, None, 0, 256, None, 0, None, None) == P
+    assert lib.tppo_select(256, 256, 256, None, -1, 1, 0, 256, 256, 256, None, None, None, 0, 256, None, 0, None, None) == S
+    assert lib.tppo_select(256, 256, 256, None, 1, 1, 0, 256, 256, 256, None, 256, None, 4, 256, None, 0, None, None) == N  # targets without ids
+    assert lib.tppo_select(256, 256, 256, None, 1, 1, 0, 256, 256, 256, 256, None, None, 4, 256, None, 0, None, None) == W  # indices need a workspace
     # token_logprobs
     assert lib.tppo_token_logprobs(256, 4, 64, 64, 256, 100, 64, 7, 256, 256, 4, None, None, 256, None, None, 0, None, None) == D
     assert lib.tppo_token_logprobs(256, 4, 64, 32, 256, 100, 64, 0, 256, 256, 4, None, None, 256, None, None, 0, None, None) == S  # ld < H
