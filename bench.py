@@ -50,7 +50,7 @@ def parse():
     ap.add_argument("--workload", default="head32b",
                     choices=["small", "head7b", "head32b", "longcot", "longcot5x"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-rows", type=int, default=3072)
+    ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")

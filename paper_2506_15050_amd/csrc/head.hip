@@ -112,6 +112,7 @@ struct HeadParams {
     int64_t n_rows, ld_h, ld_w, M;
     int H, V, row_tiles, splits, vocab_tiles;
     int unit_splits, unit_cols, n_units;   // persistent schedule, see head_mfma_kernel
+    int unit_rows, col_major;              // col_major: the 8 XCDs sweep the same vocabulary slice together
     int32_t* unit_arrivals;                // [n_units] zeroed before the launch
 };
 
@@ -125,10 +126,13 @@ struct HeadParams {
 // cycle, i.e. 16 lanes of a ds_read_b128; those 16 lanes read the same chunk
 // of 16 consecutive rows, and the swizzle spreads them over all 16 slots of
 // the 256-byte bank window (measured: SQ_LDS_BANK_CONFLICT = 0).
-template <int TV, int TT, int WV, int WT, int BK, int ST, int WGS_PER_CU>
+template <int TV, int TT, int WV, int WT, int BK, int ST, int WGS_PER_CU, int SPREAD = 0>
 struct HeadCfg {
     static constexpr int kTileV = TV, kTileT = TT, kWavesV = WV, kWavesT = WT, kBK = BK, kStages = ST;
     static constexpr int kWgsPerCu = WGS_PER_CU;
+    // 0: a wave issues the transfers of a stage back to back; n > 0: one by one
+    // between its next n MFMAs, so the wave never sits in a full memory queue
+    static constexpr int kSpread = SPREAD;
     static constexpr int kWaves = WV * WT, kThreads = kWaves * 64;
     static constexpr int kWaveV = TV / WV, kWaveT = TT / WT;              // wave tile
     static constexpr int kVB = kWaveV / 32, kTB = kWaveT / 32;            // 32x32 blocks per wave
@@ -144,6 +148,8 @@ struct HeadCfg {
     static_assert(TV % kRowsPerDma == 0, "a transfer may not straddle W and token rows");
     static_assert(kKSteps % 2 == 0, "fragment double buffering assumes an even number of K steps");
     static_assert(WV * 3 * TT * 4 <= kLdsBytes, "merge buffer must fit in the idle stages");
+    static_assert(SPREAD == 0 || (ST == 2 && SPREAD <= kKSteps * kVB * kTB),
+                  "spread issue: two stages, at most one stage's worth of MFMAs");
     __device__ static __forceinline__ int swz(int r) {
         return BK == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3);
     }
@@ -179,6 +185,10 @@ constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4
 // may differ by one vocabulary tile, so the workgroups of an XCD re-align at
 // every unit boundary with an arrival counter.  That wait is only a hint for
 // the caches: it is bounded and falls through, and nothing depends on it.
+// Across XCDs the units are handed out so that the 8 XCDs sweep the SAME
+// vocabulary slice at the same time, each for its own 8 token tiles: W then
+// leaves HBM once per round instead of once per XCD (the later readers find it
+// in the memory-side cache), which is worth 1-2 % at the chip's power limit.
 constexpr int kAlignSpins = 4096;
 __device__ __forceinline__ void align_unit(int32_t* arrivals, int expected) {
     if (threadIdx.x == 0) {
@@ -341,7 +351,23 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
     for (int unit = xcd; unit < p.n_units; unit += 8) {
-    const int unit_row = unit / p.unit_cols, unit_col = unit - unit_row * p.unit_cols;
+    int unit_row, unit_col;
+    if (p.col_major) {
+        // round j of the grid: rows 8g .. 8g+7 (one per XCD) of column j % unit_cols; the rows
+        // left over after the last full group of 8 are dealt out column by column
+        const int j = unit >> 3, full = p.unit_rows >> 3, left = p.unit_rows & 7;
+        if (j < full * p.unit_cols) {
+            unit_row = (j / p.unit_cols) * 8 + xcd;
+            unit_col = j % p.unit_cols;
+        } else {
+            const int t = (j - full * p.unit_cols) * 8 + xcd;
+            unit_col = t / left;
+            unit_row = full * 8 + t - unit_col * left;
+        }
+    } else {
+        unit_row = unit / p.unit_cols;
+        unit_col = unit - unit_row * p.unit_cols;
+    }
     const int rt = unit_row * 8 + tile_in_unit, sp = unit_col * p.unit_splits + split_in_unit;
     const int64_t tok0 = (int64_t)rt * kTileT;
     if (unit >= 8) align_unit(p.unit_arrivals + unit, 8 * p.unit_splits);   // the first unit starts aligned
@@ -373,10 +399,11 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
         }
     };
     point_at_tile(vt_begin, false);
-    auto issue = [&]() {                // next (vocabulary tile, k tile) in sweep order
+    auto issue_one = [&](int q) {
         const unsigned dst = lds_base + issue_stage * C::kStageBytes + wave * kDmaPerWave * 1024;
-#pragma unroll
-        for (int q = 0; q < kDmaPerWave; ++q) dma_16b_per_lane(src[q] + issue_kpos, dst + q * 1024);
+        dma_16b_per_lane(src[q] + issue_kpos, dst + q * 1024);
+    };
+    auto issue_advance = [&]() {        // next (vocabulary tile, k tile) in sweep order
         issue_kpos += kBK;
         if (++issue_stage == kStages) issue_stage = 0;
         if (++issue_kt == k_tiles) {
@@ -385,6 +412,11 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
             ++issue_vt;
             point_at_tile(min(issue_vt, vt_end - 1), true);
         }
+    };
+    auto issue = [&]() {
+#pragma unroll
+        for (int q = 0; q < kDmaPerWave; ++q) issue_one(q);
+        issue_advance();
     };
 
     LaneSoftmax<C> sm;
@@ -418,6 +450,28 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
             for (int tb = 0; tb < kTB; ++tb)
                 acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][vb], fb[buf][tb], acc[vb][tb], 0, 0, 0);
     };
+    // The same K step with this wave's transfers first .. first + n - 1 of the
+    // stage being refilled issued between the MFMAs (`on` is workgroup-uniform).
+    // Transfer j of the stage being refilled follows MFMA number
+    // floor(j * kSpread / kDmaPerWave), counted from the barrier that freed it.
+    constexpr int kMfmaPerStep = kVB * kTB;
+    constexpr int kSpreadSteps = (C::kSpread + kMfmaPerStep - 1) / kMfmaPerStep;   // K steps the issue touches
+    auto mfma_step_issuing = [&](int buf, int part, bool on) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int vb = 0; vb < kVB; ++vb)
+#pragma unroll
+            for (int tb = 0; tb < kTB; ++tb) {
+                acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][vb], fb[buf][tb], acc[vb][tb], 0, 0, 0);
+                const int g = part * kMfmaPerStep + vb * kTB + tb;
+                if (on) {
+#pragma unroll
+                    for (int j = 0; j < kDmaPerWave; ++j)
+                        if (C::kSpread && j * C::kSpread / kDmaPerWave == g) issue_one(j);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    };
 
     // ---- fill the ring, publish stage 0, start on its first fragments
 #pragma unroll
@@ -432,27 +486,42 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
     load_frags(0, 0, 0);
 
     int kt = 0, vt = vt_begin, stage = 0;
+    bool refill = false;                // spread issue: transfers of the stage freed at the last barrier are pending
     for (int it = 0; it < total_iters; ++it) {
 #pragma unroll
         for (int ks = 0; ks + 1 < kKSteps; ++ks) {
             load_frags(stage, ks + 1, (ks + 1) & 1);
-            mfma_step(ks & 1);
+            if (C::kSpread && ks + 1 < kSpreadSteps) {
+                mfma_step_issuing(ks & 1, ks + 1, refill);
+                if (ks + 2 == kSpreadSteps && refill) issue_advance();
+            } else {
+                mfma_step(ks & 1);
+            }
         }
         // The stage's last fragments are in registers.  Hand the stage back,
         // publish the next one and fetch its first fragments BEFORE issuing the
         // last MFMAs, so the barrier and the LDS latency hide behind them.
         const int next_stage = stage + 1 == kStages ? 0 : stage + 1;
+        refill = false;
         if (it + 1 < total_iters) {
             if (total_iters - it - 2 >= kStages - 2)
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kDmaPerWave));
             else
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
             __syncthreads();            // stage it+1 landed for everyone; everyone left stage it
-            if (it + kStages < total_iters) issue();
+            if (it + kStages < total_iters) {
+                if (C::kSpread) refill = true;
+                else issue();
+            }
             load_frags(next_stage, 0, 0);
         }
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step((kKSteps - 1) & 1);
+        if (C::kSpread) {
+            mfma_step_issuing((kKSteps - 1) & 1, 0, refill);
+            if (kSpreadSteps == 1 && refill) issue_advance();
+        } else {
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step((kKSteps - 1) & 1);
+        }
         stage = next_stage;
         if (++kt == k_tiles) {          // a vocabulary tile is complete
             sm.fold(acc, vt, wv, frag_half, p.V);
@@ -503,9 +572,8 @@ __global__ __launch_bounds__(256) void head_combine_kernel(
 }
 
 // Kernel variants (TPPO_HEAD_VARIANT selects one; 0 is the default).
-using Cfg0 = HeadCfg<256, 256, 2, 4, 64, 2, 1>;
-using Cfg1 = HeadCfg<256, 256, 2, 4, 32, 4, 1>;
-using Cfg2 = HeadCfg<256, 256, 2, 4, 32, 5, 1>;
+using Cfg0 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 16>;
+using Cfg1 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 0>;
 
 struct HeadVariant {
     void (*kernel)(HeadParams);
@@ -515,7 +583,7 @@ template <class C>
 constexpr HeadVariant make_variant() {
     return {head_mfma_kernel<C>, C::kTileV, C::kTileT, C::kThreads, C::kLdsBytes, C::kWgsPerCu};
 }
-static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>(), make_variant<Cfg2>()};
+static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>()};
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 static const HeadVariant& pick_variant() {
@@ -628,7 +696,12 @@ extern "C" int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H
     p.splits = choose_splits(hv, M, V);
     p.unit_splits = p.splits < 4 ? p.splits : 4;
     p.unit_cols = p.splits / p.unit_splits;
-    p.n_units = ((p.row_tiles + 7) / 8) * p.unit_cols;
+    p.unit_rows = (p.row_tiles + 7) / 8;
+    p.n_units = p.unit_rows * p.unit_cols;
+    {
+        const char* e = getenv("TPPO_HEAD_ORDER");
+        p.col_major = e ? atoi(e) : 1;                    // tuning override: 0 = units in row-major order
+    }
     p.unit_arrivals = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + workspace_bytes_needed - arrivals_bytes(M));
     hipLaunchKernelGGL(head_clear_kernel, dim3((p.n_units + 255) / 256), dim3(256), 0, s, p.unit_arrivals, p.n_units);
     if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
