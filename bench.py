@@ -51,6 +51,8 @@ def parse():
                     choices=["small", "head7b", "head32b", "longcot", "longcot5x"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--no-reference-rates", action="store_true",
+                    help="skip the two measuring sticks printed beside the datasheet peak")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -182,6 +184,9 @@ def main():
                         traffic=measured_traffic(name, "egae_scan_kernel"),
                         bytes_per_launch=nbytes, avg_ms=stage_ms["egae"])
 
+    if has_head and not args.no_reference_rates:
+        roofline["measured_ceilings"] = reference_rates(tp, hidden, w_head, s_rows=sel["sel_rows"][:M])
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(b, M, args.cpu_sample_rows, has_head)
@@ -199,6 +204,36 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+
+
+def reference_rates(tp, hidden, w_head, s_rows):
+    """Two measured ceilings for the matrix-core roofline, taken after the timed
+    region on the same GPU: the library's own MFMA loop on register-resident
+    operands (what the chip sustains under its power limit), and the vendor
+    GEMM (torch.matmul) on the same M x V x H problem, which writes the logits
+    out and computes no softmax."""
+    import torch
+    ops = (torch.randn(6144, device="cuda") * 0.5).to(torch.bfloat16)
+    out = torch.empty(131072, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    tp.tppo_diag_mfma_rate(ops, out, 2000)
+    torch.cuda.synchronize()
+    e0.record()
+    flop = tp.tppo_diag_mfma_rate(ops, out, 100000)
+    e1.record()
+    torch.cuda.synchronize()
+    mfma_only = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    rows = hidden[s_rows.long()]
+    logits = torch.empty(rows.shape[0], w_head.shape[0], dtype=torch.bfloat16, device="cuda")
+    torch.matmul(rows, w_head.t(), out=logits)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(2):
+        torch.matmul(rows, w_head.t(), out=logits)
+    e1.record()
+    torch.cuda.synchronize()
+    gemm = 2 * 2.0 * rows.shape[0] * w_head.shape[0] * w_head.shape[1] / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return {"mfma_loop_in_registers_tflops": mfma_only, "library_gemm_logits_to_hbm_tflops": gemm}
 
 
 def cpu_baseline(b, M, sample_rows, has_head):

@@ -205,6 +205,23 @@ int tppo_ppo_losses(const float* logp_new, const float* logp_old, const float* a
                     tppo_loss_out* out, void* workspace, size_t workspace_bytes,
                     int32_t* status, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * tppo_diag_mfma_rate -- a measuring stick, not a step of the method: runs the
+ * inner loop of the LM-head kernel (v_mfma_f32_32x32x16_bf16, 8 wavefronts per
+ * workgroup, one workgroup per CU, 16 MFMAs per wavefront and iteration) on
+ * operands held in registers, with no memory traffic.  Timing it gives the
+ * matrix-core rate this chip sustains under its power limit, the practical
+ * ceiling beside the datasheet peak in the benchmark's roofline entry.
+ *
+ * in : operands  device, 6144 bf16 values (16-byte aligned); finite values of
+ *                the magnitude of real inputs make the power draw realistic.
+ *      iters     loop count (0 .. 2^24).
+ * out: out       device, 131072 floats (one checksum per thread; contents are
+ *                not specified).  *flop (host, may be NULL): floating-point
+ *                operations the launch performs.
+ */
+int tppo_diag_mfma_rate(const void* operands, float* out, int64_t iters, double* flop, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

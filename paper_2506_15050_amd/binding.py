@@ -34,6 +34,7 @@ _SIGNATURES = {
     "tppo_ppo_losses_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
     "tppo_ppo_losses": (ctypes.c_int, [_c_ptr] * 9 + [_c_i64, _c_i64] + [_c_f32] * 4 +
                         [_c_ptr, _c_ptr, _c_size, _c_ptr, _c_ptr]),
+    "tppo_diag_mfma_rate": (ctypes.c_int, [_c_ptr, _c_ptr, _c_i64, ctypes.POINTER(ctypes.c_double), _c_ptr]),
 }
 EXPORTS = tuple(_SIGNATURES)
 _lib = None
@@ -189,3 +190,12 @@ def read_loss_out(res):
     raw = bytes(res.cpu().numpy().tobytes())
     s = LossOut.from_buffer_copy(raw)
     return {name: getattr(s, name) for name, _ in LossOut._fields_}
+
+
+def tppo_diag_mfma_rate(operands, out, iters):
+    """Launch the register-resident MFMA loop; returns the flop count of the launch."""
+    lib = load()
+    flop = ctypes.c_double(0.0)
+    rc = lib.tppo_diag_mfma_rate(_ptr(operands), _ptr(out), int(iters), ctypes.byref(flop), _stream())
+    _check(rc, "tppo_diag_mfma_rate")
+    return flop.value
