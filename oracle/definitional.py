@@ -170,3 +170,65 @@ def ppo_losses(logp_new, logp_old, adv, v_new, v_old, ret,
                 value_loss=value_sum / n_val if n_val else 0.0,
                 policy_sum=policy_sum, value_sum=value_sum,
                 n_policy=n_pol, n_value=n_val)
+
+
+# --------------------------------------------------------------------------
+# Derivatives of the two losses with respect to the new policy's log-probs and
+# the new values (the step after the losses in Alg. 1: the policy and value
+# updates).  Written out branch by branch from Eq. (ppoloss) and
+# Eqs. (valueclip), (valueloss).
+# --------------------------------------------------------------------------
+def ppo_loss_grads(logp_new, logp_old, adv, v_new, v_old, ret,
+                   resp_off, keep_len, done,
+                   eps_low, eps_high, xi_low, xi_high,
+                   policy_scale=1.0, value_scale=1.0,
+                   policy_denominator=None, value_denominator=None):
+    """d(policy_scale * policy_loss)/d logp_new and d(value_scale * value_loss)/d v_new.
+
+    Policy token: the surrogate is min(u, c) with u = rho A, c = clip(rho) A,
+    rho = exp(logp_new - logp_old), so d rho / d logp_new = rho.  Where u <= c
+    the unclipped branch is the minimum (inside the clip range the two are the
+    same function) and the derivative of the term is rho A; where c < u the
+    clip is saturated, c is constant and the derivative is 0 ("clipped").
+    Value token: the term is 1/2 max(d0^2, d1^2), d0 = V - R, d1 = V_clip - R.
+    Where d0^2 >= d1^2 the derivative is d0; where d1^2 > d0^2 V lies outside
+    the clip range (inside it V_clip = V and the squares are equal), V_clip is
+    constant and the derivative is 0 ("clipped").
+    Token-level means: each derivative is divided by the number of tokens of
+    its set (or by the given denominator, for a batch spread over several
+    calls).  policy_loss = -J_PPO, hence the minus sign.  Entries outside a set
+    get 0.  Also returns the clipped-token counts and the mean ratio.
+    """
+    n = int(resp_off[len(done)])
+    g_lp, g_v = [0.0] * n, [0.0] * n
+    n_pol = sum(min(int(keep_len[i]), int(resp_off[i + 1]) - int(resp_off[i])) for i in range(len(done)))
+    n_val = sum(int(resp_off[i + 1]) - int(resp_off[i]) for i in range(len(done)) if int(done[i]) != 0)
+    den_p = float(policy_denominator) if policy_denominator else float(n_pol)
+    den_v = float(value_denominator) if value_denominator else float(n_val)
+    pol_clipped = val_clipped = 0
+    ratios = []
+    for i in range(len(done)):
+        lo, hi = int(resp_off[i]), int(resp_off[i + 1])
+        for t in range(hi - lo):
+            j = lo + t
+            if t < int(keep_len[i]):
+                ratio = math.exp(float(logp_new[j]) - float(logp_old[j]))
+                a = float(adv[j])
+                u = ratio * a
+                c = _clip(ratio, 1.0 - eps_low, 1.0 + eps_high) * a
+                ratios.append(ratio)
+                if u <= c:
+                    g_lp[j] = -policy_scale * ratio * a / den_p
+                else:
+                    pol_clipped += 1
+            if int(done[i]) != 0:
+                v, vo, r = float(v_new[j]), float(v_old[j]), float(ret[j])
+                d0 = v - r
+                d1 = _clip(v, vo - xi_low, vo + xi_high) - r
+                if d0 * d0 >= d1 * d1:
+                    g_v[j] = value_scale * d0 / den_v
+                else:
+                    val_clipped += 1
+    return dict(grad_logp=g_lp, grad_v=g_v, n_policy=n_pol, n_value=n_val,
+                n_policy_clipped=pol_clipped, n_value_clipped=val_clipped,
+                ratio_mean=math.fsum(ratios) / len(ratios) if ratios else 0.0)

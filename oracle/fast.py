@@ -180,3 +180,40 @@ def ppo_losses(logp_new, logp_old, adv, v_new, v_old, ret,
                 value_loss=value_sum / n_val if n_val else 0.0,
                 policy_sum=policy_sum, value_sum=value_sum,
                 n_policy=n_pol, n_value=n_val)
+
+
+def ppo_loss_grads(logp_new, logp_old, adv, v_new, v_old, ret,
+                   resp_off, keep_len, done,
+                   eps_low, eps_high, xi_low, xi_high,
+                   policy_scale=1.0, value_scale=1.0,
+                   policy_denominator=None, value_denominator=None):
+    """Derivatives of policy_scale * policy_loss with respect to logp_new and of
+    value_scale * value_loss with respect to v_new (Eq. (ppoloss);
+    Eqs. (valueclip), (valueloss); token-level means), zero outside the sets:
+    -rho A / N where the unclipped surrogate is the minimum, 0 where the clip is
+    saturated; (V - R) / N where the unclipped square is the maximum, 0 where
+    the clipped one is.  Plus clipped-token counts and the mean ratio."""
+    pol, val = loss_masks(resp_off, keep_len, done)
+    n = pol.shape[0]
+    n_pol, n_val = int(pol.sum()), int(val.sum())
+    den_p = float(policy_denominator) if policy_denominator else float(n_pol)
+    den_v = float(value_denominator) if value_denominator else float(n_val)
+    g_lp, g_v = np.zeros(n), np.zeros(n)
+    pol_clipped = val_clipped = 0
+    ratio_mean = 0.0
+    if n_pol:
+        ln, lo_, a = (decode(x)[pol] for x in (logp_new, logp_old, adv))
+        rho = np.exp(ln - lo_)
+        unclipped = rho * a <= np.clip(rho, 1.0 - eps_low, 1.0 + eps_high) * a
+        g_lp[pol] = np.where(unclipped, -policy_scale * rho * a / den_p, 0.0)
+        pol_clipped = int((~unclipped).sum())
+        ratio_mean = float(rho.mean())
+    if n_val:
+        v, vo, r = (decode(x)[val] for x in (v_new, v_old, ret))
+        d0 = v - r
+        d1 = np.clip(v, vo - xi_low, vo + xi_high) - r
+        unclipped = d0 * d0 >= d1 * d1
+        g_v[val] = np.where(unclipped, value_scale * d0 / den_v, 0.0)
+        val_clipped = int((~unclipped).sum())
+    return dict(grad_logp=g_lp, grad_v=g_v, n_policy=n_pol, n_value=n_val,
+                n_policy_clipped=pol_clipped, n_value_clipped=val_clipped, ratio_mean=ratio_mean)

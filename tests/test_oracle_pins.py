@@ -392,3 +392,119 @@ def test_clip_is_asymmetric():
     vargs = ([0.0], [0.0], [0.0], [0.55], [0.0], [2.0], [0, 1], [1], [1])
     assert ofast.ppo_losses(*vargs, 0.2, 0.28, 0.5, 0.6)["value_loss"] == pytest.approx(0.5 * 1.45 ** 2)
     assert ofast.ppo_losses(*vargs, 0.2, 0.28, 0.6, 0.5)["value_loss"] == pytest.approx(0.5 * 1.5 ** 2)
+
+
+# ------------------------------------------------------------------ loss derivatives
+def _grad_call(impl, a, off, keep, done, eps=(0.2, 0.28), xi=(0.5, 0.6), **kw):
+    return impl.ppo_loss_grads(a["logp_new"], a["logp_old"], a["adv"], a["v_new"], a["v_old"],
+                               a["ret"], off, keep, done, eps[0], eps[1], xi[0], xi[1], **kw)
+
+
+def _loss_grad_golden():
+    pol, val, exp = [], [], {}
+    for line in open(os.path.join(GOLDEN, "loss_grad_worked_examples.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, v = line.split(":")
+        nums = [float(x) for x in v.split()]
+        if key == "policy":
+            pol.append(nums)
+        elif key == "value":
+            val.append(nums)
+        else:
+            exp[key] = nums[0]
+    return np.array(pol), np.array(val), exp
+
+
+@pytest.mark.parametrize("impl", [odef, ofast], ids=["definitional", "fast"])
+def test_loss_grad_worked_examples(impl):
+    pol, val, exp = _loss_grad_golden()
+    n = len(pol)
+    out = impl.ppo_loss_grads(np.log(pol[:, 1]), np.zeros(n), pol[:, 0], val[:, 0], val[:, 1], val[:, 2],
+                              [0, n], [n], [1], 0.2, 0.28, 0.5, 0.6)
+    assert np.allclose(np.asarray(out["grad_logp"]) * n, pol[:, 2], rtol=0, atol=1e-12)
+    assert np.allclose(np.asarray(out["grad_v"]) * n, val[:, 3], rtol=0, atol=1e-12)
+    assert out["n_policy_clipped"] == int(pol[:, 3].sum()) and out["n_value_clipped"] == int(val[:, 4].sum())
+    assert abs(out["ratio_mean"] - exp["ratio_mean"]) < 1e-12
+    # scales multiply, denominators replace the token counts
+    out2 = impl.ppo_loss_grads(np.log(pol[:, 1]), np.zeros(n), pol[:, 0], val[:, 0], val[:, 1], val[:, 2],
+                               [0, n], [n], [1], 0.2, 0.28, 0.5, 0.6, policy_scale=2.0, value_scale=-3.0,
+                               policy_denominator=10, value_denominator=20)
+    assert np.allclose(np.asarray(out2["grad_logp"]) * 10 / 2.0, pol[:, 2], rtol=0, atol=1e-12)
+    assert np.allclose(np.asarray(out2["grad_v"]) * 20 / -3.0, val[:, 3], rtol=0, atol=1e-12)
+
+
+def test_loss_grads_fast_equals_definitional():
+    rng = np.random.default_rng(21)
+    off, keep, done, a = _random_loss_inputs(rng)
+    d, f = _grad_call(odef, a, off, keep, done), _grad_call(ofast, a, off, keep, done)
+    for k in ("grad_logp", "grad_v"):
+        assert np.allclose(np.asarray(d[k]), f[k], rtol=1e-13, atol=1e-15), k
+    for k in ("n_policy", "n_value", "n_policy_clipped", "n_value_clipped"):
+        assert d[k] == f[k], k
+    assert abs(d["ratio_mean"] - f["ratio_mean"]) < 1e-13
+
+
+def test_loss_grads_match_autograd():
+    """The derivative formulas against reverse-mode differentiation of the loss
+    written with library tensor ops (an independent mechanism: nothing of the
+    branch analysis is shared)."""
+    import torch
+    rng = np.random.default_rng(22)
+    off, keep, done, a = _random_loss_inputs(rng, B=11, max_len=40)
+    pol, val = ofast.loss_masks(off, keep, done)
+    ln = torch.tensor(a["logp_new"], dtype=torch.float64, requires_grad=True)
+    v = torch.tensor(a["v_new"], dtype=torch.float64, requires_grad=True)
+    lo_, adv, vo, r = (torch.tensor(a[k], dtype=torch.float64) for k in ("logp_old", "adv", "v_old", "ret"))
+    pm, vm = torch.tensor(pol), torch.tensor(val)
+    rho = torch.exp(ln - lo_)
+    surr = torch.minimum(rho * adv, torch.clamp(rho, 0.8, 1.28) * adv)
+    policy_loss = -(surr[pm]).sum() / int(pol.sum())
+    v_clip = torch.maximum(torch.minimum(v, vo + 0.6), vo - 0.5)
+    value_loss = 0.5 * torch.maximum((v - r) ** 2, (v_clip - r) ** 2)[vm].sum() / int(val.sum())
+    (1.7 * policy_loss - 0.4 * value_loss).backward()
+    out = _grad_call(ofast, a, off, keep, done, policy_scale=1.7, value_scale=-0.4)
+    assert np.allclose(out["grad_logp"], ln.grad.numpy(), rtol=1e-12, atol=1e-15)
+    assert np.allclose(out["grad_v"], v.grad.numpy(), rtol=1e-12, atol=1e-15)
+    assert np.all(out["grad_logp"][~pol] == 0.0) and np.all(out["grad_v"][~val] == 0.0)
+    assert out["n_policy_clipped"] > 0 and out["n_value_clipped"] > 0       # both branches exercised
+    assert out["n_policy_clipped"] < pol.sum() and out["n_value_clipped"] < val.sum()
+
+
+def test_loss_grads_match_finite_differences_of_the_pinned_loss():
+    rng = np.random.default_rng(23)
+    off, keep, done, a = _random_loss_inputs(rng, B=4, max_len=8)
+    g = _grad_call(odef, a, off, keep, done)
+    h = 1e-6
+    for name, key, loss in (("logp_new", "grad_logp", "policy_loss"), ("v_new", "grad_v", "value_loss")):
+        for j in range(len(a[name])):
+            up, dn = {k: x.copy() for k, x in a.items()}, {k: x.copy() for k, x in a.items()}
+            up[name][j] += h
+            dn[name][j] -= h
+            fd = (_call(odef, up, off, keep, done)[loss] - _call(odef, dn, off, keep, done)[loss]) / (2 * h)
+            assert abs(fd - g[key][j]) < 1e-7, (name, j)     # kinks have measure zero for these draws
+
+
+def test_loss_grads_masks_poison_and_counts():
+    rng = np.random.default_rng(24)
+    off, keep, done, a = _random_loss_inputs(rng, B=9)
+    pol, val = ofast.loss_masks(off, keep, done)
+    ref = _grad_call(ofast, a, off, keep, done)
+    c = {k: v.copy() for k, v in a.items()}
+    for k in ("logp_new", "logp_old", "adv"):
+        c[k][~pol] = np.nan
+    for k in ("v_new", "v_old", "ret"):
+        c[k][~val] = np.inf
+    out = _grad_call(ofast, c, off, keep, done)
+    assert np.array_equal(out["grad_logp"], ref["grad_logp"]) and np.array_equal(out["grad_v"], ref["grad_v"])
+    # same policy and same value function: nothing is clipped, ratio 1
+    b = dict(a, logp_old=a["logp_new"].copy(), v_old=a["v_new"].copy())
+    same = _grad_call(ofast, b, off, keep, done)
+    assert same["n_policy_clipped"] == 0 and same["n_value_clipped"] == 0 and same["ratio_mean"] == 1.0
+    assert np.allclose(same["grad_logp"][pol], -a["adv"][pol] / pol.sum(), rtol=1e-13)
+    assert np.allclose(same["grad_v"][val], (a["v_new"] - a["ret"])[val] / val.sum(), rtol=1e-13)
+    # empty sets
+    e = ofast.ppo_loss_grads(np.zeros(3), np.zeros(3), np.ones(3), np.zeros(3), np.zeros(3), np.ones(3),
+                             [0, 3], [0], [0], 0.2, 0.28, 0.5, 0.6)
+    assert not e["grad_logp"].any() and not e["grad_v"].any() and e["ratio_mean"] == 0.0
