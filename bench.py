@@ -187,6 +187,34 @@ def main():
     if has_head and not args.no_reference_rates:
         roofline["measured_ceilings"] = reference_rates(tp, hidden, w_head, s_rows=sel["sel_rows"][:M])
 
+    # --- beyond the metric's four steps: the loss derivatives (one more streaming pass), timed on their own
+    ws_bwd = tp._workspace(lib.tppo_ppo_losses_backward_workspace_bytes(n_resp, b["B"]), "cuda")
+    grads = (torch.empty(n_resp, device="cuda"), torch.empty(n_resp, device="cuda"))
+    stats_out = torch.empty(32, dtype=torch.uint8, device="cuda")
+    s_last = tp.tppo_select(d["cu_seqlens"], d["ctx_len"], d["done"], ids, b["tail_drop"], n_tok=n_tok)
+    logp_last = logp0
+    adv_last, ret_last = adv_ret
+
+    def backward_pass():
+        tp.tppo_ppo_losses_backward(logp_last, logp_old, adv_last, d["v_new"], d["values"], ret_last,
+                                    s_last["resp_off"], s_last["keep_len"], d["done"], b["eps_low"],
+                                    b["eps_high"], b["xi_low"], b["xi_high"], status=status,
+                                    workspace=ws_bwd, out=loss_out, stats=stats_out, grads=grads)
+
+    backward_pass()
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(args.steps):
+        backward_pass()
+    e1.record()
+    torch.cuda.synchronize()
+    bwd_ms = e0.elapsed_time(e1) / args.steps
+    bwd_bytes = 16.0 * (losses["n_policy"] + losses["n_value"]) + 4.0 * (2 * n_resp - losses["n_policy"] - losses["n_value"])
+    extra = {"ppo_losses_backward": {"ms": bwd_ms, "algorithmic_bytes": bwd_bytes,
+                                     "GB/s": bwd_bytes / (bwd_ms * 1e-3) / 1e9,
+                                     "clip_stats": tp.read_loss_stats(stats_out)}}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(b, M, args.cpu_sample_rows, has_head)
@@ -201,7 +229,7 @@ def main():
                    "gamma": b["gamma"], "lambda": b["lam"]},
         "stages_ms": stage_ms,
         "losses": {k: losses[k] for k in ("policy_loss", "value_loss", "n_policy", "n_value")},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "beyond_the_metric": extra,
     }
     print(json.dumps(out))
 

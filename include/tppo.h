@@ -206,6 +206,54 @@ int tppo_ppo_losses(const float* logp_new, const float* logp_old, const float* a
                     int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * tppo_ppo_losses_backward -- the step after the losses in Alg. 1 (policy and
+ * value updates): derivatives of Eq. (ppoloss) and Eqs. (valueclip),
+ * (valueloss) with respect to the new policy's log-probs and the new values,
+ * in one streaming pass that also yields the losses themselves and the
+ * fraction of tokens whose clip is active.
+ *
+ *   grad_logp[j] = policy_scale * d policy_loss / d logp_new[j]
+ *                = -policy_scale * rho_j A_j / N_policy  where rho A <= clip(rho) A
+ *                  (the unclipped surrogate is the minimum), 0 where the clip is
+ *                  saturated ("clipped" token) and 0 outside the policy set;
+ *   grad_v[j]    = value_scale * d value_loss / d v_new[j]
+ *                = value_scale * (V_j - R_j) / N_value  where (V-R)^2 >= (V_clip-R)^2,
+ *                  0 where the clipped square is larger ("clipped") and 0 outside
+ *                  the value set.
+ * N_policy / N_value are this call's token counts (token-level mean, Sec.
+ * 4.1.1) unless policy_denominator / value_denominator > 0 replace them (a
+ * batch spread over several calls or devices).  Sets, masking by selection and
+ * determinism as in tppo_ppo_losses.  Decisions are taken in fp32.
+ *
+ * in : as tppo_ppo_losses, plus the two scales (finite) and denominators.
+ * out: grad_logp[n_resp], grad_v[n_resp] device fp32, every element written
+ *      (NULL exactly when the corresponding input half is NULL); out and stats
+ *      device, each may be NULL.
+ * Errors: as tppo_ppo_losses; a gradient pointer that does not match its half
+ *      -> TPPO_ERR_NULL; NaN scale -> TPPO_ERR_PARAM.
+ */
+typedef struct {
+    float ratio_mean;          /* mean of rho over the policy set */
+    float policy_clip_frac;    /* n_policy_clipped / n_policy */
+    float value_clip_frac;     /* n_value_clipped / n_value */
+    float reserved;
+    int64_t n_policy_clipped, n_value_clipped;
+} tppo_loss_stats;
+
+size_t tppo_ppo_losses_backward_workspace_bytes(int64_t n_resp, int64_t B);
+int tppo_ppo_losses_backward(const float* logp_new, const float* logp_old, const float* adv,
+                             const float* v_new, const float* v_old, const float* ret,
+                             const int32_t* resp_off, const int32_t* keep_len, const int32_t* done,
+                             int64_t B, int64_t n_resp,
+                             float eps_low, float eps_high, float xi_low, float xi_high,
+                             float policy_scale, float value_scale,
+                             int64_t policy_denominator, int64_t value_denominator,
+                             float* grad_logp, float* grad_v,
+                             tppo_loss_out* out, tppo_loss_stats* stats,
+                             void* workspace, size_t workspace_bytes,
+                             int32_t* status, void* stream);
+
+/* ---------------------------------------------------------------------------
  * tppo_diag_mfma_rate -- a measuring stick, not a step of the method: runs the
  * inner loop of the LM-head kernel (v_mfma_f32_32x32x16_bf16, 8 wavefronts per
  * workgroup, one workgroup per CU, 16 MFMAs per wavefront and iteration) on

@@ -34,6 +34,9 @@ _SIGNATURES = {
     "tppo_ppo_losses_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
     "tppo_ppo_losses": (ctypes.c_int, [_c_ptr] * 9 + [_c_i64, _c_i64] + [_c_f32] * 4 +
                         [_c_ptr, _c_ptr, _c_size, _c_ptr, _c_ptr]),
+    "tppo_ppo_losses_backward_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
+    "tppo_ppo_losses_backward": (ctypes.c_int, [_c_ptr] * 9 + [_c_i64, _c_i64] + [_c_f32] * 6 +
+                                 [_c_i64, _c_i64] + [_c_ptr] * 5 + [_c_size, _c_ptr, _c_ptr]),
     "tppo_diag_mfma_rate": (ctypes.c_int, [_c_ptr, _c_ptr, _c_i64, ctypes.POINTER(ctypes.c_double), _c_ptr]),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -190,6 +193,47 @@ def read_loss_out(res):
     raw = bytes(res.cpu().numpy().tobytes())
     s = LossOut.from_buffer_copy(raw)
     return {name: getattr(s, name) for name, _ in LossOut._fields_}
+
+
+class LossStats(ctypes.Structure):
+    _fields_ = [("ratio_mean", ctypes.c_float), ("policy_clip_frac", ctypes.c_float),
+                ("value_clip_frac", ctypes.c_float), ("reserved", ctypes.c_float),
+                ("n_policy_clipped", ctypes.c_int64), ("n_value_clipped", ctypes.c_int64)]
+
+
+def tppo_ppo_losses_backward(logp_new, logp_old, adv, v_new, v_old, ret, resp_off, keep_len, done,
+                             eps_low, eps_high, xi_low, xi_high, policy_scale=1.0, value_scale=1.0,
+                             policy_denominator=0, value_denominator=0, status=None, workspace=None,
+                             out=None, stats=None, grads=None):
+    """Derivatives of the two losses (plus the losses and clip statistics) in one
+    pass.  Returns (grad_logp, grad_v, loss_out tensor, stats tensor)."""
+    lib = load()
+    dev = resp_off.device
+    B = done.numel()
+    n_resp = (logp_new if logp_new is not None else v_new).numel()
+    if grads is None:
+        g_lp = torch.empty(n_resp, dtype=torch.float32, device=dev) if logp_new is not None else None
+        g_v = torch.empty(n_resp, dtype=torch.float32, device=dev) if v_new is not None else None
+    else:
+        g_lp, g_v = grads
+    res = torch.empty(ctypes.sizeof(LossOut), dtype=torch.uint8, device=dev) if out is None else out
+    st = torch.empty(ctypes.sizeof(LossStats), dtype=torch.uint8, device=dev) if stats is None else stats
+    ws_bytes = lib.tppo_ppo_losses_backward_workspace_bytes(n_resp, B)
+    ws = _workspace(ws_bytes, dev) if workspace is None else workspace
+    rc = lib.tppo_ppo_losses_backward(
+        _ptr(logp_new), _ptr(logp_old), _ptr(adv), _ptr(v_new), _ptr(v_old), _ptr(ret),
+        _ptr(_dev_i32(resp_off)), _ptr(_dev_i32(keep_len)), _ptr(_dev_i32(done)), B, n_resp,
+        float(eps_low), float(eps_high), float(xi_low), float(xi_high), float(policy_scale),
+        float(value_scale), int(policy_denominator), int(value_denominator), _ptr(g_lp), _ptr(g_v),
+        _ptr(res), _ptr(st), _ptr(ws), ws.numel(), _ptr(status), _stream())
+    _check(rc, "tppo_ppo_losses_backward")
+    return g_lp, g_v, res, st
+
+
+def read_loss_stats(st):
+    """Device ``tppo_loss_stats`` -> dict (synchronises)."""
+    s = LossStats.from_buffer_copy(bytes(st.cpu().numpy().tobytes()))
+    return {name: getattr(s, name) for name, _ in LossStats._fields_ if name != "reserved"}
 
 
 def tppo_diag_mfma_rate(operands, out, iters):

@@ -218,6 +218,246 @@ __global__ __launch_bounds__(kChunkThreads) void loss_final_kernel(
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// tppo_ppo_losses_backward: the same streaming pass, also writing the
+// derivatives of the two losses with respect to logp_new and v_new and
+// counting the tokens whose clip is active.
+//   policy token: surrogate min(u, c), u = rho A, c = clip(rho) A.  Where
+//     u <= c the unclipped branch is the minimum (inside the clip range both
+//     are the same function) and d/dlogp_new = rho A; where c < u the clip is
+//     saturated, c is constant, the derivative is 0.
+//   value token: 1/2 max(d0^2, d1^2), d0 = V - R, d1 = V_clip - R.  Where
+//     d0^2 >= d1^2 the derivative is d0; otherwise V is outside the clip
+//     range, V_clip is constant and the derivative is 0.
+// Token-level means: the set sizes are known from the metadata before the pass
+// (the list-building kernel counts them), so each derivative is final when it
+// is written; tokens outside a set get 0.
+constexpr int kGradPartials = 5;       // policy sum, value sum, ratio sum, clipped policy, clipped value
+
+struct GradWs {
+    Chunk* chunks;        // [cap]
+    double* partials;     // [kLossMaxGroups][kGradPartials]
+    long long* counts;    // [2]: tokens in the policy set, in the value set
+    int32_t* n_chunks;    // [1]
+};
+
+static inline size_t grad_ws_bytes(int64_t cap) {
+    return round_up((size_t)cap * sizeof(Chunk), 256) + (size_t)kLossMaxGroups * kGradPartials * sizeof(double) + 256;
+}
+
+__host__ __device__ __forceinline__ GradWs grad_ws(void* ws, int64_t cap) {
+    char* p = static_cast<char*>(ws);
+    GradWs w;
+    w.chunks = reinterpret_cast<Chunk*>(p);
+    p += ((size_t)cap * sizeof(Chunk) + 255) / 256 * 256;
+    w.partials = reinterpret_cast<double*>(p);
+    p += (size_t)kLossMaxGroups * kGradPartials * sizeof(double);
+    w.counts = reinterpret_cast<long long*>(p);
+    w.n_chunks = reinterpret_cast<int32_t*>(p + 2 * sizeof(long long));
+    return w;
+}
+
+struct GradParams {
+    LossParams fwd;
+    float* grad_logp;
+    float* grad_v;
+    float policy_scale, value_scale;
+    long long policy_denominator, value_denominator;     // <= 0: the call's own token counts
+};
+
+__global__ __launch_bounds__(kBuildThreads) void loss_grad_init_kernel(
+    const int32_t* __restrict__ resp_off, const int32_t* __restrict__ keep_len,
+    const int32_t* __restrict__ done, int B, int n_resp, int cap, int has_pol, int has_val, void* ws_raw,
+    int32_t* status) {
+    __shared__ long long s_cnt[2][kBuildThreads / kWave];
+    GradWs ws = grad_ws(ws_raw, cap);
+    build_chunks(resp_off, B, n_resp, ws.chunks, cap, ws.n_chunks, status);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    long long np = 0, nv = 0;
+    for (int i = tid; i < B; i += kBuildThreads) {
+        const int win = max(resp_off[i + 1] - resp_off[i], 0);
+        np += min(max(keep_len[i], 0), win);
+        nv += done[i] != 0 ? win : 0;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        np += __shfl_down(np, off);
+        nv += __shfl_down(nv, off);
+    }
+    if (lane == 0) {
+        s_cnt[0][wave] = np;
+        s_cnt[1][wave] = nv;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        np = nv = 0;
+        for (int w = 0; w < kBuildThreads / kWave; ++w) {
+            np += s_cnt[0][w];
+            nv += s_cnt[1][w];
+        }
+        ws.counts[0] = has_pol ? np : 0;
+        ws.counts[1] = has_val ? nv : 0;
+    }
+}
+
+// Four consecutive results per access; `n` = how many of the four exist.
+__device__ __forceinline__ void store4(float* __restrict__ dst, int first, const float (&x)[4], int n) {
+    if (n >= 4) {
+        float4u t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = x[e];
+        *reinterpret_cast<float4u*>(dst + first) = t;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (e < n) dst[first + e] = x[e];
+    }
+}
+
+__global__ __launch_bounds__(kChunkThreads) void loss_grad_kernel(GradParams gp, void* ws_raw) {
+    __shared__ double s_red[kChunkThreads / kWave];
+    const LossParams& p = gp.fwd;
+    GradWs ws = grad_ws(ws_raw, p.cap);
+    const int tid = threadIdx.x;
+    const bool has_pol = p.logp_new != nullptr, has_val = p.v_new != nullptr;
+    const int count = *ws.n_chunks;
+    constexpr int kGroups = kChunkTokens / (4 * kChunkThreads);      // 16-byte groups per thread: 2
+    const long long den_p = gp.policy_denominator > 0 ? gp.policy_denominator : ws.counts[0];
+    const long long den_v = gp.value_denominator > 0 ? gp.value_denominator : ws.counts[1];
+    const float pol_coef = den_p > 0 ? -gp.policy_scale / (float)den_p : 0.f;     // policy_loss = -J_PPO
+    const float val_coef = den_v > 0 ? gp.value_scale / (float)den_v : 0.f;
+
+    float pol_acc = 0.f, val_acc = 0.f, ratio_acc = 0.f;
+    int pol_clipped = 0, val_clipped = 0;
+    int w = blockIdx.x;
+    Chunk cur = ws.chunks[w < count ? w : 0];
+    int keep = 0, fin = 0;
+    if (w < count) {
+        keep = p.keep_len[cur.seg];
+        fin = p.done[cur.seg];
+    }
+    for (; w < count; w += gridDim.x) {
+        const int start = cur.start, len = cur.len();
+        const int pol_in_chunk = has_pol ? min(max(keep - cur.number() * kChunkTokens, 0), len) : 0;
+        const int val_in_chunk = (has_val && fin != 0) ? len : 0;
+        const int w_next = w + gridDim.x;
+        Chunk nxt = cur;
+        int keep_n = 0, fin_n = 0;
+        if (w_next < count) {
+            nxt = ws.chunks[w_next];
+            keep_n = p.keep_len[nxt.seg];
+            fin_n = p.done[nxt.seg];
+        }
+        float ln[kGroups][4], lo[kGroups][4], a[kGroups][4], v[kGroups][4], vo[kGroups][4], r[kGroups][4];
+        int n_pol[kGroups], n_val[kGroups], n_tok[kGroups];
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) {
+            const int k0 = g * 4 * kChunkThreads + tid * 4;
+            n_tok[g] = min(max(len - k0, 0), 4);
+            n_pol[g] = min(max(pol_in_chunk - k0, 0), 4);
+            n_val[g] = min(max(val_in_chunk - k0, 0), 4);
+            if (n_pol[g] > 0) {
+                load4(ln[g], p.logp_new, start + k0, n_pol[g]);
+                load4(lo[g], p.logp_old, start + k0, n_pol[g]);
+                load4(a[g], p.adv, start + k0, n_pol[g]);
+            }
+            if (n_val[g] > 0) {
+                load4(v[g], p.v_new, start + k0, n_val[g]);
+                load4(vo[g], p.v_old, start + k0, n_val[g]);
+                load4(r[g], p.ret, start + k0, n_val[g]);
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) {
+            const int k0 = g * 4 * kChunkThreads + tid * 4;
+            if (has_pol && n_tok[g] > 0) {
+                float gl[4] = {0.f, 0.f, 0.f, 0.f};
+                if (n_pol[g] > 0) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float rho = expf(ln[g][e] - lo[g][e]);
+                        const float u = rho * a[g][e];
+                        const float c = clampf(rho, p.ratio_lo, p.ratio_hi) * a[g][e];
+                        const bool in_set = e < n_pol[g], unclipped = u <= c;
+                        pol_acc += in_set ? fminf(u, c) : 0.f;     // select, never multiply by a mask
+                        ratio_acc += in_set ? rho : 0.f;
+                        pol_clipped += (in_set && !unclipped) ? 1 : 0;
+                        gl[e] = (in_set && unclipped) ? pol_coef * u : 0.f;
+                    }
+                }
+                store4(gp.grad_logp, start + k0, gl, n_tok[g]);
+            }
+            if (has_val && n_tok[g] > 0) {
+                float gv[4] = {0.f, 0.f, 0.f, 0.f};
+                if (n_val[g] > 0) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float d0 = v[g][e] - r[g][e];
+                        const float d1 = clampf(v[g][e], vo[g][e] - p.xi_low, vo[g][e] + p.xi_high) - r[g][e];
+                        const float q0 = d0 * d0, q1 = d1 * d1;
+                        const bool in_set = e < n_val[g], unclipped = q0 >= q1;
+                        val_acc += in_set ? fmaxf(q0, q1) : 0.f;
+                        val_clipped += (in_set && !unclipped) ? 1 : 0;
+                        gv[e] = (in_set && unclipped) ? val_coef * d0 : 0.f;
+                    }
+                }
+                store4(gp.grad_v, start + k0, gv, n_tok[g]);
+            }
+        }
+        cur = nxt;
+        keep = keep_n;
+        fin = fin_n;
+    }
+    const double sums[kGradPartials] = {(double)pol_acc, (double)val_acc, (double)ratio_acc,
+                                        (double)pol_clipped, (double)val_clipped};
+#pragma unroll
+    for (int q = 0; q < kGradPartials; ++q) {
+        const double t = block_sum(sums[q], s_red);
+        if (tid == 0) ws.partials[kGradPartials * blockIdx.x + q] = t;
+    }
+}
+
+__global__ void loss_grad_zero_counts_kernel(void* ws_raw, int cap) {
+    GradWs ws = grad_ws(ws_raw, cap);
+    if (threadIdx.x < 2) ws.counts[threadIdx.x] = 0;
+}
+
+__global__ __launch_bounds__(kChunkThreads) void loss_grad_final_kernel(void* ws_raw, int cap, int groups,
+                                                                       tppo_loss_out* __restrict__ out,
+                                                                       tppo_loss_stats* __restrict__ stats) {
+    __shared__ double s_red[kChunkThreads / kWave];
+    GradWs ws = grad_ws(ws_raw, cap);
+    const int tid = threadIdx.x;
+    double acc[kGradPartials] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int g = tid; g < groups; g += kChunkThreads)
+#pragma unroll
+        for (int q = 0; q < kGradPartials; ++q) acc[q] += ws.partials[kGradPartials * g + q];
+    double tot[kGradPartials];
+#pragma unroll
+    for (int q = 0; q < kGradPartials; ++q) tot[q] = block_sum(acc[q], s_red);
+    if (tid == 0) {
+        const long long np = ws.counts[0], nv = ws.counts[1];
+        const double policy_sum = -tot[0], value_sum = 0.5 * tot[1];
+        if (out) {
+            out->policy_sum = (float)policy_sum;
+            out->value_sum = (float)value_sum;
+            out->policy_loss = np > 0 ? (float)(policy_sum / (double)np) : 0.f;
+            out->value_loss = nv > 0 ? (float)(value_sum / (double)nv) : 0.f;
+            out->n_policy = np;
+            out->n_value = nv;
+        }
+        if (stats) {
+            stats->ratio_mean = np > 0 ? (float)(tot[2] / (double)np) : 0.f;
+            stats->policy_clip_frac = np > 0 ? (float)(tot[3] / (double)np) : 0.f;
+            stats->value_clip_frac = nv > 0 ? (float)(tot[4] / (double)nv) : 0.f;
+            stats->reserved = 0.f;
+            stats->n_policy_clipped = (long long)tot[3];
+            stats->n_value_clipped = (long long)tot[4];
+        }
+    }
+}
+
 }  // namespace tppo
 
 extern "C" size_t tppo_ppo_losses_workspace_bytes(int64_t n_resp, int64_t B) {
@@ -269,5 +509,71 @@ extern "C" int tppo_ppo_losses(const float* logp_new, const float* logp_old, con
     }
     hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(kChunkThreads), 0, s, ws.partials, groups,
                        resp_off, keep_len, done, (int)B, n_pol_ptr ? 1 : 0, n_val_ptr ? 1 : 0, out);
+    return launch_result();
+}
+
+extern "C" size_t tppo_ppo_losses_backward_workspace_bytes(int64_t n_resp, int64_t B) {
+    if (n_resp < 0 || B < 0) return 256;
+    return tppo::grad_ws_bytes(tppo::max_chunks(n_resp, B));
+}
+
+extern "C" int tppo_ppo_losses_backward(const float* logp_new, const float* logp_old, const float* adv,
+                                        const float* v_new, const float* v_old, const float* ret,
+                                        const int32_t* resp_off, const int32_t* keep_len,
+                                        const int32_t* done, int64_t B, int64_t n_resp, float eps_low,
+                                        float eps_high, float xi_low, float xi_high, float policy_scale,
+                                        float value_scale, int64_t policy_denominator,
+                                        int64_t value_denominator, float* grad_logp, float* grad_v,
+                                        tppo_loss_out* out, tppo_loss_stats* stats, void* workspace,
+                                        size_t workspace_bytes, int32_t* status, void* stream) {
+    using namespace tppo;
+    if (B < 0 || n_resp < 0 || n_resp > INT32_MAX - kChunkTokens || B > INT32_MAX / 4) return TPPO_ERR_SIZE;
+    if (!(eps_low >= 0.f) || !(eps_high >= 0.f) || !(xi_low >= 0.f) || !(xi_high >= 0.f))
+        return TPPO_ERR_PARAM;
+    if (!(policy_scale == policy_scale) || !(value_scale == value_scale)) return TPPO_ERR_PARAM;
+    const int n_pol_ptr = (logp_new != nullptr) + (logp_old != nullptr) + (adv != nullptr);
+    const int n_val_ptr = (v_new != nullptr) + (v_old != nullptr) + (ret != nullptr);
+    if ((n_pol_ptr != 0 && n_pol_ptr != 3) || (n_val_ptr != 0 && n_val_ptr != 3)) return TPPO_ERR_NULL;
+    if ((n_pol_ptr == 3) != (grad_logp != nullptr) || (n_val_ptr == 3) != (grad_v != nullptr)) return TPPO_ERR_NULL;
+    if (B > 0 && (!resp_off || !keep_len || !done)) return TPPO_ERR_NULL;
+    if (n_resp > 0 && B == 0) return TPPO_ERR_SIZE;
+    if (!workspace || !is_aligned(workspace, 256) ||
+        workspace_bytes < tppo_ppo_losses_backward_workspace_bytes(n_resp, B))
+        return TPPO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t cap64 = max_chunks(n_resp, B);
+    if (cap64 > INT32_MAX / 4) return TPPO_ERR_SIZE;
+    const int cap = (int)cap64;
+
+    // the list-building kernel also counts the two sets; it runs for an empty batch too (B = 0: zero counts)
+    int groups = 0;
+    if (B > 0) {
+        hipLaunchKernelGGL(loss_grad_init_kernel, dim3(1), dim3(kBuildThreads), 0, s, resp_off, keep_len, done,
+                           (int)B, (int)n_resp, cap, n_pol_ptr ? 1 : 0, n_val_ptr ? 1 : 0, workspace, status);
+        if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
+        if (n_resp > 0 && (n_pol_ptr || n_val_ptr)) {
+            GradParams gp;
+            gp.fwd.logp_new = logp_new; gp.fwd.logp_old = logp_old; gp.fwd.adv = adv;
+            gp.fwd.v_new = v_new; gp.fwd.v_old = v_old; gp.fwd.ret = ret;
+            gp.fwd.keep_len = keep_len; gp.fwd.done = done;
+            gp.fwd.cap = cap;
+            gp.fwd.ratio_lo = 1.f - eps_low; gp.fwd.ratio_hi = 1.f + eps_high;
+            gp.fwd.xi_low = xi_low; gp.fwd.xi_high = xi_high;
+            gp.grad_logp = grad_logp; gp.grad_v = grad_v;
+            gp.policy_scale = policy_scale; gp.value_scale = value_scale;
+            gp.policy_denominator = policy_denominator; gp.value_denominator = value_denominator;
+            groups = cap < kLossMaxGroups ? cap : kLossMaxGroups;
+            hipLaunchKernelGGL(loss_grad_kernel, dim3(groups), dim3(kChunkThreads), 0, s, gp, workspace);
+            if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
+        }
+    }
+    if (out || stats) {
+        if (B == 0) {       // no metadata kernel ran: counts are zero by definition
+            hipLaunchKernelGGL(loss_grad_zero_counts_kernel, dim3(1), dim3(64), 0, s, workspace, cap);
+            if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
+        }
+        hipLaunchKernelGGL(loss_grad_final_kernel, dim3(1), dim3(kChunkThreads), 0, s, workspace, cap, groups,
+                           out, stats);
+    }
     return launch_result();
 }

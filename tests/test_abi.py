@@ -68,6 +68,19 @@ def test_host_side_argument_errors(lib):
     assert lib.tppo_ppo_losses(256, None, 256, None, None, None, 256, 256, 256, 1, 4, 0.2, 0.2, 0.5, 0.6, 256, 256, 1 << 20, None, None) == N
     assert lib.tppo_ppo_losses(None, None, None, None, None, None, 256, 256, 256, 1, 4, 0.2, 0.2, 0.5, 0.6, None, 256, 1 << 20, None, None) == N
     assert lib.tppo_ppo_losses(None, None, None, None, None, None, 256, 256, 256, 1, 4, 0.2, 0.2, 0.5, 0.6, 256, None, 0, None, None) == W
+    # loss derivatives: same checks, plus gradient pointers that must match their halves, and the scales
+    bw = lib.tppo_ppo_losses_backward
+    assert bw(256, 256, 256, None, None, None, 256, 256, 256, 1, 4, 0.2, 0.2, 0.5, 0.6, 1.0, 1.0, 0, 0, None, None, None, None, 256, 1 << 20, None, None) == N
+    assert bw(256, 256, 256, None, None, None, 256, 256, 256, 1, 4, 0.2, 0.2, 0.5, 0.6, 1.0, 1.0, 0, 0, 256, 256, None, None, 256, 1 << 20, None, None) == N
+    assert bw(256, 256, 256, None, None, None, 256, 256, 256, 1, 4, 0.2, -1.0, 0.5, 0.6, 1.0, 1.0, 0, 0, 256, None, None, None, 256, 1 << 20, None, None) == P
+    assert bw(256, 256, 256, None, None, None, 256, 256, 256, 1, 4, 0.2, 0.2, 0.5, 0.6, float("nan"), 1.0, 0, 0, 256, None, None, None, 256, 1 << 20, None, None) == P
+    assert bw(256, 256, 256, None, None, None, 256, 256, 256, 1, 4, 0.2, 0.2, 0.5, 0.6, 1.0, 1.0, 0, 0, 256, None, None, None, None, 0, None, None) == W
+    assert bw(256, 256, 256, None, None, None, 256, 256, 256, 1, -4, 0.2, 0.2, 0.5, 0.6, 1.0, 1.0, 0, 0, 256, None, None, None, 256, 1 << 20, None, None) == S
+    assert lib.tppo_ppo_losses_backward_workspace_bytes(10, 1) >= 5 * 8
+    # diagnostic loop
+    assert lib.tppo_diag_mfma_rate(None, None, 10, None, None) == N
+    assert lib.tppo_diag_mfma_rate(256, 256, -1, None, None) == S
+    assert lib.tppo_diag_mfma_rate(264, 256, 10, None, None) == P          # operands not 16-byte aligned
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):

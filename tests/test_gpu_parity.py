@@ -422,6 +422,110 @@ def test_losses_split_batch_additivity(tp):
     assert g1["n_value"] + g2["n_value"] == full["n_value"]
 
 
+# ------------------------------------------------------------------ loss derivatives
+GRAD_RTOL = 1e-5      # fp32 exp, two products and one scale: a few 1e-7 relative; 1e-5 leaves a decade
+
+
+def run_loss_grads(tp, a, b, keep, skip=None, **kw):
+    d = {k: dev(v) for k, v in a.items()}
+    if skip == "policy":
+        d["logp_new"] = d["logp_old"] = d["adv"] = None
+    if skip == "value":
+        d["v_new"] = d["v_old"] = d["ret"] = None
+    g_lp, g_v, res, st = tp.tppo_ppo_losses_backward(
+        d["logp_new"], d["logp_old"], d["adv"], d["v_new"], d["v_old"], d["ret"], dev(b["resp_off"]),
+        dev(keep), dev(b["done"]), b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"], **kw)
+    return (None if g_lp is None else g_lp.cpu().numpy(), None if g_v is None else g_v.cpu().numpy(),
+            tp.read_loss_out(res), tp.read_loss_stats(st))
+
+
+def near_kinks(a, b, keep):
+    """Tokens whose branch (clipped or not) is decided by less than 1e-5: there the
+    fp32 decision of the kernel may legitimately differ from the fp64 one."""
+    pol, val = ofast.loss_masks(b["resp_off"], keep, b["done"])
+    f = {k: v.astype(np.float64) for k, v in a.items()}
+    with np.errstate(all="ignore"):
+        rho = np.exp(f["logp_new"] - f["logp_old"])
+        kp = pol & ((np.abs(rho - (1 - np.float32(b["eps_low"]))) < 1e-5) | (np.abs(rho - (1 + np.float32(b["eps_high"]))) < 1e-5))
+        lo, hi = f["v_old"] - b["xi_low"], f["v_old"] + b["xi_high"]
+        d0 = f["v_new"] - f["ret"]
+        d1 = np.clip(f["v_new"], lo, hi) - f["ret"]
+        scale = np.maximum(1.0, np.abs(f["v_new"]))
+        kv = val & ((np.abs(f["v_new"] - lo) < 1e-5 * scale) | (np.abs(f["v_new"] - hi) < 1e-5 * scale) |
+                    ((d0 != d1) & (np.abs(d0 * d0 - d1 * d1) < 1e-5 * np.maximum(d0 * d0, 1e-12))))
+    return kp, kv
+
+
+def assert_grads_close(got, ref, kink, unclipped_value):
+    """Element by element; at a near-kink token either branch's value is accepted."""
+    tol = GRAD_RTOL * np.abs(ref) + 1e-30
+    ok = np.abs(got - ref) <= tol
+    alt = kink & ((got == 0.0) | (np.abs(got - unclipped_value) <= GRAD_RTOL * np.abs(unclipped_value) + 1e-30))
+    bad = ~(ok | alt)
+    assert not bad.any(), (int(bad.sum()), np.flatnonzero(bad)[:5], got[bad][:5], ref[bad][:5])
+
+
+@pytest.mark.parametrize("name", ["tiny", "small", "longcot"])
+def test_loss_grads_configs(tp, name):
+    b = synth.make_batch(name, with_head=False)
+    a, keep = loss_inputs(b)
+    kw = dict(policy_scale=1.0, value_scale=0.5)
+    ref = ofast.ppo_loss_grads(a["logp_new"], a["logp_old"], a["adv"], a["v_new"], a["v_old"], a["ret"],
+                               b["resp_off"], keep, b["done"], float(np.float32(b["eps_low"])),
+                               float(np.float32(b["eps_high"])), float(np.float32(b["xi_low"])),
+                               float(np.float32(b["xi_high"])), **kw)
+    g_lp, g_v, losses, stats = run_loss_grads(tp, a, b, keep, **kw)
+    kp, kv = near_kinks(a, b, keep)
+    f = {k: v.astype(np.float64) for k, v in a.items()}
+    with np.errstate(all="ignore"):
+        free_p = -np.exp(f["logp_new"] - f["logp_old"]) * f["adv"] / max(ref["n_policy"], 1)
+        free_v = 0.5 * (f["v_new"] - f["ret"]) / max(ref["n_value"], 1)
+    assert_grads_close(g_lp, ref["grad_logp"], kp, free_p)
+    assert_grads_close(g_v, ref["grad_v"], kv, free_v)
+    pol, val = ofast.loss_masks(b["resp_off"], keep, b["done"])
+    assert not g_lp[~pol].any() and not g_v[~val].any()            # exact zeros outside the sets
+    assert abs(stats["n_policy_clipped"] - ref["n_policy_clipped"]) <= int(kp.sum())
+    assert abs(stats["n_value_clipped"] - ref["n_value_clipped"]) <= int(kv.sum())
+    assert abs(stats["ratio_mean"] - ref["ratio_mean"]) <= 1e-5 * ref["ratio_mean"]
+    assert ref["n_policy_clipped"] > 0 and ref["n_value_clipped"] > 0  # both branches are exercised
+    # the losses of the same pass agree with the forward entry point
+    fwd = run_losses(tp, a, b, keep)
+    for k in ("policy_loss", "value_loss"):
+        assert abs(losses[k] - fwd[k]) <= 1e-6 * abs(fwd[k]) + 1e-12
+    assert losses["n_policy"] == fwd["n_policy"] and losses["n_value"] == fwd["n_value"]
+    # deterministic
+    g2 = run_loss_grads(tp, a, b, keep, **kw)
+    assert np.array_equal(g2[0], g_lp) and np.array_equal(g2[1], g_v) and g2[3] == stats
+
+
+def test_loss_grads_poison_halves_denominators(tp):
+    b = synth.make_batch("small", with_head=False)
+    a, keep = loss_inputs(b)
+    g_lp, g_v, _, stats = run_loss_grads(tp, a, b, keep)
+    pol, val = ofast.loss_masks(b["resp_off"], keep, b["done"])
+    p = {k: v.copy() for k, v in a.items()}
+    for k in ("logp_new", "logp_old", "adv"):
+        p[k][~pol] = np.nan
+    for k in ("v_new", "v_old", "ret"):
+        p[k][~val] = np.inf
+    q_lp, q_v, _, qstats = run_loss_grads(tp, p, b, keep)
+    assert np.array_equal(q_lp, g_lp) and np.array_equal(q_v, g_v) and qstats == stats   # bit-identical
+    # one half only
+    only_p = run_loss_grads(tp, a, b, keep, skip="value")
+    only_v = run_loss_grads(tp, a, b, keep, skip="policy")
+    assert only_p[1] is None and np.array_equal(only_p[0], g_lp)
+    assert only_v[0] is None and np.array_equal(only_v[1], g_v)
+    # explicit denominators and scales: a plain rescaling of the same derivatives
+    n_pol, n_val = int(pol.sum()), int(val.sum())
+    s_lp, s_v, _, _ = run_loss_grads(tp, a, b, keep, policy_scale=2.0, value_scale=-1.0,
+                                     policy_denominator=4 * n_pol, value_denominator=2 * n_val)
+    assert np.allclose(s_lp, 0.5 * g_lp, rtol=1e-6, atol=0) and np.allclose(s_v, -0.5 * g_v, rtol=1e-6, atol=0)
+    # nothing kept, nothing finished: all zeros
+    none_done = dict(b, done=np.zeros_like(b["done"]))
+    z_lp, z_v, zl, zs = run_loss_grads(tp, a, none_done, np.zeros_like(keep))
+    assert not z_lp.any() and not z_v.any() and zl["n_policy"] == 0 and zs["n_policy_clipped"] == 0
+
+
 # ------------------------------------------------------------------ whole path
 def test_whole_path_tiny(tp):
     """select -> log-probs -> EGAE -> losses chained on device buffers, against
