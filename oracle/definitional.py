@@ -232,3 +232,28 @@ def ppo_loss_grads(logp_new, logp_old, adv, v_new, v_old, ret,
     return dict(grad_logp=g_lp, grad_v=g_v, n_policy=n_pol, n_value=n_val,
                 n_policy_clipped=pol_clipped, n_value_clipped=val_clipped,
                 ratio_mean=math.fsum(ratios) / len(ratios) if ratios else 0.0)
+
+
+# --------------------------------------------------------------------------
+# Derivatives of the kept tokens' log-probs (the policy update of Alg. 1 one
+# layer down): d/dh and d/dW of  L = sum_t g_t logp_t,  logp_t = z_t[a_t] - lse_t,
+# z_t = W h_t.  Since d lse / d z_v = softmax(z)_v, d logp_t / d z_v = [v = a_t] - p_v.
+# --------------------------------------------------------------------------
+def token_logprob_grads(hidden, w_head, sel_rows, sel_targets, grad_logp):
+    """Returns (grad_hidden, grad_w): grad_hidden[t] = sum_v dz[t][v] W[v],
+    grad_w[v] = sum_t dz[t][v] h_t with dz[t][v] = g_t ([v = a_t] - p_t[v]).
+    Brute force; lists of lists in, lists of lists out."""
+    V, H = len(w_head), len(w_head[0])
+    grad_w = [[0.0] * H for _ in range(V)]
+    grad_hidden = []
+    for row, tgt, g in zip(sel_rows, sel_targets, grad_logp):
+        h = hidden[row]
+        z = [math.fsum(hk * wk for hk, wk in zip(h, w_v)) for w_v in w_head]
+        zmax = max(z)
+        total = math.fsum(math.exp(zv - zmax) for zv in z)
+        dz = [g * ((1.0 if v == tgt else 0.0) - math.exp(z[v] - zmax) / total) for v in range(V)]
+        grad_hidden.append([math.fsum(dz[v] * w_head[v][k] for v in range(V)) for k in range(H)])
+        for v in range(V):
+            for k in range(H):
+                grad_w[v][k] += dz[v] * h[k]
+    return grad_hidden, grad_w

@@ -217,3 +217,45 @@ def ppo_loss_grads(logp_new, logp_old, adv, v_new, v_old, ret,
         val_clipped = int((~unclipped).sum())
     return dict(grad_logp=g_lp, grad_v=g_v, n_policy=n_pol, n_value=n_val,
                 n_policy_clipped=pol_clipped, n_value_clipped=val_clipped, ratio_mean=ratio_mean)
+
+
+def token_logprob_grads(hidden, w_head, sel_rows, sel_targets, grad_logp, row_block=256, want_w=True,
+                        return_abs_bounds=False):
+    """Derivatives of L = sum_t g_t logp_t with respect to the kept hidden rows
+    and the head matrix: with z = W h, p = softmax(z),
+        dz[t, v] = g_t ([v = target_t] - p[t, v]),
+        grad_hidden[t] = dz[t] W,    grad_w = dz^T Hid.
+    All logits of a block of rows are formed in full, fp64 throughout.  With
+    ``return_abs_bounds`` also returns |dz| |W| and |dz|^T |Hid| (the sums of
+    the magnitudes of the terms of each output element), which tests use to
+    bound the effect of rounding dz."""
+    sel_rows = np.asarray(sel_rows, dtype=np.int64)
+    sel_targets = np.asarray(sel_targets, dtype=np.int64)
+    g = decode(grad_logp)
+    M = sel_rows.shape[0]
+    V, H = w_head.shape
+    w = decode(w_head)
+    grad_hidden = np.zeros((M, H))
+    grad_w = np.zeros((V, H)) if want_w else None
+    abs_h = np.zeros((M, H)) if return_abs_bounds else None
+    abs_w = np.zeros((V, H)) if (return_abs_bounds and want_w) else None
+    for r0 in range(0, M, row_block):
+        r1 = min(r0 + row_block, M)
+        h = decode(hidden[sel_rows[r0:r1]])
+        z = h @ w.T
+        z -= z.max(axis=1, keepdims=True)
+        p = np.exp(z)
+        p /= p.sum(axis=1, keepdims=True)
+        dz = -p
+        dz[np.arange(r1 - r0), sel_targets[r0:r1]] += 1.0
+        dz *= g[r0:r1, None]
+        grad_hidden[r0:r1] = dz @ w
+        if want_w:
+            grad_w += dz.T @ h
+        if return_abs_bounds:
+            abs_h[r0:r1] = np.abs(dz) @ np.abs(w)
+            if want_w:
+                abs_w += np.abs(dz).T @ np.abs(h)
+    if return_abs_bounds:
+        return grad_hidden, grad_w, abs_h, abs_w
+    return grad_hidden, grad_w

@@ -508,3 +508,91 @@ def test_loss_grads_masks_poison_and_counts():
     e = ofast.ppo_loss_grads(np.zeros(3), np.zeros(3), np.ones(3), np.zeros(3), np.zeros(3), np.ones(3),
                              [0, 3], [0], [0], 0.2, 0.28, 0.5, 0.6)
     assert not e["grad_logp"].any() and not e["grad_v"].any() and e["ratio_mean"] == 0.0
+
+
+# ------------------------------------------------------------------ log-prob derivatives
+def _head_case(rng, M=7, n_rows=9, V=11, H=5):
+    hidden = rng.normal(size=(n_rows, H))
+    w = rng.normal(0, 0.5, size=(V, H))
+    rows = rng.integers(0, n_rows, size=M)
+    tg = rng.integers(0, V, size=M)
+    g = rng.normal(size=M)
+    return hidden, w, rows, tg, g
+
+
+def test_logprob_grads_fast_equals_definitional():
+    hidden, w, rows, tg, g = _head_case(np.random.default_rng(31))
+    dh_d, dw_d = odef.token_logprob_grads(hidden.tolist(), w.tolist(), rows.tolist(), tg.tolist(), g.tolist())
+    dh_f, dw_f = ofast.token_logprob_grads(hidden, w, rows, tg, g)
+    assert np.allclose(dh_f, np.array(dh_d), rtol=1e-12, atol=1e-14)
+    assert np.allclose(dw_f, np.array(dw_d), rtol=1e-12, atol=1e-14)
+
+
+def test_logprob_grads_match_autograd():
+    import torch
+    hidden, w, rows, tg, g = _head_case(np.random.default_rng(32), M=13, n_rows=13, V=17, H=6)
+    rows = np.arange(13)                                   # distinct rows: row derivative = hidden derivative
+    ht = torch.tensor(hidden, dtype=torch.float64, requires_grad=True)
+    wt = torch.tensor(w, dtype=torch.float64, requires_grad=True)
+    logp = torch.log_softmax(ht[torch.tensor(rows)] @ wt.T, dim=1)[torch.arange(13), torch.tensor(tg)]
+    (logp * torch.tensor(g)).sum().backward()
+    dh, dw = ofast.token_logprob_grads(hidden, w, rows, tg, g)
+    assert np.allclose(dh, ht.grad.numpy(), rtol=1e-12, atol=1e-14)
+    assert np.allclose(dw, wt.grad.numpy(), rtol=1e-12, atol=1e-14)
+
+
+def test_logprob_grads_match_finite_differences_of_the_pinned_forward():
+    hidden, w, rows, tg, g = _head_case(np.random.default_rng(33), M=4, n_rows=4, V=6, H=3)
+    rows = np.arange(4)
+    dh, dw = ofast.token_logprob_grads(hidden, w, rows, tg, g)
+    eps = 1e-6
+
+    def loss(hid, wm):
+        lp, _ = ofast.token_logprobs(hid, wm, rows, tg)
+        return float((lp * g).sum())
+    for t in range(4):
+        for k in range(3):
+            up, dn = hidden.copy(), hidden.copy()
+            up[t, k] += eps
+            dn[t, k] -= eps
+            assert abs((loss(up, w) - loss(dn, w)) / (2 * eps) - dh[t, k]) < 1e-8
+    for v in range(6):
+        for k in range(3):
+            up, dn = w.copy(), w.copy()
+            up[v, k] += eps
+            dn[v, k] -= eps
+            assert abs((loss(hidden, up) - loss(hidden, dn)) / (2 * eps) - dw[v, k]) < 1e-8
+
+
+def test_logprob_grads_closed_forms_and_invariants():
+    rng = np.random.default_rng(34)
+    hidden, w, rows, tg, g = _head_case(rng, M=9, n_rows=5, V=8, H=4)       # rows repeat
+    dh, dw, abs_h, abs_w = ofast.token_logprob_grads(hidden, w, rows, tg, g, return_abs_bounds=True)
+    # softmax derivative sums to zero over the vocabulary: so do the columns of grad_w
+    assert np.allclose(dw.sum(axis=0), 0.0, atol=1e-13)
+    assert np.all(np.abs(dh) <= abs_h + 1e-15) and np.all(np.abs(dw) <= abs_w + 1e-15)
+    # zero head matrix: uniform softmax, grad_hidden = 0, grad_w[v] = sum_t g_t ([v = a_t] - 1/V) h_t
+    dh0, dw0 = ofast.token_logprob_grads(hidden, np.zeros_like(w), rows, tg, g)
+    assert not dh0.any()
+    expect = np.zeros_like(w)
+    for t in range(9):
+        for v in range(8):
+            expect[v] += g[t] * ((1.0 if v == tg[t] else 0.0) - 1.0 / 8) * hidden[rows[t]]
+    assert np.allclose(dw0, expect, rtol=1e-13, atol=1e-15)
+    # a vocabulary of one entry: log-prob is identically 0, every derivative vanishes
+    dh1, dw1 = ofast.token_logprob_grads(hidden, w[:1], rows, np.zeros(9, int), g)
+    assert np.allclose(dh1, 0.0, atol=1e-15) and np.allclose(dw1, 0.0, atol=1e-15)
+    # linear in g; tokens with g = 0 contribute nothing
+    dh2, dw2 = ofast.token_logprob_grads(hidden, w, rows, tg, 2.0 * g)
+    assert np.allclose(dh2, 2 * dh) and np.allclose(dw2, 2 * dw)
+    gz = g.copy()
+    gz[3:] = 0.0
+    dh3, dw3 = ofast.token_logprob_grads(hidden, w, rows, tg, gz)
+    dh4, dw4 = ofast.token_logprob_grads(hidden, w, rows[:3], tg[:3], g[:3])
+    assert np.allclose(dh3[:3], dh4) and not dh3[3:].any() and np.allclose(dw3, dw4)
+    # bf16 inputs are decoded, not cast
+    from paper_2506_15050_amd.synth import f32_to_bf16_bits
+    hb, wb = f32_to_bf16_bits(hidden.astype(np.float32)), f32_to_bf16_bits(w.astype(np.float32))
+    dh5, dw5 = ofast.token_logprob_grads(hb, wb, rows, tg, g)
+    dh6, dw6 = ofast.token_logprob_grads(ofast.decode(hb), ofast.decode(wb), rows, tg, g)
+    assert np.array_equal(dh5, dh6) and np.array_equal(dw5, dw6)
