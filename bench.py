@@ -215,6 +215,26 @@ def main():
                                      "GB/s": bwd_bytes / (bwd_ms * 1e-3) / 1e9,
                                      "clip_stats": tp.read_loss_stats(stats_out)}}
 
+    if has_head:
+        # derivatives of the log-probs with respect to hidden rows and head matrix (three sweeps of the same size)
+        _, lse0 = tp.tppo_token_logprobs(hidden, w_head, sel["sel_rows"], sel["sel_targets"], M=M)
+        g_tok = grads[0][sel["sel_resp_idx"][:M].long()].contiguous()
+        ws_hb = tp._workspace(lib.tppo_token_logprobs_backward_workspace_bytes(M, H, V, tp.TPPO_BF16), "cuda")
+        grad_w = torch.empty(V, H, dtype=torch.float32, device="cuda")
+        run_hb = lambda: tp.tppo_token_logprobs_backward(hidden, w_head, sel["sel_rows"], sel["sel_targets"],
+                                                         lse0, g_tok, M=M, grad_w=grad_w, workspace=ws_hb)
+        run_hb()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(2):
+            run_hb()
+        e1.record()
+        torch.cuda.synchronize()
+        hb_ms = e0.elapsed_time(e1) / 2
+        extra["token_logprobs_backward"] = {"ms": hb_ms, "flop": 6.0 * M * V * H,
+                                            "TFLOP/s": 6.0 * M * V * H / (hb_ms * 1e-3) / 1e12}
+        del ws_hb, grad_w
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(b, M, args.cpu_sample_rows, has_head)

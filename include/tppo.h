@@ -254,6 +254,40 @@ int tppo_ppo_losses_backward(const float* logp_new, const float* logp_old, const
                              int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * tppo_token_logprobs_backward -- derivatives of the kept tokens' log-probs
+ * (the quantity inside the ratio of Eq. (ppoloss)) with respect to the hidden
+ * rows and the head matrix: the policy update of Alg. 1 carried one layer down.
+ * With z = W h and logp_t = z_t[target_t] - lse_t,
+ *     dz[t, v]          = g_t * ([v == target_t] - exp(z[t, v] - lse_t)),
+ *     grad_hidden[t, :] = sum_v dz[t, v] * W[v, :],
+ *     grad_w[v, :]     (+)= sum_t dz[t, v] * hidden[sel_rows[t], :],
+ * where g_t is the upstream derivative d L / d logp_t (for instance grad_logp
+ * of tppo_ppo_losses_backward) and lse_t the forward pass's log-sum-exp.  No
+ * logits are kept from the forward pass: they are recomputed tile by tile.
+ * dz is rounded to bf16 (round to nearest even) before the two products, which
+ * accumulate in fp32.
+ *
+ * in : hidden, w_head, sel_rows, sel_targets, M as in tppo_token_logprobs
+ *      (bf16 only; H % 64 == 0, leading dimensions % 8 == 0, 16-byte aligned
+ *      bases, else TPPO_ERR_PARAM; fp32 -> TPPO_ERR_DTYPE);
+ *      lse, grad_logp  device fp32; token t's entries are element in_index[t]
+ *                      (in_index NULL: element t).
+ * out: grad_hidden[M, H]  device fp32, row t belongs to hidden row sel_rows[t];
+ *      grad_w[V, H]       device fp32, overwritten, or added to when
+ *                         accumulate_w != 0.  Either may be NULL to skip it.
+ * workspace: at least tppo_token_logprobs_backward_workspace_bytes; a larger
+ *      one lets more tokens (up to 16384) go through per chunk.
+ */
+size_t tppo_token_logprobs_backward_workspace_bytes(int64_t M, int64_t H, int64_t V, tppo_dtype dt);
+int tppo_token_logprobs_backward(const void* hidden, int64_t n_rows, int64_t H, int64_t ld_hidden,
+                                 const void* w_head, int64_t V, int64_t ld_w, tppo_dtype dt,
+                                 const int32_t* sel_rows, const int32_t* sel_targets, int64_t M,
+                                 const float* lse, const float* grad_logp, const int32_t* in_index,
+                                 float* grad_hidden, float* grad_w, int32_t accumulate_w,
+                                 void* workspace, size_t workspace_bytes,
+                                 int32_t* status, void* stream);
+
+/* ---------------------------------------------------------------------------
  * tppo_diag_mfma_rate -- a measuring stick, not a step of the method: runs the
  * inner loop of the LM-head kernel (v_mfma_f32_32x32x16_bf16, 8 wavefronts per
  * workgroup, one workgroup per CU, 16 MFMAs per wavefront and iteration) on

@@ -37,6 +37,11 @@ _SIGNATURES = {
     "tppo_ppo_losses_backward_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
     "tppo_ppo_losses_backward": (ctypes.c_int, [_c_ptr] * 9 + [_c_i64, _c_i64] + [_c_f32] * 6 +
                                  [_c_i64, _c_i64] + [_c_ptr] * 5 + [_c_size, _c_ptr, _c_ptr]),
+    "tppo_token_logprobs_backward_workspace_bytes": (_c_size, [_c_i64, _c_i64, _c_i64, ctypes.c_int]),
+    "tppo_token_logprobs_backward": (ctypes.c_int, [_c_ptr, _c_i64, _c_i64, _c_i64, _c_ptr, _c_i64, _c_i64,
+                                                    ctypes.c_int, _c_ptr, _c_ptr, _c_i64, _c_ptr, _c_ptr,
+                                                    _c_ptr, _c_ptr, _c_ptr, _c_i32, _c_ptr, _c_size, _c_ptr,
+                                                    _c_ptr]),
     "tppo_diag_mfma_rate": (ctypes.c_int, [_c_ptr, _c_ptr, _c_i64, ctypes.POINTER(ctypes.c_double), _c_ptr]),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -193,6 +198,36 @@ def read_loss_out(res):
     raw = bytes(res.cpu().numpy().tobytes())
     s = LossOut.from_buffer_copy(raw)
     return {name: getattr(s, name) for name, _ in LossOut._fields_}
+
+
+def tppo_token_logprobs_backward(hidden, w_head, sel_rows, sel_targets, lse, grad_logp, M=None,
+                                 in_index=None, want_hidden=True, want_w=True, grad_w=None,
+                                 accumulate_w=False, status=None, workspace=None):
+    """Derivatives of the kept tokens' log-probs with respect to the hidden rows
+    ([M, H] fp32, compact order) and the head matrix ([V, H] fp32)."""
+    lib = load()
+    assert hidden.is_cuda and w_head.is_cuda and hidden.dtype == w_head.dtype == torch.bfloat16
+    assert hidden.stride(1) == 1 and w_head.stride(1) == 1
+    n_rows, H = hidden.shape
+    V = w_head.shape[0]
+    M = sel_rows.numel() if M is None else int(M)
+    dev = hidden.device
+    g_h = torch.empty(M, H, dtype=torch.float32, device=dev) if want_hidden else None
+    if want_w and grad_w is None:
+        grad_w = torch.empty(V, H, dtype=torch.float32, device=dev)
+    if not want_w:
+        grad_w = None
+    ws = workspace
+    if ws is None:
+        ws = _workspace(lib.tppo_token_logprobs_backward_workspace_bytes(M, H, V, TPPO_BF16), dev)
+    rc = lib.tppo_token_logprobs_backward(_ptr(hidden), n_rows, H, hidden.stride(0), _ptr(w_head), V,
+                                          w_head.stride(0), TPPO_BF16, _ptr(_dev_i32(sel_rows)),
+                                          _ptr(_dev_i32(sel_targets)), M, _ptr(_dev_f32(lse)),
+                                          _ptr(_dev_f32(grad_logp)), _ptr(in_index), _ptr(g_h), _ptr(grad_w),
+                                          1 if accumulate_w else 0, _ptr(ws), ws.numel(), _ptr(status),
+                                          _stream())
+    _check(rc, "tppo_token_logprobs_backward")
+    return g_h, grad_w
 
 
 class LossStats(ctypes.Structure):

@@ -18,9 +18,7 @@
 // layout the MFMA wants for both, so tiles are staged into LDS as 16-byte
 // chunks with an XOR swizzle of the chunk index (conflict-free ds_read_b128)
 // and read back as operand fragments directly.
-#include <stdlib.h>
-
-#include "common.h"
+#include "head_tile.h"
 
 namespace tppo {
 
@@ -94,112 +92,6 @@ __global__ __launch_bounds__(kGenThreads) void head_generic_kernel(
 }
 
 // ------------------------------------------------------------------ MFMA path
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-
-constexpr int kMaxSplits = 64;
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kNegBig = -3.0e38f;    // finite stand-in for -inf (keeps exp2(m - m') NaN-free)
-
-struct HeadParams {
-    const uint16_t* hidden;
-    const uint16_t* w;
-    const int32_t* sel_rows;
-    const int32_t* sel_targets;
-    const int64_t* m_actual;
-    float* part;                       // [3][splits][M]: max (log2 domain), sumexp, target logit
-    int64_t n_rows, ld_h, ld_w, M;
-    int H, V, row_tiles, splits, vocab_tiles;
-    int unit_splits, unit_cols, n_units;   // persistent schedule, see head_mfma_kernel
-    int unit_rows, col_major;              // col_major: the 8 XCDs sweep the same vocabulary slice together
-    int32_t* unit_arrivals;                // [n_units] zeroed before the launch
-};
-
-// Compile-time shape of one kernel variant: a kTileV x kTileT (vocabulary x
-// tokens) output tile per workgroup, kWavesV x kWavesT wavefronts, kBK
-// K-elements per LDS stage, a ring of kStages stages.
-//
-// LDS staging layout.  A stage holds kTileV + kTileT rows of kBK bf16 (W rows
-// first, then token rows), each row as kBK/8 chunks of 16 bytes.  Chunk c of
-// row r sits in slot c ^ swz(r).  The LDS serves 64 banks x 4 B = 256 B per
-// cycle, i.e. 16 lanes of a ds_read_b128; those 16 lanes read the same chunk
-// of 16 consecutive rows, and the swizzle spreads them over all 16 slots of
-// the 256-byte bank window (measured: SQ_LDS_BANK_CONFLICT = 0).
-template <int TV, int TT, int WV, int WT, int BK, int ST, int WGS_PER_CU, int SPREAD = 0>
-struct HeadCfg {
-    static constexpr int kTileV = TV, kTileT = TT, kWavesV = WV, kWavesT = WT, kBK = BK, kStages = ST;
-    static constexpr int kWgsPerCu = WGS_PER_CU;
-    // 0: a wave issues the transfers of a stage back to back; n > 0: one by one
-    // between its next n MFMAs, so the wave never sits in a full memory queue
-    static constexpr int kSpread = SPREAD;
-    static constexpr int kWaves = WV * WT, kThreads = kWaves * 64;
-    static constexpr int kWaveV = TV / WV, kWaveT = TT / WT;              // wave tile
-    static constexpr int kVB = kWaveV / 32, kTB = kWaveT / 32;            // 32x32 blocks per wave
-    static constexpr int kRowBytes = BK * 2, kChunks = BK / 8;
-    static constexpr int kRows = TV + TT;
-    static constexpr int kStageBytes = kRows * kRowBytes;
-    static constexpr int kLdsBytes = ST * kStageBytes;
-    static constexpr int kRowsPerDma = 1024 / kRowBytes;                  // one wave-wide 16 B/lane transfer
-    static constexpr int kDmaPerStage = kRows / kRowsPerDma;
-    static constexpr int kDmaPerWave = kDmaPerStage / kWaves;
-    static constexpr int kKSteps = BK / 16;
-    static_assert(kDmaPerWave * kWaves == kDmaPerStage, "transfers must divide evenly over the waves");
-    static_assert(TV % kRowsPerDma == 0, "a transfer may not straddle W and token rows");
-    static_assert(kKSteps % 2 == 0, "fragment double buffering assumes an even number of K steps");
-    static_assert(WV * 3 * TT * 4 <= kLdsBytes, "merge buffer must fit in the idle stages");
-    static_assert(SPREAD == 0 || (ST == 2 && SPREAD <= kKSteps * kVB * kTB),
-                  "spread issue: two stages, at most one stage's worth of MFMAs");
-    __device__ static __forceinline__ int swz(int r) {
-        return BK == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3);
-    }
-    __device__ static __forceinline__ int chunk_off(int r, int c) {
-        return r * kRowBytes + ((c ^ swz(r)) << 4);
-    }
-};
-
-// One wave-wide global -> LDS transfer without a register round trip: lane l's
-// 16 bytes at `src` land at LDS byte address lds_base + 16*l (lds_base is
-// wave-uniform and goes through M0).  Written as inline assembly so that the
-// transfer stays asynchronous: completion is awaited by hand (vmcnt) right
-// before the workgroup barrier that publishes the stage.
-__device__ __forceinline__ void dma_16b_per_lane(const void* src, unsigned lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(lds_base), "v"(src)
-                 : "memory", "m0");
-}
-
-// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding)
-constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
-
-// Schedule.  The grid is persistent: 256 workgroups, one per CU, hardware id
-// b runs on XCD b % 8 (ids go round-robin over the 8 XCDs, each with its own
-// L2).  The work is cut into units of 8 token tiles x unit_splits (<= 4)
-// vocabulary splits; the 32 workgroups of an XCD take one unit together, one
-// (token tile, split) pair each, then the XCD's next unit.  Inside a unit every
-// W tile is wanted by 8 workgroups and every hidden tile by up to 4 at the same
-// step of the same sweep, so one of them pays the L2 miss and the others hit;
-// equal work per pair keeps them in step for the whole sweep, which a
-// free-running grid of independent workgroups does not.  The splits of a unit
-// may differ by one vocabulary tile, so the workgroups of an XCD re-align at
-// every unit boundary with an arrival counter.  That wait is only a hint for
-// the caches: it is bounded and falls through, and nothing depends on it.
-// Across XCDs the units are handed out so that the 8 XCDs sweep the SAME
-// vocabulary slice at the same time, each for its own 8 token tiles: W then
-// leaves HBM once per round instead of once per XCD (the later readers find it
-// in the memory-side cache), which is worth 1-2 % at the chip's power limit.
-constexpr int kAlignSpins = 4096;
-__device__ __forceinline__ void align_unit(int32_t* arrivals, int expected) {
-    if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(arrivals, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (int spin = 0; spin < kAlignSpins; ++spin) {
-            if (__hip_atomic_load(arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= expected) break;
-            __builtin_amdgcn_s_sleep(8);
-        }
-    }
-    __syncthreads();
-}
 // Per-lane running log-softmax state of the kTB token columns a lane owns, and
 // the two steps that use it: folding a finished 256-wide vocabulary tile, and
 // the final merge across lane halves / waves.
@@ -221,8 +113,10 @@ struct LaneSoftmax {
 
     // acc holds logits: lane owns column lane%32 of block tb; entry e of block vb
     // is vocabulary id v_wave + vb*32 + (e/4)*8 + (lane/32)*4 + e%4.  Clears acc.
-    __device__ __forceinline__ void fold(f32x16 (&acc)[C::kVB][C::kTB], int vt, int wv, int frag_half, int V) {
+    __device__ __forceinline__ void fold(f32x16 (&acc)[C::kVB][C::kTB], const HeadParams& p, int64_t, int64_t,
+                                         int vt, int wv, int, int lane) {
         constexpr int kVB = C::kVB, kTB = C::kTB;
+        const int frag_half = lane >> 5, V = p.V;
         const int v_wave = vt * C::kTileV + wv * C::kWaveV;
         const int v_lane = v_wave + frag_half * 4;
         if (vt * C::kTileV + C::kTileV > V) {                       // ragged last tile: mask ids >= V
@@ -292,7 +186,7 @@ struct LaneSoftmax {
     // Merge the two lane halves (same token, different vocabulary rows), then
     // the kWavesV waves that share a token, and write the split's triple.
     // s_merge: LDS scratch [kWavesV][3][kTileT] floats, idle at this point.
-    __device__ __forceinline__ void merge_store(const HeadParams& p, float* s_merge, int64_t tok0, int64_t m_eff,
+    __device__ __forceinline__ void finish(const HeadParams& p, float* s_merge, int64_t tok0, int64_t m_eff,
                                                 int sp, int wv, int wt, int lane, int tid) {
         constexpr int kTileT = C::kTileT;
 #pragma unroll
@@ -333,213 +227,6 @@ struct LaneSoftmax {
     }
 };
 
-template <class C>
-__global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head_mfma_kernel(HeadParams p) {
-    constexpr int kTileV = C::kTileV, kTileT = C::kTileT, kWaveV = C::kWaveV, kWaveT = C::kWaveT;
-    constexpr int kVB = C::kVB, kTB = C::kTB, kBK = C::kBK, kStages = C::kStages;
-    constexpr int kDmaPerWave = C::kDmaPerWave, kKSteps = C::kKSteps;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int tile_in_unit = slot & 7, split_in_unit = slot >> 3;
-    if (split_in_unit >= p.unit_splits) return;
-    const int64_t m_eff = p.m_actual ? min(p.M, *p.m_actual) : p.M;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wv = wave / C::kWavesT, wt = wave % C::kWavesT;
-    const int frag_row = lane & 31, frag_half = lane >> 5;
-    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
-
-    for (int unit = xcd; unit < p.n_units; unit += 8) {
-    int unit_row, unit_col;
-    if (p.col_major) {
-        // round j of the grid: rows 8g .. 8g+7 (one per XCD) of column j % unit_cols; the rows
-        // left over after the last full group of 8 are dealt out column by column
-        const int j = unit >> 3, full = p.unit_rows >> 3, left = p.unit_rows & 7;
-        if (j < full * p.unit_cols) {
-            unit_row = (j / p.unit_cols) * 8 + xcd;
-            unit_col = j % p.unit_cols;
-        } else {
-            const int t = (j - full * p.unit_cols) * 8 + xcd;
-            unit_col = t / left;
-            unit_row = full * 8 + t - unit_col * left;
-        }
-    } else {
-        unit_row = unit / p.unit_cols;
-        unit_col = unit - unit_row * p.unit_cols;
-    }
-    const int rt = unit_row * 8 + tile_in_unit, sp = unit_col * p.unit_splits + split_in_unit;
-    const int64_t tok0 = (int64_t)rt * kTileT;
-    if (unit >= 8) align_unit(p.unit_arrivals + unit, 8 * p.unit_splits);   // the first unit starts aligned
-    if (rt >= p.row_tiles || tok0 >= m_eff) continue;       // uniform over the workgroup
-    const int vt_begin = (int)((int64_t)p.vocab_tiles * sp / p.splits);
-    const int vt_end = (int)((int64_t)p.vocab_tiles * (sp + 1) / p.splits);
-    const int k_tiles = p.H / kBK;
-    const int total_iters = (vt_end - vt_begin) * k_tiles;
-
-    // ---- loader role: transfers wave*kDmaPerWave + q, each kRowsPerDma staged rows
-    const int ld_row0 = wave * kDmaPerWave * C::kRowsPerDma + lane / C::kChunks;   // + q * kRowsPerDma
-    const int ld_slot = lane % C::kChunks;
-    const uint16_t* src[kDmaPerWave];
-    int issue_vt = vt_begin, issue_kt = 0, issue_stage = 0, issue_kpos = 0;
-    auto point_at_tile = [&](int vt, bool w_only) {
-#pragma unroll
-        for (int q = 0; q < kDmaPerWave; ++q) {
-            const int r = ld_row0 + q * C::kRowsPerDma;                 // staged row; < kTileV means a W row
-            const int chunk = (ld_slot ^ C::swz(r)) * 8;
-            if (r < kTileV) {
-                const int64_t v = min((int64_t)vt * kTileV + r, (int64_t)p.V - 1);
-                src[q] = p.w + v * p.ld_w + chunk;
-            } else if (!w_only) {
-                const int64_t t = min(tok0 + (r - kTileV), m_eff - 1);
-                int64_t row = p.sel_rows[t];
-                row = min(max(row, (int64_t)0), p.n_rows - 1);
-                src[q] = p.hidden + row * p.ld_h + chunk;
-            }
-        }
-    };
-    point_at_tile(vt_begin, false);
-    auto issue_one = [&](int q) {
-        const unsigned dst = lds_base + issue_stage * C::kStageBytes + wave * kDmaPerWave * 1024;
-        dma_16b_per_lane(src[q] + issue_kpos, dst + q * 1024);
-    };
-    auto issue_advance = [&]() {        // next (vocabulary tile, k tile) in sweep order
-        issue_kpos += kBK;
-        if (++issue_stage == kStages) issue_stage = 0;
-        if (++issue_kt == k_tiles) {
-            issue_kt = 0;
-            issue_kpos = 0;
-            ++issue_vt;
-            point_at_tile(min(issue_vt, vt_end - 1), true);
-        }
-    };
-    auto issue = [&]() {
-#pragma unroll
-        for (int q = 0; q < kDmaPerWave; ++q) issue_one(q);
-        issue_advance();
-    };
-
-    LaneSoftmax<C> sm;
-    sm.init(p, tok0, m_eff, wt, lane);
-
-    f32x16 acc[kVB][kTB];
-#pragma unroll
-    for (int vb = 0; vb < kVB; ++vb)
-#pragma unroll
-        for (int tb = 0; tb < kTB; ++tb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
-
-    bf16x8 fa[2][kVB], fb[2][kTB];
-    auto load_frags = [&](int stage, int ks, int buf) {
-        const unsigned char* st = smem + stage * C::kStageBytes;
-        const unsigned char* a_base = st + (wv * kWaveV) * C::kRowBytes;
-        const unsigned char* b_base = st + (kTileV + wt * kWaveT) * C::kRowBytes;
-        const int c = ks * 2 + frag_half;
-#pragma unroll
-        for (int vb = 0; vb < kVB; ++vb)
-            fa[buf][vb] = *reinterpret_cast<const bf16x8*>(a_base + C::chunk_off(vb * 32 + frag_row, c));
-#pragma unroll
-        for (int tb = 0; tb < kTB; ++tb)
-            fb[buf][tb] = *reinterpret_cast<const bf16x8*>(b_base + C::chunk_off(tb * 32 + frag_row, c));
-    };
-    auto mfma_step = [&](int buf) {
-#pragma unroll
-        for (int vb = 0; vb < kVB; ++vb)
-#pragma unroll
-            for (int tb = 0; tb < kTB; ++tb)
-                acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][vb], fb[buf][tb], acc[vb][tb], 0, 0, 0);
-    };
-    // The same K step with this wave's transfers first .. first + n - 1 of the
-    // stage being refilled issued between the MFMAs (`on` is workgroup-uniform).
-    // Transfer j of the stage being refilled follows MFMA number
-    // floor(j * kSpread / kDmaPerWave), counted from the barrier that freed it.
-    constexpr int kMfmaPerStep = kVB * kTB;
-    constexpr int kSpreadSteps = (C::kSpread + kMfmaPerStep - 1) / kMfmaPerStep;   // K steps the issue touches
-    auto mfma_step_issuing = [&](int buf, int part, bool on) {
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int vb = 0; vb < kVB; ++vb)
-#pragma unroll
-            for (int tb = 0; tb < kTB; ++tb) {
-                acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][vb], fb[buf][tb], acc[vb][tb], 0, 0, 0);
-                const int g = part * kMfmaPerStep + vb * kTB + tb;
-                if (on) {
-#pragma unroll
-                    for (int j = 0; j < kDmaPerWave; ++j)
-                        if (C::kSpread && j * C::kSpread / kDmaPerWave == g) issue_one(j);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-    };
-
-    // ---- fill the ring, publish stage 0, start on its first fragments
-#pragma unroll
-    for (int s = 0; s < kStages - 1; ++s)
-        if (s < total_iters) issue();
-    if (total_iters >= kStages - 1)
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kDmaPerWave));
-    else
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    __syncthreads();
-    if (kStages - 1 < total_iters) issue();
-    load_frags(0, 0, 0);
-
-    int kt = 0, vt = vt_begin, stage = 0;
-    bool refill = false;                // spread issue: transfers of the stage freed at the last barrier are pending
-    for (int it = 0; it < total_iters; ++it) {
-#pragma unroll
-        for (int ks = 0; ks + 1 < kKSteps; ++ks) {
-            load_frags(stage, ks + 1, (ks + 1) & 1);
-            if (C::kSpread && ks + 1 < kSpreadSteps) {
-                mfma_step_issuing(ks & 1, ks + 1, refill);
-                if (ks + 2 == kSpreadSteps && refill) issue_advance();
-            } else {
-                mfma_step(ks & 1);
-            }
-        }
-        // The stage's last fragments are in registers.  Hand the stage back,
-        // publish the next one and fetch its first fragments BEFORE issuing the
-        // last MFMAs, so the barrier and the LDS latency hide behind them.
-        const int next_stage = stage + 1 == kStages ? 0 : stage + 1;
-        refill = false;
-        if (it + 1 < total_iters) {
-            if (total_iters - it - 2 >= kStages - 2)
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm((kStages - 2) * kDmaPerWave));
-            else
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            __syncthreads();            // stage it+1 landed for everyone; everyone left stage it
-            if (it + kStages < total_iters) {
-                if (C::kSpread) refill = true;
-                else issue();
-            }
-            load_frags(next_stage, 0, 0);
-        }
-        if (C::kSpread) {
-            mfma_step_issuing((kKSteps - 1) & 1, 0, refill);
-            if (kSpreadSteps == 1 && refill) issue_advance();
-        } else {
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_step((kKSteps - 1) & 1);
-        }
-        stage = next_stage;
-        if (++kt == k_tiles) {          // a vocabulary tile is complete
-            sm.fold(acc, vt, wv, frag_half, p.V);
-            kt = 0;
-            ++vt;
-        }
-    }
-    __syncthreads();                    // every fragment read is done before the stages are reused
-    sm.merge_store(p, reinterpret_cast<float*>(smem), tok0, m_eff, sp, wv, wt, lane, tid);
-    __syncthreads();                    // merge buffer is read before the next unit's transfers land
-    }
-}
-
-__global__ __launch_bounds__(256) void head_clear_kernel(int32_t* p, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
-}
-
 __global__ __launch_bounds__(256) void head_combine_kernel(
     const float* __restrict__ part, int splits, int64_t M, const int64_t* __restrict__ m_actual,
     const int32_t* __restrict__ sel_rows, const int32_t* __restrict__ sel_targets, int64_t n_rows,
@@ -575,13 +262,9 @@ __global__ __launch_bounds__(256) void head_combine_kernel(
 using Cfg0 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 16>;
 using Cfg1 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 0>;
 
-struct HeadVariant {
-    void (*kernel)(HeadParams);
-    int tile_v, tile_t, threads, lds_bytes, wgs_per_cu;
-};
 template <class C>
 constexpr HeadVariant make_variant() {
-    return {head_mfma_kernel<C>, C::kTileV, C::kTileT, C::kThreads, C::kLdsBytes, C::kWgsPerCu};
+    return {head_mfma_kernel<C, LaneSoftmax>, C::kTileV, C::kTileT, C::kThreads, C::kLdsBytes, C::kWgsPerCu};
 }
 static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>()};
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
@@ -592,38 +275,6 @@ static const HeadVariant& pick_variant() {
     if (id < 0 || id >= kNumVariants) id = 0;
     return kVariants[id];
 }
-
-// Number of vocabulary splits.  A unit is 8 token tiles x min(splits, 4) splits
-// and every XCD works through ceil(units / 8) units of ceil(vocab_tiles /
-// splits) vocabulary tiles each; pick the count (1, 2, 3 or a multiple of 4)
-// that minimises that product, with a small per-unit overhead.
-static int choose_splits(const HeadVariant& hv, int64_t M, int64_t V) {
-    const int64_t row_tiles = (M + hv.tile_t - 1) / hv.tile_t, vocab_tiles = (V + hv.tile_v - 1) / hv.tile_v;
-    const int64_t unit_rows = (row_tiles + 7) / 8;
-    const int max_s = (int)(vocab_tiles < kMaxSplits ? vocab_tiles : kMaxSplits);
-    if (const char* e = getenv("TPPO_HEAD_SPLITS")) {       // tuning override
-        const int forced = atoi(e);
-        if (forced >= 1 && (forced < 4 || forced % 4 == 0)) return forced < max_s ? forced : max_s < 4 ? max_s : max_s / 4 * 4;
-    }
-    int best = 1;
-    double best_cost = 1e300;
-    for (int s = 1; s <= max_s; ++s) {
-        if (s > 4 && s % 4 != 0) continue;
-        const int64_t units = unit_rows * (s <= 4 ? 1 : s / 4);
-        const double rounds = (double)((units + 7) / 8);
-        const double per = (double)((vocab_tiles + s - 1) / s) + 0.25;
-        // fewer than 4 splits leave CUs idle: 8*s of the 32 workgroups of an XCD work
-        const double cost = rounds * per;
-        if (cost < best_cost - 1e-9) {
-            best_cost = cost;
-            best = s;
-        }
-    }
-    return best;
-}
-
-// arrival counters of the persistent schedule: one per unit, at the end of the workspace
-static size_t arrivals_bytes(int64_t M) { return round_up((size_t)((M / 256 / 8 + 2) * (kMaxSplits / 4)) * 4, 256); }
 
 static bool mfma_eligible(const void* hidden, int64_t H, int64_t ld_h, const void* w, int64_t ld_w,
                           tppo_dtype dt) {
@@ -681,36 +332,18 @@ extern "C" int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H
     const size_t workspace_bytes_needed = tppo_token_logprobs_workspace_bytes(M, H, V, dt);
     if (!workspace || !is_aligned(workspace, 256) || workspace_bytes < workspace_bytes_needed)
         return TPPO_ERR_WORKSPACE;
-    HeadParams p;
+    HeadParams p = {};
     p.hidden = static_cast<const uint16_t*>(hidden);
     p.w = static_cast<const uint16_t*>(w_head);
     p.sel_rows = sel_rows;
     p.sel_targets = sel_targets;
     p.m_actual = m_actual;
     p.part = static_cast<float*>(workspace);
-    p.n_rows = n_rows; p.ld_h = ld_hidden; p.ld_w = ld_w; p.M = M;
-    p.H = (int)H; p.V = (int)V;
+    p.n_rows = n_rows; p.ld_h = ld_hidden; p.ld_w = ld_w;
+    p.H = (int)H;
     const HeadVariant& hv = pick_variant();
-    p.row_tiles = (int)((M + hv.tile_t - 1) / hv.tile_t);
-    p.vocab_tiles = (int)((V + hv.tile_v - 1) / hv.tile_v);
-    p.splits = choose_splits(hv, M, V);
-    p.unit_splits = p.splits < 4 ? p.splits : 4;
-    p.unit_cols = p.splits / p.unit_splits;
-    p.unit_rows = (p.row_tiles + 7) / 8;
-    p.n_units = p.unit_rows * p.unit_cols;
-    {
-        const char* e = getenv("TPPO_HEAD_ORDER");
-        p.col_major = e ? atoi(e) : 1;                    // tuning override: 0 = units in row-major order
-    }
-    p.unit_arrivals = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + workspace_bytes_needed - arrivals_bytes(M));
-    hipLaunchKernelGGL(head_clear_kernel, dim3((p.n_units + 255) / 256), dim3(256), 0, s, p.unit_arrivals, p.n_units);
-    if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(hv.kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, hv.lds_bytes) != hipSuccess)
-        return TPPO_ERR_LAUNCH;
-    const int grid = 256;                                   // persistent: one workgroup per CU
-    hipLaunchKernelGGL(hv.kernel, dim3(grid), dim3(hv.threads), hv.lds_bytes, s, p);
-    if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
+    plan_sweep(p, hv, M, V, static_cast<char*>(workspace) + workspace_bytes_needed - arrivals_bytes(M));
+    if (launch_sweep(hv, p, s) != TPPO_OK) return TPPO_ERR_LAUNCH;
     hipLaunchKernelGGL(head_combine_kernel, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, s, p.part,
                        p.splits, M, m_actual, sel_rows, sel_targets, n_rows, (int)V, out_index, logp,
                        lse, status);

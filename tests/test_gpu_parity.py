@@ -254,6 +254,138 @@ def test_logprobs_full_size_sampled(tp, name):
     assert np.abs(got_lse[pick] - ref_lse).max() <= LOGP_ATOL
 
 
+# ------------------------------------------------------------------ log-prob derivatives
+# dz is rounded to bf16 (relative error <= 2^-9 per element) before the two
+# products; an output element is a sum of terms dz * w (or dz * h), so its error
+# is at most 2^-9 times the sum of the terms' magnitudes.  The tests allow twice
+# that, plus 1e-6 of the largest such sum for the fp32 arithmetic in front.
+DZ_RTOL = 2.0 ** -8
+
+
+def assert_within_term_bound(got, ref, abs_bound, what):
+    tol = DZ_RTOL * abs_bound + 1e-6 * abs_bound.max() + 1e-30
+    err = np.abs(got.astype(np.float64) - ref)
+    bad = err > tol
+    assert not bad.any(), (what, int(bad.sum()), float((err / tol).max()))
+
+
+def check_logprob_grads(tp, hidden, w, rows, targets, g, workspace=None, via_index=False):
+    import torch
+    _, lse = ofast.token_logprobs(hidden, w, rows, targets)
+    M = len(rows)
+    lse32, g32 = lse.astype(np.float32), g.astype(np.float32)
+    kw = {}
+    if via_index:                                           # scalars stored in a permuted, larger array
+        perm = np.random.default_rng(1).permutation(M + 9)[:M].astype(np.int32)
+        big_l, big_g = np.full(M + 9, np.nan, np.float32), np.full(M + 9, np.nan, np.float32)
+        big_l[perm], big_g[perm] = lse32, g32
+        lse_d, g_d, kw["in_index"] = dev(big_l), dev(big_g), dev(perm)
+    else:
+        lse_d, g_d = dev(lse32), dev(g32)
+    dh, dw = tp.tppo_token_logprobs_backward(dev(hidden), dev(w), dev(np.asarray(rows, np.int32)),
+                                             dev(np.asarray(targets, np.int32)), lse_d, g_d,
+                                             workspace=workspace, **kw)
+    torch.cuda.synchronize()
+    ref_h, ref_w, abs_h, abs_w = ofast.token_logprob_grads(hidden, w, rows, targets, g32, return_abs_bounds=True)
+    assert_within_term_bound(host(dh), ref_h, abs_h, "grad_hidden")
+    assert_within_term_bound(host(dw), ref_w, abs_w, "grad_w")
+    return host(dh), host(dw)
+
+
+def _bf16_case(M, V, H, seed):
+    rng = np.random.default_rng(seed)
+    N = M + 5
+    hidden = synth.f32_to_bf16_bits(rng.normal(size=(N, H)).astype(np.float32))
+    w = synth.f32_to_bf16_bits((rng.normal(size=(V, H)) / np.sqrt(H)).astype(np.float32))
+    rows = rng.permutation(N)[:M]
+    targets = (np.arange(M) * 7 + 3) % V
+    targets[0], targets[-1] = 0, V - 1
+    return hidden, w, rows, targets, rng.normal(size=M)
+
+
+@pytest.mark.parametrize("M,V,H", [(1, 256, 64), (37, 1000, 128), (300, 1000, 256), (513, 2049, 192),
+                                   (700, 5000, 1024)])
+def test_logprob_grads_ragged_shapes(tp, M, V, H):
+    check_logprob_grads(tp, *_bf16_case(M, V, H, seed=M + V))
+
+
+def test_logprob_grads_index_chunks_halves_accumulate(tp):
+    import torch
+    hidden, w, rows, targets, g = _bf16_case(700, 1000, 128, seed=77)
+    dh, dw = check_logprob_grads(tp, hidden, w, rows, targets, g, via_index=True)
+    # a workspace that only holds 256 tokens at a time: three chunks, same result up to fp32 summation order
+    lib = tp.load()
+    small_ws = tp._workspace(lib.tppo_token_logprobs_backward_workspace_bytes(256, 128, 1000, tp.TPPO_BF16), "cuda")
+    dh_c, dw_c = check_logprob_grads(tp, hidden, w, rows, targets, g, workspace=small_ws)
+    assert np.array_equal(dh_c, dh)                         # rows do not interact
+    assert np.allclose(dw_c, dw, rtol=0, atol=1e-5 * np.abs(dw).max())
+    # one output at a time, and accumulation into grad_w
+    _, lse = ofast.token_logprobs(hidden, w, rows, targets)
+    args = (dev(hidden), dev(w), dev(rows.astype(np.int32)), dev(targets.astype(np.int32)),
+            dev(lse.astype(np.float32)), dev(g.astype(np.float32)))
+    only_h, none_w = tp.tppo_token_logprobs_backward(*args, want_w=False)
+    none_h, only_w = tp.tppo_token_logprobs_backward(*args, want_hidden=False)
+    assert none_w is None and none_h is None
+    assert np.array_equal(host(only_h), dh) and np.array_equal(host(only_w), dw)
+    acc = only_w.clone()
+    tp.tppo_token_logprobs_backward(*args, want_hidden=False, grad_w=acc, accumulate_w=True)
+    torch.cuda.synchronize()
+    assert np.allclose(host(acc), 2 * dw, rtol=1e-6, atol=0)
+    # tokens with a zero upstream derivative contribute exactly nothing
+    g0 = g.copy()
+    g0[100:] = 0.0
+    dh0, _ = check_logprob_grads(tp, hidden, w, rows, targets, g0)
+    assert not dh0[100:].any()
+
+
+def test_logprob_grads_small_config_slice(tp):
+    b = synth.make_batch("small", B=4)
+    sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    g = np.random.default_rng(3).normal(size=sel["M"]) / sel["M"]
+    check_logprob_grads(tp, b["hidden"], b["w_head"], sel["sel_rows"], sel["sel_targets"], g)
+
+
+@pytest.mark.timeout(900)
+def test_logprob_grads_full_vocabulary_few_tokens(tp):
+    """Vocabulary and hidden size of the 32B-shaped workload, 192 kept tokens:
+    every element of both outputs against the oracle."""
+    b = synth.make_batch("head32b")
+    sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    pick = _sampled_rows(sel, 160, seed=4)[:192]
+    g = np.random.default_rng(5).normal(size=len(pick))
+    check_logprob_grads(tp, b["hidden"], b["w_head"], sel["sel_rows"][pick], sel["sel_targets"][pick], g)
+
+
+@pytest.mark.timeout(900)
+def test_logprob_grads_full_size_sampled(tp):
+    """The 32B-shaped workload at full size: grad_hidden on a seeded sample of
+    tokens one by one; for grad_w, which needs every token, the properties that
+    hold at any size (its columns sum to zero; bit-identical reruns)."""
+    import torch
+    b = synth.make_batch("head32b")
+    synth.sample_ids_from_policy(b, device="cuda")
+    sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    M = sel["M"]
+    hidden, w = dev(b["hidden"]), dev(b["w_head"])
+    rows, tg = dev(sel["sel_rows"]), dev(sel["sel_targets"])
+    _, lse = tp.tppo_token_logprobs(hidden, w, rows, tg)      # the backward entry point's own input
+    g = (np.random.default_rng(6).normal(size=M) / M).astype(np.float32)
+    ws = tp._workspace(tp.load().tppo_token_logprobs_backward_workspace_bytes(M, b["H"], b["V"], tp.TPPO_BF16), "cuda")
+    dh, dw = tp.tppo_token_logprobs_backward(hidden, w, rows, tg, lse, dev(g), workspace=ws)
+    dh2, dw2 = tp.tppo_token_logprobs_backward(hidden, w, rows, tg, lse, dev(g), workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dh, dh2) and torch.equal(dw, dw2)
+    assert bool(torch.isfinite(dh).all()) and bool(torch.isfinite(dw).all())
+    col = dw.double().sum(dim=0).abs().cpu().numpy()
+    mass = dw.double().abs().sum(dim=0).cpu().numpy()
+    assert (col <= 1e-2 * mass).all(), float((col / mass).max())
+    pick = _sampled_rows(sel, 40, seed=7)[:64]
+    ref_h, _, abs_h, _ = ofast.token_logprob_grads(b["hidden"], b["w_head"], sel["sel_rows"][pick],
+                                                   sel["sel_targets"][pick], g[pick], want_w=False,
+                                                   return_abs_bounds=True)
+    assert_within_term_bound(dh[torch.from_numpy(pick).cuda()].cpu().numpy(), ref_h, abs_h, "grad_hidden")
+
+
 # ------------------------------------------------------------------ EGAE
 def check_egae(tp, rewards, values, resp_off, done, gamma, lam, bootstrap=None):
     st = tp.new_status("cuda")
