@@ -51,6 +51,8 @@ def parse():
                     choices=["small", "head7b", "head32b", "longcot", "longcot5x"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--metric-only", action="store_true",
+                    help="skip everything outside the metric's four steps (measured ceilings, backward passes)")
     ap.add_argument("--no-reference-rates", action="store_true",
                     help="skip the two measuring sticks printed beside the datasheet peak")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
@@ -184,56 +186,58 @@ def main():
                         traffic=measured_traffic(name, "egae_scan_kernel"),
                         bytes_per_launch=nbytes, avg_ms=stage_ms["egae"])
 
-    if has_head and not args.no_reference_rates:
+    if has_head and not (args.no_reference_rates or args.metric_only):
         roofline["measured_ceilings"] = reference_rates(tp, hidden, w_head, s_rows=sel["sel_rows"][:M])
 
-    # --- beyond the metric's four steps: the loss derivatives (one more streaming pass), timed on their own
-    ws_bwd = tp._workspace(lib.tppo_ppo_losses_backward_workspace_bytes(n_resp, b["B"]), "cuda")
-    grads = (torch.empty(n_resp, device="cuda"), torch.empty(n_resp, device="cuda"))
-    stats_out = torch.empty(32, dtype=torch.uint8, device="cuda")
-    s_last = tp.tppo_select(d["cu_seqlens"], d["ctx_len"], d["done"], ids, b["tail_drop"], n_tok=n_tok)
-    logp_last = logp0
-    adv_last, ret_last = adv_ret
+    extra = None
+    if not args.metric_only:
+        # --- beyond the metric's four steps: the loss derivatives (one more streaming pass), timed on their own
+        ws_bwd = tp._workspace(lib.tppo_ppo_losses_backward_workspace_bytes(n_resp, b["B"]), "cuda")
+        grads = (torch.empty(n_resp, device="cuda"), torch.empty(n_resp, device="cuda"))
+        stats_out = torch.empty(32, dtype=torch.uint8, device="cuda")
+        s_last = tp.tppo_select(d["cu_seqlens"], d["ctx_len"], d["done"], ids, b["tail_drop"], n_tok=n_tok)
+        logp_last = logp0
+        adv_last, ret_last = adv_ret
 
-    def backward_pass():
-        tp.tppo_ppo_losses_backward(logp_last, logp_old, adv_last, d["v_new"], d["values"], ret_last,
-                                    s_last["resp_off"], s_last["keep_len"], d["done"], b["eps_low"],
-                                    b["eps_high"], b["xi_low"], b["xi_high"], status=status,
-                                    workspace=ws_bwd, out=loss_out, stats=stats_out, grads=grads)
+        def backward_pass():
+            tp.tppo_ppo_losses_backward(logp_last, logp_old, adv_last, d["v_new"], d["values"], ret_last,
+                                        s_last["resp_off"], s_last["keep_len"], d["done"], b["eps_low"],
+                                        b["eps_high"], b["xi_low"], b["xi_high"], status=status,
+                                        workspace=ws_bwd, out=loss_out, stats=stats_out, grads=grads)
 
-    backward_pass()
-    torch.cuda.synchronize()
-    e0, e1 = ev(), ev()
-    e0.record()
-    for _ in range(args.steps):
         backward_pass()
-    e1.record()
-    torch.cuda.synchronize()
-    bwd_ms = e0.elapsed_time(e1) / args.steps
-    bwd_bytes = 16.0 * (losses["n_policy"] + losses["n_value"]) + 4.0 * (2 * n_resp - losses["n_policy"] - losses["n_value"])
-    extra = {"ppo_losses_backward": {"ms": bwd_ms, "algorithmic_bytes": bwd_bytes,
-                                     "GB/s": bwd_bytes / (bwd_ms * 1e-3) / 1e9,
-                                     "clip_stats": tp.read_loss_stats(stats_out)}}
-
-    if has_head:
-        # derivatives of the log-probs with respect to hidden rows and head matrix (three sweeps of the same size)
-        _, lse0 = tp.tppo_token_logprobs(hidden, w_head, sel["sel_rows"], sel["sel_targets"], M=M)
-        g_tok = grads[0][sel["sel_resp_idx"][:M].long()].contiguous()
-        ws_hb = tp._workspace(lib.tppo_token_logprobs_backward_workspace_bytes(M, H, V, tp.TPPO_BF16), "cuda")
-        grad_w = torch.empty(V, H, dtype=torch.float32, device="cuda")
-        run_hb = lambda: tp.tppo_token_logprobs_backward(hidden, w_head, sel["sel_rows"], sel["sel_targets"],
-                                                         lse0, g_tok, M=M, grad_w=grad_w, workspace=ws_hb)
-        run_hb()
         torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
         e0.record()
-        for _ in range(2):
-            run_hb()
+        for _ in range(args.steps):
+            backward_pass()
         e1.record()
         torch.cuda.synchronize()
-        hb_ms = e0.elapsed_time(e1) / 2
-        extra["token_logprobs_backward"] = {"ms": hb_ms, "flop": 6.0 * M * V * H,
-                                            "TFLOP/s": 6.0 * M * V * H / (hb_ms * 1e-3) / 1e12}
-        del ws_hb, grad_w
+        bwd_ms = e0.elapsed_time(e1) / args.steps
+        bwd_bytes = 16.0 * (losses["n_policy"] + losses["n_value"]) + 4.0 * (2 * n_resp - losses["n_policy"] - losses["n_value"])
+        extra = {"ppo_losses_backward": {"ms": bwd_ms, "algorithmic_bytes": bwd_bytes,
+                                         "GB/s": bwd_bytes / (bwd_ms * 1e-3) / 1e9,
+                                         "clip_stats": tp.read_loss_stats(stats_out)}}
+
+        if has_head:
+            # derivatives of the log-probs with respect to hidden rows and head matrix (three sweeps of the same size)
+            _, lse0 = tp.tppo_token_logprobs(hidden, w_head, sel["sel_rows"], sel["sel_targets"], M=M)
+            g_tok = grads[0][sel["sel_resp_idx"][:M].long()].contiguous()
+            ws_hb = tp._workspace(lib.tppo_token_logprobs_backward_workspace_bytes(M, H, V, tp.TPPO_BF16), "cuda")
+            grad_w = torch.empty(V, H, dtype=torch.float32, device="cuda")
+            run_hb = lambda: tp.tppo_token_logprobs_backward(hidden, w_head, sel["sel_rows"], sel["sel_targets"],
+                                                             lse0, g_tok, M=M, grad_w=grad_w, workspace=ws_hb)
+            run_hb()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(2):
+                run_hb()
+            e1.record()
+            torch.cuda.synchronize()
+            hb_ms = e0.elapsed_time(e1) / 2
+            extra["token_logprobs_backward"] = {"ms": hb_ms, "flop": 6.0 * M * V * H,
+                                                "TFLOP/s": 6.0 * M * V * H / (hb_ms * 1e-3) / 1e12}
+            del ws_hb, grad_w
 
     cpu = None
     if not args.no_cpu_baseline:
