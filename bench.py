@@ -219,6 +219,20 @@ def main():
                                          "GB/s": bwd_bytes / (bwd_ms * 1e-3) / 1e9,
                                          "clip_stats": tp.read_loss_stats(stats_out)}}
 
+        # Extended GAE from one terminal reward per sequence (12 instead of 16 bytes per token)
+        terminal = torch.ones(b["B"], dtype=torch.float32, device="cuda")
+        run_t = lambda: tp.tppo_egae_terminal(terminal, d["values"], s_last["resp_off"], d["done"], b["gamma"],
+                                              b["lam"], status=status, workspace=ws_egae, out=adv_ret)
+        run_t()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            run_t()
+        e1.record()
+        torch.cuda.synchronize()
+        t_ms = e0.elapsed_time(e1) / args.steps
+        extra["egae_terminal"] = {"ms": t_ms, "algorithmic_bytes": 12.0 * n_resp,
+                                  "GB/s": 12.0 * n_resp / (t_ms * 1e-3) / 1e9}
         if has_head:
             # derivatives of the log-probs with respect to hidden rows and head matrix (three sweeps of the same size)
             _, lse0 = tp.tppo_token_logprobs(hidden, w_head, sel["sel_rows"], sel["sel_targets"], M=M)

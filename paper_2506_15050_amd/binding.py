@@ -31,6 +31,8 @@ _SIGNATURES = {
     "tppo_egae_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
     "tppo_egae": (ctypes.c_int, [_c_ptr] * 5 + [_c_i64, _c_i64, _c_f32, _c_f32, _c_ptr, _c_ptr,
                                                 _c_ptr, _c_size, _c_ptr, _c_ptr]),
+    "tppo_egae_terminal": (ctypes.c_int, [_c_ptr] * 5 + [_c_i64, _c_i64, _c_f32, _c_f32, _c_ptr, _c_ptr,
+                                                         _c_ptr, _c_size, _c_ptr, _c_ptr]),
     "tppo_ppo_losses_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
     "tppo_ppo_losses": (ctypes.c_int, [_c_ptr] * 9 + [_c_i64, _c_i64] + [_c_f32] * 4 +
                         [_c_ptr, _c_ptr, _c_size, _c_ptr, _c_ptr]),
@@ -164,6 +166,23 @@ def tppo_egae(rewards, values, resp_off, done, gamma, lam, bootstrap=None, statu
                        _ptr(_dev_i32(done)), _ptr(bootstrap), B, n_resp, float(gamma), float(lam),
                        _ptr(adv), _ptr(ret), _ptr(ws), ws.numel(), _ptr(status), _stream())
     _check(rc, "tppo_egae")
+    return adv, ret
+
+
+def tppo_egae_terminal(terminal_reward, values, resp_off, done, gamma, lam, bootstrap=None, status=None,
+                       workspace=None, out=None):
+    """Extended GAE with one terminal reward per finished sequence instead of a
+    dense reward array.  Returns (adv, ret)."""
+    lib = load()
+    n_resp, B = values.numel(), done.numel()
+    adv, ret = out if out is not None else (torch.empty_like(values), torch.empty_like(values))
+    ws_bytes = lib.tppo_egae_workspace_bytes(n_resp, B)
+    ws = _workspace(ws_bytes, values.device) if workspace is None else workspace
+    rc = lib.tppo_egae_terminal(_ptr(_dev_f32(terminal_reward)), _ptr(_dev_f32(values)),
+                                _ptr(_dev_i32(resp_off)), _ptr(_dev_i32(done)), _ptr(bootstrap), B, n_resp,
+                                float(gamma), float(lam), _ptr(adv), _ptr(ret), _ptr(ws), ws.numel(),
+                                _ptr(status), _stream())
+    _check(rc, "tppo_egae_terminal")
     return adv, ret
 
 

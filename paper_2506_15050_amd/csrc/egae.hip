@@ -135,21 +135,36 @@ __device__ __forceinline__ int lds_slot(int token) { return (token / kTpt) * kLd
 
 struct Raw { float4u r[kGroups], v[kGroups]; float v_after; };
 
-// issue the global loads of a chunk: group g of thread tid = tokens g*512 + tid*4 .. +3
+// issue the global loads of a chunk: group g of thread tid = tokens g*512 + tid*4 .. +3.
+// kTerminal: there is no reward array; the only reward is terminal[seq] on the last token
+// of a finished sequence (Sec. 2.1: the rule-based reward arrives with the end of the response).
+template <bool kTerminal>
 __device__ __forceinline__ void load_raw(Raw& x, const float* __restrict__ rewards,
-                                         const float* __restrict__ values, int start, int len, int tid) {
+                                         const float* __restrict__ values, const Chunk& ch,
+                                         const int32_t* __restrict__ done, int tid) {
+    const int start = ch.start, len = ch.len();
 #pragma unroll
     for (int g = 0; g < kGroups; ++g) {
         const int k0 = g * 4 * kEgaeThreads + tid * 4;
         if (k0 + 4 <= len) {
-            x.r[g] = *reinterpret_cast<const float4u*>(rewards + start + k0);
+            if (!kTerminal) x.r[g] = *reinterpret_cast<const float4u*>(rewards + start + k0);
             x.v[g] = *reinterpret_cast<const float4u*>(values + start + k0);
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const bool ok = k0 + e < len;
-                x.r[g][e] = ok ? rewards[start + k0 + e] : 0.f;
+                if (!kTerminal) x.r[g][e] = ok ? rewards[start + k0 + e] : 0.f;
                 x.v[g][e] = ok ? values[start + k0 + e] : 0.f;
+            }
+        }
+        if (kTerminal) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x.r[g][e] = 0.f;
+            const int last = len - 1 - k0;                          // the chunk's last token, if it is in this group
+            if (ch.after == 0 && last >= 0 && last < 4 && done[ch.seg] != 0) {
+                const float t = rewards[ch.seg];                    // `rewards` is terminal[B] in this mode
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x.r[g][e] = e == last ? t : 0.f;
             }
         }
     }
@@ -230,6 +245,7 @@ __device__ __forceinline__ void walk_tokens(const TokenRegs& tk, int n_mine, flo
     }
 }
 
+template <bool kTerminal>
 __global__ __launch_bounds__(kEgaeThreads, 3) void egae_scan_kernel(
     const float* __restrict__ rewards, const float* __restrict__ values,
     const int32_t* __restrict__ done, const float* __restrict__ bootstrap, int n_resp, int cap,
@@ -249,7 +265,7 @@ __global__ __launch_bounds__(kEgaeThreads, 3) void egae_scan_kernel(
 
     Chunk cur = ws.chunks[w];
     Raw raw;
-    load_raw(raw, rewards, values, cur.start, cur.len(), tid);
+    load_raw<kTerminal>(raw, rewards, values, cur, done, tid);
     raw.v_after = load_v_after(cur, values, done, bootstrap, tid);
 
     for (; w < count; w += gridDim.x) {
@@ -266,7 +282,7 @@ __global__ __launch_bounds__(kEgaeThreads, 3) void egae_scan_kernel(
         Chunk nxt = cur;
         if (w_next < count) {
             nxt = ws.chunks[w_next];
-            load_raw(raw, rewards, values, nxt.start, nxt.len(), tid);
+            load_raw<kTerminal>(raw, rewards, values, nxt, done, tid);
             raw.v_after = load_v_after(nxt, values, done, bootstrap, tid);
         }
 
@@ -393,11 +409,31 @@ extern "C" size_t tppo_egae_workspace_bytes(int64_t n_resp, int64_t B) {
     return tppo::egae_ws_bytes(tppo::max_chunks(n_resp, B));
 }
 
-extern "C" int tppo_egae(const float* rewards, const float* values, const int32_t* resp_off,
-                         const int32_t* done, const float* bootstrap, int64_t B, int64_t n_resp,
-                         float gamma, float lambda, float* adv, float* ret, void* workspace,
-                         size_t workspace_bytes, int32_t* status, void* stream) {
-    using namespace tppo;
+namespace tppo {
+// Workgroups of the scan that the current device keeps resident at the same time.  The look-back waits on
+// chunks held by other workgroups, so the grid must never exceed this (else a waiting workgroup could keep
+// the one it waits for from starting); asked of the runtime once per device.
+static int egae_resident_groups() {
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] > 0) return cached[dev];
+    int per_cu = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, egae_scan_kernel<false>, kEgaeThreads, 0) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return 0;
+    const int n = per_cu * cus;
+    cached[dev] = n < kEgaeMaxGroups ? n : kEgaeMaxGroups;
+    return cached[dev];
+}
+}  // namespace tppo
+
+namespace tppo {
+// `rewards` is the dense [n_resp] array, or with terminal_mode the per-sequence terminal[B] array
+static int egae_launch(const float* rewards, bool terminal_mode, const float* values, const int32_t* resp_off,
+                       const int32_t* done, const float* bootstrap, int64_t B, int64_t n_resp,
+                       float gamma, float lambda, float* adv, float* ret, void* workspace,
+                       size_t workspace_bytes, int32_t* status, void* stream) {
     if (B < 0 || n_resp < 0 || n_resp > INT32_MAX - kChunkTokens || B > INT32_MAX / 4) return TPPO_ERR_SIZE;
     if (!(gamma >= 0.f && gamma <= 1.f) || !(lambda >= 0.f && lambda <= 1.f)) return TPPO_ERR_PARAM;
     if (n_resp == 0) return TPPO_OK;
@@ -417,8 +453,31 @@ extern "C" int tppo_egae(const float* rewards, const float* values, const int32_
     const double g = (double)gamma, c = (double)gamma * (double)lambda;
     // weight of a whole chunk in the carry: (gamma*lambda)^2048 resp. gamma^2048
     const double gamma_pow_chunk = pow(g, (double)kChunkTokens), c_pow_chunk = pow(c, (double)kChunkTokens);
-    const int groups = cap < kEgaeMaxGroups ? cap : kEgaeMaxGroups;
-    hipLaunchKernelGGL(egae_scan_kernel, dim3(groups), dim3(kEgaeThreads), 0, s, rewards, values, done,
-                       bootstrap, (int)n_resp, cap, g, c, gamma_pow_chunk, c_pow_chunk, adv, ret, workspace, status);
+    const int resident = egae_resident_groups();
+    if (resident < 1) return TPPO_ERR_LAUNCH;
+    const int groups = cap < resident ? cap : resident;
+    if (terminal_mode)
+        hipLaunchKernelGGL(egae_scan_kernel<true>, dim3(groups), dim3(kEgaeThreads), 0, s, rewards, values, done,
+                           bootstrap, (int)n_resp, cap, g, c, gamma_pow_chunk, c_pow_chunk, adv, ret, workspace, status);
+    else
+        hipLaunchKernelGGL(egae_scan_kernel<false>, dim3(groups), dim3(kEgaeThreads), 0, s, rewards, values, done,
+                           bootstrap, (int)n_resp, cap, g, c, gamma_pow_chunk, c_pow_chunk, adv, ret, workspace, status);
     return launch_result();
+}
+}  // namespace tppo
+
+extern "C" int tppo_egae(const float* rewards, const float* values, const int32_t* resp_off,
+                         const int32_t* done, const float* bootstrap, int64_t B, int64_t n_resp,
+                         float gamma, float lambda, float* adv, float* ret, void* workspace,
+                         size_t workspace_bytes, int32_t* status, void* stream) {
+    return tppo::egae_launch(rewards, false, values, resp_off, done, bootstrap, B, n_resp, gamma, lambda, adv,
+                             ret, workspace, workspace_bytes, status, stream);
+}
+
+extern "C" int tppo_egae_terminal(const float* terminal_reward, const float* values, const int32_t* resp_off,
+                                  const int32_t* done, const float* bootstrap, int64_t B, int64_t n_resp,
+                                  float gamma, float lambda, float* adv, float* ret, void* workspace,
+                                  size_t workspace_bytes, int32_t* status, void* stream) {
+    return tppo::egae_launch(terminal_reward, true, values, resp_off, done, bootstrap, B, n_resp, gamma, lambda,
+                             adv, ret, workspace, workspace_bytes, status, stream);
 }

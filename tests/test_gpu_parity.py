@@ -468,6 +468,30 @@ def test_egae_empty(tp):
     assert adv.numel() == 0 and ret.numel() == 0
 
 
+@pytest.mark.parametrize("name,lam,gamma", [("tiny", 0.95, 1.0), ("small", 1.0, 1.0), ("longcot", 0.95, 0.999)])
+def test_egae_terminal_reward_equals_dense(tp, name, lam, gamma):
+    """One reward per finished sequence (Sec. 2.1) instead of a dense array: the
+    oracle evaluates the dense array built from it; the two entry points agree bit for bit."""
+    b = synth.make_batch(name, with_head=False)
+    off, done = b["resp_off"], b["done"]
+    rng = np.random.default_rng(11)
+    terminal = rng.choice([-1.0, 1.0], size=len(done)).astype(np.float32)   # also set for unfinished ones: ignored
+    dense = np.zeros(b["n_resp"], np.float32)
+    for i in range(len(done)):
+        if done[i] != 0 and off[i + 1] > off[i]:
+            dense[off[i + 1] - 1] = terminal[i]
+    st = tp.new_status("cuda")
+    adv, ret = tp.tppo_egae_terminal(dev(terminal), dev(b["values"]), dev(off.astype(np.int32)),
+                                     dev(done.astype(np.int32)), gamma, lam, status=st)
+    ref_a, ref_r = ofast.egae(dense, b["values"], off, done, float(np.float32(gamma)), float(np.float32(lam)))
+    assert int(host(st)[0]) == 0
+    assert_egae_close(host(adv), ref_a, "adv")
+    assert_egae_close(host(ret), ref_r, "ret")
+    adv2, ret2 = tp.tppo_egae(dev(dense), dev(b["values"]), dev(off.astype(np.int32)),
+                              dev(done.astype(np.int32)), gamma, lam)
+    assert np.array_equal(host(adv), host(adv2)) and np.array_equal(host(ret), host(ret2))
+
+
 # ------------------------------------------------------------------ losses
 def loss_inputs(b, rng=None):
     adv, ret = ofast.egae(b["rewards"], b["values"], b["resp_off"], b["done"], b["gamma"], b["lam"])
