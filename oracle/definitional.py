@@ -257,3 +257,11 @@ def token_logprob_grads(hidden, w_head, sel_rows, sel_targets, grad_logp):
             for k in range(H):
                 grad_w[v][k] += dz[v] * h[k]
     return grad_hidden, grad_w
+
+
+# --------------------------------------------------------------------------
+# Value head (Sec. 2.2: the value model maps a state to one scalar)
+# --------------------------------------------------------------------------
+def value_head(hidden, w_value, bias, rows):
+    """V(s_t) = w_value . hidden[rows[t]] + bias, one dot product per row."""
+    return [math.fsum(hk * wk for hk, wk in zip(hidden[r], w_value)) + bias for r in rows]

@@ -259,3 +259,18 @@ def token_logprob_grads(hidden, w_head, sel_rows, sel_targets, grad_logp, row_bl
     if return_abs_bounds:
         return grad_hidden, grad_w, abs_h, abs_w
     return grad_hidden, grad_w
+
+
+def value_head(hidden, w_value, bias, rows, return_abs_bound=False):
+    """V(s_t) = w_value . hidden[rows[t]] + bias in fp64 on the exact bf16 / fp32
+    inputs (Sec. 2.2).  ``return_abs_bound`` adds sum_k |w_k h_k| per row."""
+    rows = np.asarray(rows, dtype=np.int64)
+    w = decode(w_value)
+    v = np.empty(rows.shape[0])
+    bound = np.empty(rows.shape[0])
+    for r0 in range(0, rows.shape[0], 4096):
+        h = decode(hidden[rows[r0:r0 + 4096]])
+        v[r0:r0 + 4096] = h @ w + bias
+        if return_abs_bound:
+            bound[r0:r0 + 4096] = np.abs(h) @ np.abs(w)
+    return (v, bound) if return_abs_bound else v

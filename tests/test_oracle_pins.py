@@ -596,3 +596,30 @@ def test_logprob_grads_closed_forms_and_invariants():
     dh5, dw5 = ofast.token_logprob_grads(hb, wb, rows, tg, g)
     dh6, dw6 = ofast.token_logprob_grads(ofast.decode(hb), ofast.decode(wb), rows, tg, g)
     assert np.array_equal(dh5, dh6) and np.array_equal(dw5, dw6)
+
+
+# ------------------------------------------------------------------ value head
+def test_value_head_definition_and_closed_forms():
+    rng = np.random.default_rng(41)
+    hidden = rng.normal(size=(9, 16))
+    w = rng.normal(size=16)
+    rows = rng.integers(0, 9, size=13)
+    d = odef.value_head(hidden.tolist(), w.tolist(), 0.25, rows.tolist())
+    f, bound = ofast.value_head(hidden, w, 0.25, rows, return_abs_bound=True)
+    assert np.allclose(f, d, rtol=1e-14, atol=1e-15)
+    assert np.all(np.abs(f - 0.25) <= bound + 1e-15)
+    # a unit weight vector picks one column; all-ones sums the row; the bias is added once
+    e3 = np.zeros(16)
+    e3[3] = 1.0
+    assert np.array_equal(ofast.value_head(hidden, e3, 0.0, rows), hidden[rows, 3])
+    ones = ofast.value_head(hidden, np.ones(16), 1.5, rows)
+    assert np.allclose(ones, [math.fsum(hidden[r]) + 1.5 for r in rows], rtol=1e-14)
+    # linear in the weights
+    w2 = rng.normal(size=16)
+    assert np.allclose(ofast.value_head(hidden, w + 2 * w2, 0.0, rows),
+                       ofast.value_head(hidden, w, 0.0, rows) + 2 * ofast.value_head(hidden, w2, 0.0, rows))
+    # bf16 bit patterns are decoded
+    from paper_2506_15050_amd.synth import f32_to_bf16_bits
+    hb, wb = f32_to_bf16_bits(hidden.astype(np.float32)), f32_to_bf16_bits(w.astype(np.float32))
+    assert np.array_equal(ofast.value_head(hb, wb, 0.0, rows),
+                          ofast.value_head(ofast.decode(hb), ofast.decode(wb), 0.0, rows))
