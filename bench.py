@@ -234,6 +234,23 @@ def main():
         extra["egae_terminal"] = {"ms": t_ms, "algorithmic_bytes": 12.0 * n_resp,
                                   "GB/s": 12.0 * n_resp / (t_ms * 1e-3) / 1e9}
         if has_head:
+            # value-head projection on the value tokens' rows (window tokens of finished sequences)
+            fin = torch.repeat_interleave(d["done"] != 0, (sel["sel_off"][1:] - sel["sel_off"][:-1]).long())
+            v_rows = sel["sel_rows"][:M][fin].contiguous()
+            w_value = (torch.randn(H, device="cuda") / H ** 0.5).to(torch.bfloat16)
+            v_out = torch.empty(v_rows.numel(), dtype=torch.float32, device="cuda")
+            run_v = lambda: tp.tppo_value_head(hidden, w_value, 0.0, v_rows, out=v_out, status=status)
+            run_v()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(args.steps):
+                run_v()
+            e1.record()
+            torch.cuda.synchronize()
+            v_ms = e0.elapsed_time(e1) / args.steps
+            v_bytes = 2.0 * H * v_rows.numel()
+            extra["value_head"] = {"ms": v_ms, "rows": int(v_rows.numel()), "algorithmic_bytes": v_bytes,
+                                   "GB/s": v_bytes / (v_ms * 1e-3) / 1e9}
             # derivatives of the log-probs with respect to hidden rows and head matrix (three sweeps of the same size)
             _, lse0 = tp.tppo_token_logprobs(hidden, w_head, sel["sel_rows"], sel["sel_targets"], M=M)
             g_tok = grads[0][sel["sel_resp_idx"][:M].long()].contiguous()

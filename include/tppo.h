@@ -301,6 +301,24 @@ int tppo_token_logprobs_backward(const void* hidden, int64_t n_rows, int64_t H, 
                                  int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * tppo_value_head -- V(s_t) = w_value . h_t + bias for a list of hidden rows of
+ * the value model (Sec. 2.2): the projection that yields the v_new consumed by
+ * Eq. (valueloss).  bf16 rows and weights, fp32 accumulation and output.
+ *
+ * in : hidden [n_rows, H] device bf16, row stride ld_hidden (H % 8 == 0,
+ *      ld_hidden % 8 == 0, 16-byte aligned base, else TPPO_ERR_PARAM;
+ *      H <= 16384); w_value [H] device bf16; bias host scalar;
+ *      rows[M] device int32 (NULL: rows 0 .. M-1); m_actual as in
+ *      tppo_token_logprobs.
+ * out: v_out[out_index[t]] (out_index NULL: v_out[t]) device fp32.
+ * A row index outside [0, n_rows) gives NaN and sets TPPO_STATUS_BAD_ROW.
+ */
+int tppo_value_head(const void* hidden, int64_t n_rows, int64_t H, int64_t ld_hidden,
+                    const void* w_value, float bias, tppo_dtype dt,
+                    const int32_t* rows, const int32_t* out_index, int64_t M, const int64_t* m_actual,
+                    float* v_out, int32_t* status, void* stream);
+
+/* ---------------------------------------------------------------------------
  * tppo_diag_mfma_rate -- a measuring stick, not a step of the method: runs the
  * inner loop of the LM-head kernel (v_mfma_f32_32x32x16_bf16, 8 wavefronts per
  * workgroup, one workgroup per CU, 16 MFMAs per wavefront and iteration) on

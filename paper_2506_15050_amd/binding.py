@@ -44,6 +44,8 @@ _SIGNATURES = {
                                                     ctypes.c_int, _c_ptr, _c_ptr, _c_i64, _c_ptr, _c_ptr,
                                                     _c_ptr, _c_ptr, _c_ptr, _c_i32, _c_ptr, _c_size, _c_ptr,
                                                     _c_ptr]),
+    "tppo_value_head": (ctypes.c_int, [_c_ptr, _c_i64, _c_i64, _c_i64, _c_ptr, _c_f32, ctypes.c_int, _c_ptr,
+                                       _c_ptr, _c_i64, _c_ptr, _c_ptr, _c_ptr, _c_ptr]),
     "tppo_diag_mfma_rate": (ctypes.c_int, [_c_ptr, _c_ptr, _c_i64, ctypes.POINTER(ctypes.c_double), _c_ptr]),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -247,6 +249,23 @@ def tppo_token_logprobs_backward(hidden, w_head, sel_rows, sel_targets, lse, gra
                                           _stream())
     _check(rc, "tppo_token_logprobs_backward")
     return g_h, grad_w
+
+
+def tppo_value_head(hidden, w_value, bias=0.0, rows=None, M=None, m_actual=None, out_index=None,
+                    out_size=None, status=None, out=None):
+    """V(s_t) = w_value . hidden[rows[t]] + bias.  Returns the fp32 values."""
+    lib = load()
+    assert hidden.is_cuda and hidden.dtype == w_value.dtype == torch.bfloat16 and hidden.stride(1) == 1
+    n_rows, H = hidden.shape
+    if M is None:
+        M = n_rows if rows is None else rows.numel()
+    n_out = int(M) if out_size is None else int(out_size)
+    v = torch.empty(n_out, dtype=torch.float32, device=hidden.device) if out is None else out
+    rc = lib.tppo_value_head(_ptr(hidden), n_rows, H, hidden.stride(0), _ptr(w_value), float(bias), TPPO_BF16,
+                             _ptr(rows), _ptr(out_index), int(M), _ptr(m_actual), _ptr(v), _ptr(status),
+                             _stream())
+    _check(rc, "tppo_value_head")
+    return v
 
 
 class LossStats(ctypes.Structure):

@@ -77,6 +77,13 @@ def test_host_side_argument_errors(lib):
     assert bw(256, 256, 256, None, None, None, 256, 256, 256, 1, 4, 0.2, 0.2, 0.5, 0.6, 1.0, 1.0, 0, 0, 256, None, None, None, None, 0, None, None) == W
     assert bw(256, 256, 256, None, None, None, 256, 256, 256, 1, -4, 0.2, 0.2, 0.5, 0.6, 1.0, 1.0, 0, 0, 256, None, None, None, 256, 1 << 20, None, None) == S
     assert lib.tppo_ppo_losses_backward_workspace_bytes(10, 1) >= 5 * 8
+    # value head
+    vh = lib.tppo_value_head
+    assert vh(256, 4, 64, 64, 256, 0.0, 0, None, None, 4, None, 256, None, None) == D          # fp32 not offered
+    assert vh(256, 4, 60, 64, 256, 0.0, 1, None, None, 4, None, 256, None, None) == P          # H % 8
+    assert vh(256, 4, 64, 32, 256, 0.0, 1, None, None, 4, None, 256, None, None) == S          # ld < H
+    assert vh(256, 4, 64, 64, None, 0.0, 1, None, None, 4, None, 256, None, None) == N
+    assert vh(256, 4, 64, 64, 256, 0.0, 1, None, None, 0, None, 256, None, None) == 0          # M = 0
     # diagnostic loop
     assert lib.tppo_diag_mfma_rate(None, None, 10, None, None) == N
     assert lib.tppo_diag_mfma_rate(256, 256, -1, None, None) == S

@@ -386,6 +386,65 @@ def test_logprob_grads_full_size_sampled(tp):
     assert_within_term_bound(dh[torch.from_numpy(pick).cuda()].cpu().numpy(), ref_h, abs_h, "grad_hidden")
 
 
+# ------------------------------------------------------------------ value head
+def check_value_head(tp, hidden, w, bias, rows, **kw):
+    got = host(tp.tppo_value_head(dev(hidden), dev(w), bias, None if rows is None else dev(np.asarray(rows, np.int32)), **kw))
+    idx = np.arange(hidden.shape[0]) if rows is None else rows
+    ref, bound = ofast.value_head(hidden, w, float(np.float32(bias)), idx, return_abs_bound=True)
+    # fp32 accumulation of H products: error <= a few sqrt(H) 2^-24 of the sum of the terms' magnitudes
+    tol = 1e-5 * (bound + abs(bias)) + 1e-30
+    assert np.all(np.abs(got - ref) <= tol), float((np.abs(got - ref) / tol).max())
+    return got
+
+
+@pytest.mark.parametrize("M,N,H", [(1, 3, 8), (57, 60, 64), (300, 305, 200), (1000, 1500, 1024), (777, 800, 5120)])
+def test_value_head_shapes(tp, M, N, H):
+    rng = np.random.default_rng(M + H)
+    hidden = synth.f32_to_bf16_bits(rng.normal(size=(N, H)).astype(np.float32))
+    w = synth.f32_to_bf16_bits((rng.normal(size=H) / np.sqrt(H)).astype(np.float32))
+    check_value_head(tp, hidden, w, 0.125, rng.integers(0, N, size=M))
+    check_value_head(tp, hidden, w, -2.0, None)             # no list: every row in order
+
+
+def test_value_head_scatter_count_status(tp):
+    import torch
+    rng = np.random.default_rng(9)
+    N, H, M = 400, 256, 333
+    hidden = synth.f32_to_bf16_bits(rng.normal(size=(N, H)).astype(np.float32))
+    w = synth.f32_to_bf16_bits((rng.normal(size=H) / 16).astype(np.float32))
+    rows = rng.integers(0, N, size=M)
+    ref = ofast.value_head(hidden, w, 0.0, rows)
+    # scatter through an index, count read from device memory, capacity larger than the count
+    cap = 500
+    rows_c = np.zeros(cap, np.int32); rows_c[:M] = rows
+    oi = np.zeros(cap, np.int32); oi[:M] = rng.permutation(600)[:M]
+    out = torch.full((600,), 7.0, device="cuda")
+    tp.tppo_value_head(dev(hidden), dev(w), 0.0, dev(rows_c), M=cap,
+                       m_actual=torch.tensor([M], dtype=torch.int64, device="cuda"), out_index=dev(oi), out=out)
+    got = host(out)
+    assert np.abs(got[oi[:M]] - ref).max() < 1e-4
+    untouched = np.ones(600, bool); untouched[oi[:M]] = False
+    assert (got[untouched] == 7.0).all()
+    # a bad row index: NaN for that token only, status bit set
+    bad = rows.copy(); bad[10] = N
+    st = tp.new_status("cuda")
+    got = host(tp.tppo_value_head(dev(hidden), dev(w), 0.0, dev(bad.astype(np.int32)), status=st))
+    assert np.isnan(got[10]) and int(host(st)[0]) == tp.STATUS_BAD_ROW
+    keep = np.arange(M) != 10
+    assert np.abs(got[keep] - ref[keep]).max() < 1e-4
+
+
+def test_value_head_32b_shape_value_tokens(tp):
+    """Hidden size and value-token rows of the 32B-shaped workload (window tokens of finished sequences)."""
+    b = synth.make_batch("head32b")
+    sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    fin = np.repeat(b["done"] != 0, np.diff(sel["sel_off"]))
+    rows = sel["sel_rows"][fin]
+    assert len(rows) == sel["N_val"]
+    w = synth.f32_to_bf16_bits((np.random.default_rng(2).normal(size=b["H"]) / np.sqrt(b["H"])).astype(np.float32))
+    check_value_head(tp, b["hidden"], w, 0.0, rows)
+
+
 # ------------------------------------------------------------------ EGAE
 def check_egae(tp, rewards, values, resp_off, done, gamma, lam, bootstrap=None):
     st = tp.new_status("cuda")
