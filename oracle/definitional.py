@@ -265,3 +265,60 @@ def token_logprob_grads(hidden, w_head, sel_rows, sel_targets, grad_logp):
 def value_head(hidden, w_value, bias, rows):
     """V(s_t) = w_value . hidden[rows[t]] + bias, one dot product per row."""
     return [math.fsum(hk * wk for hk, wk in zip(hidden[r], w_value)) + bias for r in rows]
+
+
+# --------------------------------------------------------------------------
+# Successive batching (Sec. 3.2 first paragraph, Alg. 1 line 2): a constant
+# number K of slots; a sequence that reached an ending condition is removed
+# before the next step and a new prompt takes its place, unfinished ones stay.
+# --------------------------------------------------------------------------
+class SuccessiveBatch:
+    """Book-keeping of the slots across steps.  A sequence ends when it emits
+    the end-of-sequence token or when its response reaches ``max_response``
+    tokens (the actual maximum response length L; the window length l bounds
+    what one step may add)."""
+
+    def __init__(self, slots, window, max_response):
+        self.window, self.max_response = window, max_response
+        self.seq = [None] * slots          # per slot: dict(id, prompt, ctx, win, done) or None
+        self.next_id = 0
+
+    def refill(self, prompt_lens):
+        """Put new prompts into empty slots (and slots whose sequence is finished),
+        in slot order; returns how many prompts were taken."""
+        taken = 0
+        for k in range(len(self.seq)):
+            s = self.seq[k]
+            if (s is None or s["done"]) and taken < len(prompt_lens):
+                self.seq[k] = dict(id=self.next_id, prompt=int(prompt_lens[taken]), ctx=int(prompt_lens[taken]),
+                                   win=0, done=False)
+                self.next_id += 1
+                taken += 1
+        return taken
+
+    def advance(self, gen_len, eos):
+        """One rollout window: slot k generated gen_len[k] tokens and (eos[k]) ended
+        with the end-of-sequence token.  Tokens of the previous window become context."""
+        for k, s in enumerate(self.seq):
+            if s is None or s["done"]:
+                raise ValueError("advance() on an empty or finished slot: refill first")
+            g = int(gen_len[k])
+            so_far = s["ctx"] + s["win"] - s["prompt"]
+            if g < 0 or g > self.window or so_far + g > self.max_response:
+                raise ValueError("window or maximum response length exceeded")
+            if not eos[k] and g < self.window and so_far + g < self.max_response:
+                raise ValueError("a sequence stops short of the window only by ending")
+            s["ctx"] += s["win"]
+            s["win"] = g
+            s["done"] = bool(eos[k]) or so_far + g == self.max_response
+
+    def layout(self):
+        """(cu_seqlens, ctx_len, prompt_len, done, seq_id) of the current training batch."""
+        cu, ctx, prompt, done, ids = [0], [], [], [], []
+        for s in self.seq:
+            cu.append(cu[-1] + s["ctx"] + s["win"])
+            ctx.append(s["ctx"])
+            prompt.append(s["prompt"])
+            done.append(1 if s["done"] else 0)
+            ids.append(s["id"])
+        return cu, ctx, prompt, done, ids

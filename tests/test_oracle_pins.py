@@ -623,3 +623,58 @@ def test_value_head_definition_and_closed_forms():
     hb, wb = f32_to_bf16_bits(hidden.astype(np.float32)), f32_to_bf16_bits(w.astype(np.float32))
     assert np.array_equal(ofast.value_head(hb, wb, 0.0, rows),
                           ofast.value_head(ofast.decode(hb), ofast.decode(wb), 0.0, rows))
+
+
+# ------------------------------------------------------------------ successive batching
+def test_successive_batching_paper_example():
+    rows = {}
+    for line in open(os.path.join(GOLDEN, "successive_batching_example.txt")):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            k, v = line.split(":")
+            rows[k] = [int(x) for x in v.split()]
+    sb = odef.SuccessiveBatch(slots=5, window=8, max_response=24)
+    assert sb.refill([3, 4, 5, 6, 7, 8, 9]) == 5                      # only five slots: two prompts wait
+    assert sb.layout()[4] == rows["step0"]
+    eos = [1 if k in rows["finished0"] else 0 for k in range(5)]
+    sb.advance([8, 8, 5, 2, 8], eos)
+    assert [k for k, d in enumerate(sb.layout()[3]) if d] == rows["finished0"]
+    assert sb.refill([8, 9]) == 2
+    assert sb.layout()[4] == rows["step1"]
+
+
+def test_successive_batching_invariants():
+    rng = np.random.default_rng(51)
+    K, l, L = 6, 8, 24
+    sb = odef.SuccessiveBatch(K, l, L)
+    sb.refill(rng.integers(1, 9, size=K))
+    trained_policy = {}                                              # seq id -> response tokens seen by the policy
+    finished = {}
+    for step in range(12):
+        cu, ctx, prompt, done, ids = sb.layout()
+        gen, eos = [], []
+        for k in range(K):
+            so_far = ctx[k] - prompt[k] + (cu[k + 1] - cu[k] - ctx[k])
+            room = min(l, L - so_far)
+            stop = rng.random() < 0.3
+            g = int(rng.integers(1, room + 1)) if stop else room
+            gen.append(g)
+            eos.append(1 if stop else 0)
+        sb.advance(gen, eos)
+        cu, ctx, prompt, done, ids = sb.layout()
+        assert len(ids) == K and len(set(ids)) == K                 # constant batch, no duplicates
+        for k in range(K):
+            win = cu[k + 1] - cu[k] - ctx[k]
+            assert win == gen[k] and 0 < win <= l
+            trained_policy[ids[k]] = trained_policy.get(ids[k], 0) + win
+            resp = ctx[k] + win - prompt[k]
+            assert resp <= L and trained_policy[ids[k]] == resp      # every response token is in exactly one window
+            if done[k]:
+                assert eos[k] or resp == L
+                finished[ids[k]] = resp                              # value tokens: the whole response
+            else:
+                assert win == l                                      # unfinished sequences fill the window
+        sb.refill(rng.integers(1, 9, size=sum(done)))
+    assert len(finished) > K                                         # slots were reused
+    with pytest.raises(ValueError):
+        sb.advance([l + 1] * K, [0] * K)
