@@ -301,6 +301,42 @@ int tppo_token_logprobs_backward(const void* hidden, int64_t n_rows, int64_t H, 
                                  int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * tppo_batcher_* -- slot bookkeeping of successive batching (Sec. 3.2 first
+ * paragraph, Alg. 1 line 2).  HOST code and HOST pointers only, integers only.
+ * A constant number of slots; a sequence ends when it emits the
+ * end-of-sequence token or when its response reaches max_response tokens (the
+ * actual maximum length L); one step adds at most `window` (l) tokens.  Ended
+ * sequences are replaced by new prompts at the next refill, the others stay and
+ * their previous window becomes context.
+ *
+ *   create(slots, window, max_response)   NULL on bad sizes or no memory; the
+ *                                         caller owns the object until destroy.
+ *   refill(b, prompt_len, n_available, n_taken)
+ *        new prompts (>= 1 token each) go into empty or finished slots in slot
+ *        order, ids count up from 0; *n_taken (may be NULL) says how many.
+ *        An empty prompt among those that would be taken -> TPPO_ERR_PARAM,
+ *        nothing changed.
+ *   advance(b, gen_len[slots], eos[slots])
+ *        one rollout window.  Every slot must hold an unfinished sequence
+ *        (else TPPO_ERR_PARAM); 0 <= gen_len <= window and the response may not
+ *        pass max_response (TPPO_ERR_SIZE); a sequence that stops short of both
+ *        limits must have eos set (TPPO_ERR_PARAM).  A rejected call changes nothing.
+ *   layout(b, cu_seqlens[slots+1], ctx_len, prompt_len, done, seq_id)
+ *        the packed layout of the current training batch (seq_id may be NULL).
+ *        For the policy tokens call tppo_select with ctx_len; for the value
+ *        tokens (every response token of finished sequences, whichever window
+ *        produced it) call it with prompt_len in place of ctx_len and
+ *        tail_drop = INT32_MAX.
+ */
+typedef struct tppo_batcher tppo_batcher;
+tppo_batcher* tppo_batcher_create(int64_t slots, int32_t window, int32_t max_response);
+void tppo_batcher_destroy(tppo_batcher* b);
+int tppo_batcher_refill(tppo_batcher* b, const int32_t* prompt_len, int64_t n_available, int64_t* n_taken);
+int tppo_batcher_advance(tppo_batcher* b, const int32_t* gen_len, const int32_t* eos);
+int tppo_batcher_layout(const tppo_batcher* b, int32_t* cu_seqlens, int32_t* ctx_len, int32_t* prompt_len,
+                        int32_t* done, int64_t* seq_id);
+
+/* ---------------------------------------------------------------------------
  * tppo_value_head -- V(s_t) = w_value . h_t + bias for a list of hidden rows of
  * the value model (Sec. 2.2): the projection that yields the v_new consumed by
  * Eq. (valueloss).  bf16 rows and weights, fp32 accumulation and output.

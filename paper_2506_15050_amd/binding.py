@@ -44,6 +44,11 @@ _SIGNATURES = {
                                                     ctypes.c_int, _c_ptr, _c_ptr, _c_i64, _c_ptr, _c_ptr,
                                                     _c_ptr, _c_ptr, _c_ptr, _c_i32, _c_ptr, _c_size, _c_ptr,
                                                     _c_ptr]),
+    "tppo_batcher_create": (_c_ptr, [_c_i64, _c_i32, _c_i32]),
+    "tppo_batcher_destroy": (None, [_c_ptr]),
+    "tppo_batcher_refill": (ctypes.c_int, [_c_ptr, _c_ptr, _c_i64, ctypes.POINTER(ctypes.c_int64)]),
+    "tppo_batcher_advance": (ctypes.c_int, [_c_ptr, _c_ptr, _c_ptr]),
+    "tppo_batcher_layout": (ctypes.c_int, [_c_ptr] * 6),
     "tppo_value_head": (ctypes.c_int, [_c_ptr, _c_i64, _c_i64, _c_i64, _c_ptr, _c_f32, ctypes.c_int, _c_ptr,
                                        _c_ptr, _c_i64, _c_ptr, _c_ptr, _c_ptr, _c_ptr]),
     "tppo_diag_mfma_rate": (ctypes.c_int, [_c_ptr, _c_ptr, _c_i64, ctypes.POINTER(ctypes.c_double), _c_ptr]),
@@ -266,6 +271,50 @@ def tppo_value_head(hidden, w_value, bias=0.0, rows=None, M=None, m_actual=None,
                              _stream())
     _check(rc, "tppo_value_head")
     return v
+
+
+class Batcher:
+    """Successive-batching slot bookkeeping (host side, numpy int32 arrays in and out)."""
+
+    def __init__(self, slots, window, max_response):
+        self._lib = load()
+        self.slots = int(slots)
+        self._h = self._lib.tppo_batcher_create(self.slots, int(window), int(max_response))
+        if not self._h:
+            raise ValueError("tppo_batcher_create: bad sizes")
+
+    def close(self):
+        if self._h:
+            self._lib.tppo_batcher_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    @staticmethod
+    def _i32(a):
+        import numpy as np
+        return np.ascontiguousarray(a, dtype=np.int32)
+
+    def refill(self, prompt_len):
+        p = self._i32(prompt_len)
+        taken = ctypes.c_int64(0)
+        _check(self._lib.tppo_batcher_refill(self._h, p.ctypes.data, p.size, ctypes.byref(taken)),
+               "tppo_batcher_refill")
+        return taken.value
+
+    def advance(self, gen_len, eos):
+        g, e = self._i32(gen_len), self._i32(eos)
+        assert g.size == self.slots and e.size == self.slots
+        _check(self._lib.tppo_batcher_advance(self._h, g.ctypes.data, e.ctypes.data), "tppo_batcher_advance")
+
+    def layout(self):
+        import numpy as np
+        cu = np.empty(self.slots + 1, np.int32)
+        ctx, prompt, done = (np.empty(self.slots, np.int32) for _ in range(3))
+        ids = np.empty(self.slots, np.int64)
+        _check(self._lib.tppo_batcher_layout(self._h, cu.ctypes.data, ctx.ctypes.data, prompt.ctypes.data,
+                                             done.ctypes.data, ids.ctypes.data), "tppo_batcher_layout")
+        return cu, ctx, prompt, done, ids
 
 
 class LossStats(ctypes.Structure):

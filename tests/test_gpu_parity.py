@@ -122,6 +122,43 @@ def test_select_edge_cases(tp):
     assert host(out["keep_len"])[1] == 0
 
 
+@pytest.mark.parametrize("K,l,L", [(12, 512, 1536), (8, 8192, 24576)])
+def test_select_across_successive_batching_steps(tp, K, l, L):
+    """Several training steps of successive batching (window l of a maximum L, as in
+    the paper's 8k of 24k): the policy tokens are the current window, the value
+    tokens every response token of the finished sequences, whichever step made them."""
+    rng = np.random.default_rng(K + l)
+    bt = tp.Batcher(K, l, L)
+    bt.refill(rng.integers(16, 200, size=K))
+    tail = l // 8
+    seen_value = {}
+    for step in range(5):
+        cu, ctx, prompt, done, ids = bt.layout()
+        gen, eos = [], []
+        for k in range(K):
+            room = min(l, L - (cu[k + 1] - cu[k] - prompt[k]))
+            stop = rng.random() < 0.4
+            gen.append(int(rng.integers(1, room + 1)) if stop else room)
+            eos.append(1 if stop else 0)
+        bt.advance(gen, eos)
+        cu, ctx, prompt, done, ids = bt.layout()
+        b = dict(cu_seqlens=cu, ctx_len=ctx, done=done, n_tok=int(cu[-1]),
+                 input_ids=rng.integers(0, 50000, size=int(cu[-1])).astype(np.int32), tail_drop=tail)
+        _, pol = check_select(tp, b)                                       # policy tokens: the current window
+        assert pol["N_resp"] == sum(gen)
+        _, val = check_select(tp, dict(b, ctx_len=prompt), tail_drop=2**31 - 1)   # value tokens
+        lens = (cu[1:] - cu[:-1] - prompt)[done != 0]
+        assert val["M"] == int(lens.sum())
+        for k in np.flatnonzero(done):                                     # the whole response, in order
+            lo, hi = val["sel_off"][k], val["sel_off"][k + 1]
+            assert np.array_equal(val["sel_rows"][lo:hi], np.arange(cu[k] + prompt[k] - 1, cu[k + 1] - 1))
+            assert ids[k] not in seen_value
+            seen_value[ids[k]] = hi - lo
+        bt.refill(rng.integers(16, 200, size=int(done.sum())))
+    assert len(seen_value) >= 3
+    bt.close()
+
+
 # ------------------------------------------------------------------ log-probs
 def check_logprobs(tp, hidden, w, rows, targets, **kw):
     st = tp.new_status("cuda")
