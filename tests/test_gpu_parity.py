@@ -809,3 +809,49 @@ def test_whole_path_tiny(tp):
                                b["xi_low"], b["xi_high"])
         assert_loss_close(got, ref)
     torch.cuda.synchronize()
+
+
+def test_whole_update_step_small(tp):
+    """Forward and backward chained on device buffers (a slice of config 2):
+    select -> log-probs -> EGAE -> loss derivatives -> log-prob derivatives, i.e.
+    d policy_loss / d hidden rows and / d W, against the same chain in the oracle."""
+    import torch
+    b = synth.make_batch("small", B=4, V=2000, H=256)
+    sel = tp.tppo_select(dev(b["cu_seqlens"]), dev(b["ctx_len"]), dev(b["done"]), dev(b["input_ids"]),
+                         b["tail_drop"])
+    n_resp = b["n_resp"]
+    M = int(host(sel["counts"])[0])
+    hidden, w = dev(b["hidden"]), dev(b["w_head"])
+    logp, lse = tp.tppo_token_logprobs(hidden, w, sel["sel_rows"], sel["sel_targets"], M=M,
+                                       out_index=sel["sel_resp_idx"], out_size=n_resp)
+    adv, ret = tp.tppo_egae(dev(b["rewards"]), dev(b["values"]), sel["resp_off"], dev(b["done"]),
+                            b["gamma"], b["lam"])
+    # oracle chain up to the old policy's log-probs (an input of the update)
+    osel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    olp, olse = ofast.token_logprobs(b["hidden"], b["w_head"], osel["sel_rows"], osel["sel_targets"])
+    o_new = np.zeros(n_resp); o_new[osel["sel_resp_idx"]] = olp
+    o_old = (o_new + b["logp_gap"]).astype(np.float32)
+    oadv, oret = ofast.egae(b["rewards"], b["values"], osel["resp_off"], b["done"], b["gamma"], b["lam"])
+    g_lp, g_v, res, st = tp.tppo_ppo_losses_backward(logp, dev(o_old), adv, dev(b["v_new"]), dev(b["values"]),
+                                                     ret, sel["resp_off"], sel["keep_len"], dev(b["done"]),
+                                                     b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"])
+    dh, dw = tp.tppo_token_logprobs_backward(hidden, w, sel["sel_rows"], sel["sel_targets"], lse, g_lp, M=M,
+                                             in_index=sel["sel_resp_idx"])
+    torch.cuda.synchronize()
+    og = ofast.ppo_loss_grads(o_new, o_old, oadv, b["v_new"], b["values"], oret, osel["resp_off"],
+                              osel["keep_len"], b["done"], float(np.float32(b["eps_low"])),
+                              float(np.float32(b["eps_high"])), float(np.float32(b["xi_low"])),
+                              float(np.float32(b["xi_high"])))
+    a = dict(logp_new=o_new.astype(np.float32), logp_old=o_old, adv=oadv.astype(np.float32), v_new=b["v_new"],
+             v_old=b["values"], ret=oret.astype(np.float32))
+    kp, kv = near_kinks(a, b, osel["keep_len"])
+    assert not kp.any() and not kv.any()                     # this seed has no token within 1e-5 of a clip bound
+    g_tok = og["grad_logp"][osel["sel_resp_idx"]]
+    assert np.allclose(host(g_lp)[osel["sel_resp_idx"]], g_tok, rtol=1e-4, atol=1e-9)
+    ref_h, ref_w, abs_h, abs_w = ofast.token_logprob_grads(b["hidden"], b["w_head"], osel["sel_rows"],
+                                                           osel["sel_targets"], g_tok, return_abs_bounds=True)
+    # on top of the bf16 term bound: the upstream derivative itself carries the log-probs' error (2e-3 absolute
+    # on logp moves rho, hence g, by up to 2e-3 relative)
+    tol_h = (DZ_RTOL + 4e-3) * abs_h + 1e-6 * abs_h.max()
+    tol_w = (DZ_RTOL + 4e-3) * abs_w + 1e-6 * abs_w.max()
+    assert np.all(np.abs(host(dh) - ref_h) <= tol_h) and np.all(np.abs(host(dw) - ref_w) <= tol_w)
