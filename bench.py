@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="head32b",
-                    choices=["small", "head7b", "head32b", "longcot", "longcot5x"])
+                    choices=["small", "head7b", "head32b", "longcot", "longcot5x", "longcot20x"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--metric-only", action="store_true",
@@ -186,6 +186,29 @@ def main():
                         traffic=measured_traffic(name, "egae_scan_kernel"),
                         bytes_per_launch=nbytes, avg_ms=stage_ms["egae"])
 
+    if not has_head and not (args.no_reference_rates or args.metric_only):
+        # what the memory system sustains for as many concurrent streams as each kernel has, on arrays of the
+        # same length, cold (each launch walks its own part of a 2 GB pool: nothing comes from the 256 MB cache)
+        per_stream = (4 * n_resp + 15) // 16 * 16
+        pool_r = torch.zeros(6 * 2 * per_stream // 4 + 64, device="cuda")
+        pool_w = torch.empty(2 * 2 * per_stream // 4 + 64, device="cuda")
+
+        def rate(n_read, n_write):
+            run = lambda half: tp.tppo_diag_streams(pool_r[half * 6 * per_stream // 4:], pool_w[half * 2 * per_stream // 4:],
+                                                    per_stream, per_stream, n_read, n_write)
+            run(0); run(1)
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            total = sum(run(i & 1) for i in range(8))
+            e1.record()
+            torch.cuda.synchronize()
+            return total / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        roofline["measured_ceilings"] = {
+            "elementwise_2_read_2_write_streams_GBps (EGAE)": rate(2, 2),
+            "elementwise_6_read_streams_GBps (losses)": rate(6, 0),
+            "elementwise_6_read_2_write_streams_GBps (loss derivatives)": rate(6, 2)}
+        del pool_r, pool_w
     if has_head and not (args.no_reference_rates or args.metric_only):
         roofline["measured_ceilings"] = reference_rates(tp, hidden, w_head, s_rows=sel["sel_rows"][:M])
 

@@ -371,6 +371,21 @@ int tppo_value_head(const void* hidden, int64_t n_rows, int64_t H, int64_t ld_hi
  */
 int tppo_diag_mfma_rate(const void* operands, float* out, int64_t iters, double* flop, void* stream);
 
+/* tppo_diag_streams -- the streaming counterpart: one elementwise pass over
+ * n_read input streams (src + k * stride_bytes) and n_write output streams
+ * (dst + k * stride_bytes), each bytes_per_stream long; every output is the
+ * sum of the inputs.  Lanes on consecutive 16 bytes, 2048 workgroups, nothing
+ * else.  Timing it gives the rate the memory system sustains for as many
+ * concurrent streams as one of this library's kernels has: (n_read, n_write) =
+ * (2,2) EGAE, (1,2) EGAE from terminal rewards, (6,0) losses, (6,2) loss
+ * derivatives, (1,1) plain copy, (1,0) plain read; other shapes ->
+ * TPPO_ERR_PARAM.  Sizes positive multiples of 16, pointers 16-byte aligned.
+ * (With n_write = 0 nothing is written, unless the sum of everything read is
+ * exactly 1.2345e-30, in which case src[0] receives it.)
+ */
+int tppo_diag_streams(const void* src, void* dst, int64_t bytes_per_stream, int64_t stride_bytes,
+                      int32_t n_read, int32_t n_write, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -51,6 +51,7 @@ _SIGNATURES = {
     "tppo_batcher_layout": (ctypes.c_int, [_c_ptr] * 6),
     "tppo_value_head": (ctypes.c_int, [_c_ptr, _c_i64, _c_i64, _c_i64, _c_ptr, _c_f32, ctypes.c_int, _c_ptr,
                                        _c_ptr, _c_i64, _c_ptr, _c_ptr, _c_ptr, _c_ptr]),
+    "tppo_diag_streams": (ctypes.c_int, [_c_ptr, _c_ptr, _c_i64, _c_i64, _c_i32, _c_i32, _c_ptr]),
     "tppo_diag_mfma_rate": (ctypes.c_int, [_c_ptr, _c_ptr, _c_i64, ctypes.POINTER(ctypes.c_double), _c_ptr]),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -365,3 +366,11 @@ def tppo_diag_mfma_rate(operands, out, iters):
     rc = lib.tppo_diag_mfma_rate(_ptr(operands), _ptr(out), int(iters), ctypes.byref(flop), _stream())
     _check(rc, "tppo_diag_mfma_rate")
     return flop.value
+
+
+def tppo_diag_streams(src, dst, bytes_per_stream, stride_bytes, n_read, n_write):
+    """Elementwise pass over n_read input and n_write output streams; returns the bytes moved."""
+    lib = load()
+    _check(lib.tppo_diag_streams(_ptr(src), _ptr(dst), int(bytes_per_stream), int(stride_bytes), int(n_read),
+                                 int(n_write), _stream()), "tppo_diag_streams")
+    return int(bytes_per_stream) * (n_read + n_write)

@@ -8,6 +8,8 @@
 // array is read, and a chunk outside a set issues no loads for that set.  Sums
 // are token-level (Sec. 4.1.1): fp32 per thread over a few tokens, fp64 across
 // threads and workgroups, fixed order, no atomics -> bit-identical reruns.
+#include <stdlib.h>
+
 #include "chunks.h"
 
 namespace tppo {
@@ -51,12 +53,22 @@ __global__ __launch_bounds__(kBuildThreads) void loss_init_kernel(const int32_t*
 
 typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte access, 4-byte aligned
 
+// exp for the probability ratio: one multiply and the hardware exp2 (relative error ~1e-7 (1 + |x|), far inside
+// the tolerances; the library expf costs ~15 more instructions per token in a kernel that is half VALU-bound)
+__device__ __forceinline__ float ratio_exp(float x) {
+#ifdef TPPO_LIBM_EXP
+    return expf(x);
+#else
+    return __builtin_amdgcn_exp2f(x * 1.4426950408889634f);
+#endif
+}
+
 __device__ __forceinline__ float clampf(float x, float lo, float hi) {
     return fminf(fmaxf(x, lo), hi);
 }
 
 __device__ __forceinline__ float surrogate(float ln, float lo, float a, float rlo, float rhi) {
-    const float rho = expf(ln - lo);
+    const float rho = ratio_exp(ln - lo);
     return fminf(rho * a, clampf(rho, rlo, rhi) * a);
 }
 
@@ -93,74 +105,88 @@ __device__ __forceinline__ void load4(float (&x)[4], const float* __restrict__ s
     }
 }
 
+// What one thread holds of one chunk: kLossGroups 16-byte groups of each of the six arrays.
+constexpr int kLossGroups = kChunkTokens / (4 * kChunkThreads);      // 2
+struct LossRegs {
+    float ln[kLossGroups][4], lo[kLossGroups][4], a[kLossGroups][4];
+    float v[kLossGroups][4], vo[kLossGroups][4], r[kLossGroups][4];
+    int n_pol[kLossGroups], n_val[kLossGroups];
+};
+
+// issue the loads of a chunk (nothing is loaded for groups that hold no member of a set)
+__device__ __forceinline__ void loss_load(LossRegs& x, const LossParams& p, const Chunk& ch, int keep, int fin,
+                                          bool has_pol, bool has_val, int tid) {
+    const int start = ch.start, len = ch.len();
+    const int pol_in_chunk = has_pol ? min(max(keep - ch.number() * kChunkTokens, 0), len) : 0;
+    const int val_in_chunk = (has_val && fin != 0) ? len : 0;
+#pragma unroll
+    for (int g = 0; g < kLossGroups; ++g) {
+        const int k0 = g * 4 * kChunkThreads + tid * 4;
+        x.n_pol[g] = min(max(pol_in_chunk - k0, 0), 4);
+        x.n_val[g] = min(max(val_in_chunk - k0, 0), 4);
+        if (x.n_pol[g] > 0) {
+            load4(x.ln[g], p.logp_new, start + k0, x.n_pol[g]);
+            load4(x.lo[g], p.logp_old, start + k0, x.n_pol[g]);
+            load4(x.a[g], p.adv, start + k0, x.n_pol[g]);
+        }
+        if (x.n_val[g] > 0) {
+            load4(x.v[g], p.v_new, start + k0, x.n_val[g]);
+            load4(x.vo[g], p.v_old, start + k0, x.n_val[g]);
+            load4(x.r[g], p.ret, start + k0, x.n_val[g]);
+        }
+    }
+}
+
 __global__ __launch_bounds__(kChunkThreads) void loss_partial_kernel(LossParams p, void* ws_raw) {
     __shared__ double s_red[kChunkThreads / kWave];
     LossWs ws = loss_ws(ws_raw, p.cap);
     const int tid = threadIdx.x;
     const bool has_pol = p.logp_new != nullptr, has_val = p.v_new != nullptr;
     const int count = *ws.n_chunks;
-    constexpr int kGroups = kChunkTokens / (4 * kChunkThreads);      // 16-byte groups per thread: 2
 
     float pol_acc = 0.f, val_acc = 0.f;
     int w = blockIdx.x;
-    Chunk cur = ws.chunks[w < count ? w : 0];
-    int keep = 0, fin = 0;
+    // Software pipeline over the workgroup's chunks: the loads of chunk i+1 are in flight while chunk i is
+    // summed, and the descriptor (with its sequence's keep_len / done) of chunk i+2 while chunk i+1 loads.
+    LossRegs cur;
+    Chunk d_next = {};
+    int keep_next = 0, fin_next = 0;
     if (w < count) {
-        keep = p.keep_len[cur.seg];
-        fin = p.done[cur.seg];
+        const Chunk d = ws.chunks[w];
+        loss_load(cur, p, d, p.keep_len[d.seg], p.done[d.seg], has_pol, has_val, tid);
+        if (w + (int)gridDim.x < count) {
+            d_next = ws.chunks[w + gridDim.x];
+            keep_next = p.keep_len[d_next.seg];
+            fin_next = p.done[d_next.seg];
+        }
     }
     for (; w < count; w += gridDim.x) {
-        const int start = cur.start, len = cur.len();
-        // tokens of this chunk in the policy set: window positions below keep_len
-        const int pol_in_chunk = has_pol ? min(max(keep - cur.number() * kChunkTokens, 0), len) : 0;
-        const int val_in_chunk = (has_val && fin != 0) ? len : 0;
-        // metadata of the next chunk: in flight while this one streams
-        const int w_next = w + gridDim.x;
-        Chunk nxt = cur;
-        int keep_n = 0, fin_n = 0;
-        if (w_next < count) {
-            nxt = ws.chunks[w_next];
-            keep_n = p.keep_len[nxt.seg];
-            fin_n = p.done[nxt.seg];
-        }
-        float ln[kGroups][4], lo[kGroups][4], a[kGroups][4], v[kGroups][4], vo[kGroups][4], r[kGroups][4];
-        int n_pol[kGroups], n_val[kGroups];
-#pragma unroll
-        for (int g = 0; g < kGroups; ++g) {
-            const int k0 = g * 4 * kChunkThreads + tid * 4;
-            n_pol[g] = min(max(pol_in_chunk - k0, 0), 4);
-            n_val[g] = min(max(val_in_chunk - k0, 0), 4);
-            if (n_pol[g] > 0) {
-                load4(ln[g], p.logp_new, start + k0, n_pol[g]);
-                load4(lo[g], p.logp_old, start + k0, n_pol[g]);
-                load4(a[g], p.adv, start + k0, n_pol[g]);
-            }
-            if (n_val[g] > 0) {
-                load4(v[g], p.v_new, start + k0, n_val[g]);
-                load4(vo[g], p.v_old, start + k0, n_val[g]);
-                load4(r[g], p.ret, start + k0, n_val[g]);
-            }
+        const int w1 = w + gridDim.x, w2 = w1 + gridDim.x;
+        LossRegs nxt;
+        if (w1 < count) loss_load(nxt, p, d_next, keep_next, fin_next, has_pol, has_val, tid);
+        if (w2 < count) {
+            d_next = ws.chunks[w2];
+            keep_next = p.keep_len[d_next.seg];
+            fin_next = p.done[d_next.seg];
         }
 #pragma unroll
-        for (int g = 0; g < kGroups; ++g) {
-            if (n_pol[g] > 0) {
+        for (int g = 0; g < kLossGroups; ++g) {
+            if (cur.n_pol[g] > 0) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float t = surrogate(ln[g][e], lo[g][e], a[g][e], p.ratio_lo, p.ratio_hi);
-                    pol_acc += e < n_pol[g] ? t : 0.f;     // select, never multiply by a mask
+                    const float t = surrogate(cur.ln[g][e], cur.lo[g][e], cur.a[g][e], p.ratio_lo, p.ratio_hi);
+                    pol_acc += e < cur.n_pol[g] ? t : 0.f;     // select, never multiply by a mask
                 }
             }
-            if (n_val[g] > 0) {
+            if (cur.n_val[g] > 0) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float t = value_term(v[g][e], vo[g][e], r[g][e], p.xi_low, p.xi_high);
-                    val_acc += e < n_val[g] ? t : 0.f;
+                    const float t = value_term(cur.v[g][e], cur.vo[g][e], cur.r[g][e], p.xi_low, p.xi_high);
+                    val_acc += e < cur.n_val[g] ? t : 0.f;
                 }
             }
         }
-        cur = nxt;
-        keep = keep_n;
-        fin = fin_n;
+        if (w1 < count) cur = nxt;
     }
     const double ps = block_sum((double)pol_acc, s_red);
     const double vs = block_sum((double)val_acc, s_red);
@@ -376,7 +402,7 @@ __global__ __launch_bounds__(kChunkThreads) void loss_grad_kernel(GradParams gp,
                 if (n_pol[g] > 0) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float rho = expf(ln[g][e] - lo[g][e]);
+                        const float rho = ratio_exp(ln[g][e] - lo[g][e]);
                         const float u = rho * a[g][e];
                         const float c = clampf(rho, p.ratio_lo, p.ratio_hi) * a[g][e];
                         const bool in_set = e < n_pol[g], unclipped = u <= c;
@@ -460,6 +486,28 @@ __global__ __launch_bounds__(kChunkThreads) void loss_grad_final_kernel(void* ws
 
 }  // namespace tppo
 
+namespace tppo {
+// Grid of the persistent streaming kernels: as many workgroups as the device keeps resident at once (asked of
+// the runtime once per device and kernel), so that every workgroup starts at time zero and none queues behind.
+template <class Kernel>
+static int resident_groups(Kernel kernel, int* cache) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return kLossMaxGroups;
+    if (cache[dev] > 0) return cache[dev];
+    int per_cu = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kChunkThreads, 0) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || per_cu < 1)
+        return kLossMaxGroups;
+    const int n = per_cu * cus;
+    cache[dev] = n < kLossMaxGroups ? n : kLossMaxGroups;
+    if (const char* e = getenv("TPPO_LOSS_GROUPS")) {      // tuning override
+        const int forced = atoi(e);
+        if (forced >= 1 && forced <= kLossMaxGroups) cache[dev] = forced;
+    }
+    return cache[dev];
+}
+}  // namespace tppo
+
 extern "C" size_t tppo_ppo_losses_workspace_bytes(int64_t n_resp, int64_t B) {
     if (n_resp < 0 || B < 0) return 256;
     return tppo::loss_ws_bytes(tppo::max_chunks(n_resp, B));
@@ -503,7 +551,9 @@ extern "C" int tppo_ppo_losses(const float* logp_new, const float* logp_old, con
         p.cap = cap;
         p.ratio_lo = 1.f - eps_low; p.ratio_hi = 1.f + eps_high;
         p.xi_low = xi_low; p.xi_high = xi_high;
-        groups = cap < kLossMaxGroups ? cap : kLossMaxGroups;
+        static int cache[64] = {};
+        const int resident = resident_groups(loss_partial_kernel, cache);
+        groups = cap < resident ? cap : resident;
         hipLaunchKernelGGL(loss_partial_kernel, dim3(groups), dim3(kChunkThreads), 0, s, p, workspace);
         if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
     }
@@ -562,7 +612,9 @@ extern "C" int tppo_ppo_losses_backward(const float* logp_new, const float* logp
             gp.grad_logp = grad_logp; gp.grad_v = grad_v;
             gp.policy_scale = policy_scale; gp.value_scale = value_scale;
             gp.policy_denominator = policy_denominator; gp.value_denominator = value_denominator;
-            groups = cap < kLossMaxGroups ? cap : kLossMaxGroups;
+            static int cache[64] = {};
+            const int resident = resident_groups(loss_grad_kernel, cache);
+            groups = cap < resident ? cap : resident;
             hipLaunchKernelGGL(loss_grad_kernel, dim3(groups), dim3(kChunkThreads), 0, s, gp, workspace);
             if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
         }

@@ -40,6 +40,10 @@ CONFIGS = {
     "longcot5x": dict(B=2176, ctx=1, window=20480, len_dist=("loguniform", 256, 20480),
                       p_done=0.3, H=0, V=0, dtype="f32",
                       tail_drop=1024, eps=(0.2, 0.28), seed=1006),
+    # same distribution, 42 M tokens: shows the streaming kernels' rate once launch ramp and drain are small
+    "longcot20x": dict(B=8704, ctx=1, window=20480, len_dist=("loguniform", 256, 20480),
+                       p_done=0.3, H=0, V=0, dtype="f32",
+                       tail_drop=1024, eps=(0.2, 0.28), seed=1007),
 }
 GAMMA = 1.0
 LAMBDA = 0.95

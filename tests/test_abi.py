@@ -84,6 +84,11 @@ def test_host_side_argument_errors(lib):
     assert vh(256, 4, 64, 32, 256, 0.0, 1, None, None, 4, None, 256, None, None) == S          # ld < H
     assert vh(256, 4, 64, 64, None, 0.0, 1, None, None, 4, None, 256, None, None) == N
     assert vh(256, 4, 64, 64, 256, 0.0, 1, None, None, 0, None, 256, None, None) == 0          # M = 0
+    # diagnostic streams
+    assert lib.tppo_diag_streams(None, None, 64, 64, 1, 0, None) == N
+    assert lib.tppo_diag_streams(256, None, 40, 64, 1, 0, None) == S
+    assert lib.tppo_diag_streams(264, None, 64, 64, 1, 0, None) == P
+    assert lib.tppo_diag_streams(256, 512, 64, 64, 3, 3, None) == P              # not one of the offered shapes
     # diagnostic loop
     assert lib.tppo_diag_mfma_rate(None, None, 10, None, None) == N
     assert lib.tppo_diag_mfma_rate(256, 256, -1, None, None) == S
