@@ -678,3 +678,16 @@ def test_successive_batching_invariants():
     assert len(finished) > K                                         # slots were reused
     with pytest.raises(ValueError):
         sb.advance([l + 1] * K, [0] * K)
+
+
+def test_value_set_is_the_whole_window_whatever_keep_len():
+    """Sec. 3.2: value tokens are all window tokens of finished sequences; the policy
+    set's keep_len has no say in it (a caller may drop policy tokens of a finished sequence)."""
+    pol, val = ofast.loss_masks([0, 5, 9], [2, 1], [1, 0])
+    assert pol.tolist() == [True, True, False, False, False, True, False, False, False]
+    assert val.tolist() == [True] * 5 + [False] * 4
+    z = np.zeros(9)
+    for impl in (odef, ofast):
+        out = impl.ppo_losses(z, z, z + 1, z + 1, z, z, [0, 5, 9], [2, 1], [1, 0], 0.2, 0.28, 0.5, 0.6)
+        assert out["n_policy"] == 3 and out["n_value"] == 5
+        assert out["value_loss"] == pytest.approx(0.5)             # v = 1, R = 0, clipped 0.6: max(1, 0.36) / 2
