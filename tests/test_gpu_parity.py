@@ -652,6 +652,13 @@ def test_losses_halves_and_empty_sets(tp):
     only_p = run_losses(tp, a, b, keep, skip="value")
     assert only_v["value_loss"] == full["value_loss"] and only_v["policy_loss"] == 0.0 and only_v["n_policy"] == 0
     assert only_p["policy_loss"] == full["policy_loss"] and only_p["value_loss"] == 0.0 and only_p["n_value"] == 0
+    # policy tokens dropped from finished sequences too: the value set is still their whole window
+    half = (keep // 2).astype(np.int32)
+    ref = ofast.ppo_losses(a["logp_new"], a["logp_old"], a["adv"], a["v_new"], a["v_old"], a["ret"],
+                           b["resp_off"], half, b["done"], b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"])
+    got = run_losses(tp, a, b, half)
+    assert_loss_close(got, ref)
+    assert got["n_value"] == full["n_value"] and got["n_policy"] < full["n_policy"]
     # nothing kept and nothing finished
     none_done = dict(b, done=np.zeros_like(b["done"]))
     got = run_losses(tp, a, none_done, np.zeros_like(keep))
