@@ -289,7 +289,7 @@ int tppo_ppo_losses_backward(const float* logp_new, const float* logp_old, const
  *      grad_w[V, H]       device fp32, overwritten, or added to when
  *                         accumulate_w != 0.  Either may be NULL to skip it.
  * workspace: at least tppo_token_logprobs_backward_workspace_bytes; a larger
- *      one lets more tokens (up to 16384) go through per chunk.
+ *      one lets more tokens (up to 32768) go through per chunk.
  */
 size_t tppo_token_logprobs_backward_workspace_bytes(int64_t M, int64_t H, int64_t V, tppo_dtype dt);
 int tppo_token_logprobs_backward(const void* hidden, int64_t n_rows, int64_t H, int64_t ld_hidden,

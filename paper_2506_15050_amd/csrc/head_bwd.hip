@@ -187,7 +187,7 @@ static const HeadVariant kDzVariant = {head_mfma_kernel<BwdCfg, DzEpilogue>, Bwd
 static const HeadVariant kGemmVariant = {head_mfma_kernel<BwdCfg, StoreEpilogue>, BwdCfg::kTileV, BwdCfg::kTileT,
                                          BwdCfg::kThreads, BwdCfg::kLdsBytes, BwdCfg::kWgsPerCu};
 
-constexpr int64_t kBwdChunkDefault = 8192, kBwdChunkMax = 16384;
+constexpr int64_t kBwdChunkDefault = 16384, kBwdChunkMax = 32768;
 
 struct BwdLayout {
     int64_t v_pad, chunk;              // vocabulary padded to 64; tokens per chunk (multiple of 256)
