@@ -30,61 +30,71 @@ struct Chunk {
 
 static inline int64_t max_chunks(int64_t n_resp, int64_t B) { return n_resp / kChunkTokens + B + 1; }
 
-// One workgroup: chunk counts per sequence, their prefix sums in reverse
-// sequence order, then every sequence writes its own descriptors.  Sequences
-// with a bad layout (negative length, out of range) contribute no chunk and set
-// the status bit.  n_chunks[0] receives the total.
+// One workgroup builds the list.  Thread t owns a contiguous block of sequences
+// (in reverse order: last sequence first), so whatever B is there is ONE
+// workgroup-wide prefix sum: pass A adds up the chunk counts of the block, the
+// scan turns the totals into each block's first list position, pass B re-reads
+// the (cache-resident) offsets and writes the descriptors.  (Measured with
+// device timers on 8704 sequences / 24 k chunks: the descriptor stores, one
+// cache line per lane, are what takes the time -- ~8 us per 11 k descriptors;
+// staging the metadata through LDS or giving every list position its own
+// thread with a bisection is no faster.)  Sequences with a bad layout (negative
+// length, out of range) contribute no chunk and set the status bit.
+// n_chunks[0] receives the total.
+__device__ __forceinline__ int chunks_of(const int32_t* __restrict__ resp_off, int i, int n_resp, int& lo, int& len,
+                                         int32_t* status) {
+    lo = resp_off[i];
+    const int hi = resp_off[i + 1];
+    len = 0;
+    if (lo < 0 || hi < lo || hi > n_resp) {
+        if (status) set_status(status, TPPO_STATUS_BAD_LAYOUT);
+        return 0;
+    }
+    len = hi - lo;
+    return (len + kChunkTokens - 1) / kChunkTokens;
+}
+
 __device__ __forceinline__ void build_chunks(const int32_t* __restrict__ resp_off, int B, int n_resp,
                                              Chunk* __restrict__ chunks, int cap,
                                              int32_t* __restrict__ n_chunks, int32_t* status) {
     __shared__ int s_wave[kBuildThreads / kWave];
-    __shared__ int s_carry;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) {
-        s_carry = 0;
-        if (resp_off[0] != 0 || resp_off[B] != n_resp) set_status(status, TPPO_STATUS_BAD_LAYOUT);
-    }
-    __syncthreads();
-    for (int base = 0; base < B; base += kBuildThreads) {
-        const int i = B - 1 - (base + tid);                    // reverse sequence order
-        int lo = 0, len = 0, cnt = 0;
-        if (i >= 0) {
-            lo = resp_off[i];
-            const int hi = resp_off[i + 1];
-            if (lo < 0 || hi < lo || hi > n_resp) {
-                set_status(status, TPPO_STATUS_BAD_LAYOUT);
-            } else {
-                len = hi - lo;
-                cnt = (len + kChunkTokens - 1) / kChunkTokens;
-            }
-        }
-        int inc = cnt;
+    if (tid == 0 && (resp_off[0] != 0 || resp_off[B] != n_resp)) set_status(status, TPPO_STATUS_BAD_LAYOUT);
+    const int per = (B + kBuildThreads - 1) / kBuildThreads;
+    const int r_begin = min(tid * per, B), r_end = min(r_begin + per, B);     // positions in reverse sequence order
+    int lo, len, mine = 0;
+    for (int r = r_begin; r < r_end; ++r) mine += chunks_of(resp_off, B - 1 - r, n_resp, lo, len, status);
+    int inc = mine;
 #pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            const int y = __shfl_up(inc, off);
-            if (lane >= off) inc += y;
-        }
-        if (lane == kWave - 1) s_wave[wave] = inc;
-        __syncthreads();
-        int pre = s_carry;
-        for (int w = 0; w < wave; ++w) pre += s_wave[w];
-        const int first = pre + inc - cnt;                      // processing index of my last chunk
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int y = __shfl_up(inc, off);
+        if (lane >= off) inc += y;
+    }
+    if (lane == kWave - 1) s_wave[wave] = inc;
+    __syncthreads();
+    int before = inc - mine, total = 0;
+    for (int w = 0; w < kBuildThreads / kWave; ++w) {
+        before += w < wave ? s_wave[w] : 0;
+        total += s_wave[w];
+    }
+    int next = before;                                          // processing index of my next sequence's last chunk
+    for (int r = r_begin; r < r_end; ++r) {
+        const int i = B - 1 - r;
+        const int cnt = chunks_of(resp_off, i, n_resp, lo, len, nullptr);
         for (int c = cnt - 1; c >= 0; --c) {
             Chunk d;
             d.start = lo + c * kChunkTokens;
             d.pos_len = (c << 11) | (min(kChunkTokens, len - c * kChunkTokens) - 1);
             d.seg = i;
             d.after = cnt - 1 - c;
-            const int w = first + (cnt - 1 - c);
+            const int w = next + (cnt - 1 - c);
             if (w < cap) chunks[w] = d;                         // overlapping sequences cannot overflow the list
         }
-        __syncthreads();
-        if (tid == kBuildThreads - 1) s_carry = pre + inc;
-        __syncthreads();
+        next += cnt;
     }
     if (tid == 0) {
-        if (s_carry > cap) set_status(status, TPPO_STATUS_BAD_LAYOUT);
-        n_chunks[0] = min(s_carry, cap);
+        if (total > cap) set_status(status, TPPO_STATUS_BAD_LAYOUT);
+        n_chunks[0] = min(total, cap);
     }
 }
 

@@ -21,6 +21,24 @@ __device__ __forceinline__ Quad add4(Quad a, Quad b) {
 
 static inline int64_t select_max_chunks(int64_t capacity, int64_t B) { return capacity / kChunkTokens + B + 1; }
 
+// window / keep lengths of sequence i (a bad layout counts as an empty window and sets the status bit)
+__device__ __forceinline__ Quad lengths_of(const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ ctx_len,
+                                           const int32_t* __restrict__ done, int i, int n_tok, int tail_drop,
+                                           int32_t* status) {
+    const int lo = cu_seqlens[i], hi = cu_seqlens[i + 1], ctx = ctx_len[i];
+    int win = hi - lo - ctx;
+    if (ctx < 1 || win < 0 || lo < 0 || hi > n_tok) {
+        if (status) set_status(status, TPPO_STATUS_BAD_LAYOUT);
+        win = 0;
+    }
+    const bool fin = done[i] != 0;
+    const int keep = fin ? win : max(win - tail_drop, 0);
+    return {win, keep, fin ? win : 0, (keep + kChunkTokens - 1) / kChunkTokens};
+}
+
+// Thread t owns a contiguous block of sequences, so there is one workgroup-wide prefix sum whatever B is:
+// pass A adds up the block, the scan gives the block's starting offsets, pass B re-reads the (cache-resident)
+// metadata and writes the per-sequence outputs and chunk descriptors.
 __global__ __launch_bounds__(kScanThreads) void select_scan_kernel(
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ ctx_len,
     const int32_t* __restrict__ done, int B, int n_tok, int tail_drop,
@@ -28,66 +46,52 @@ __global__ __launch_bounds__(kScanThreads) void select_scan_kernel(
     int32_t* __restrict__ keep_len, int64_t* __restrict__ counts, Chunk* __restrict__ chunks,
     int chunk_cap, int32_t* __restrict__ n_chunks, int32_t* status) {
     __shared__ Quad wave_tot[kScanThreads / kWave];
-    __shared__ Quad carry_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = (B + kScanThreads - 1) / kScanThreads;
+    const int i_begin = min(tid * per, B), i_end = min(i_begin + per, B);
+    Quad mine = {0, 0, 0, 0};
+    for (int i = i_begin; i < i_end; ++i) mine = add4(mine, lengths_of(cu_seqlens, ctx_len, done, i, n_tok, tail_drop, status));
+    Quad inc = mine;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        Quad y = {__shfl_up(inc.win, off), __shfl_up(inc.keep, off), __shfl_up(inc.val, off),
+                  __shfl_up(inc.chunks, off)};
+        if (lane >= off) inc = add4(inc, y);
+    }
+    if (lane == kWave - 1) wave_tot[wave] = inc;
+    __syncthreads();
+    Quad run = {inc.win - mine.win, inc.keep - mine.keep, inc.val - mine.val, inc.chunks - mine.chunks};
+    Quad total = {0, 0, 0, 0};
+    for (int w = 0; w < kScanThreads / kWave; ++w) {
+        if (w < wave) run = add4(run, wave_tot[w]);
+        total = add4(total, wave_tot[w]);
+    }
     if (tid == 0) {
-        carry_s = {0, 0, 0, 0};
         resp_off[0] = 0;
         sel_off[0] = 0;
     }
-    __syncthreads();
-    for (int base = 0; base < B; base += kScanThreads) {
-        const int i = base + tid;
-        Quad x = {0, 0, 0, 0};
-        if (i < B) {
-            const int lo = cu_seqlens[i], hi = cu_seqlens[i + 1], ctx = ctx_len[i];
-            int win = hi - lo - ctx;
-            if (ctx < 1 || win < 0 || lo < 0 || hi > n_tok) {
-                set_status(status, TPPO_STATUS_BAD_LAYOUT);
-                win = 0;
-            }
-            const bool fin = done[i] != 0;
-            const int keep = fin ? win : max(win - tail_drop, 0);
-            keep_len[i] = keep;
-            x = {win, keep, fin ? win : 0, (keep + kChunkTokens - 1) / kChunkTokens};
-        }
-        // inclusive scan inside the wave
-        Quad inc = x;
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            Quad y = {__shfl_up(inc.win, off), __shfl_up(inc.keep, off), __shfl_up(inc.val, off),
-                      __shfl_up(inc.chunks, off)};
-            if (lane >= off) inc = add4(inc, y);
-        }
-        if (lane == kWave - 1) wave_tot[wave] = inc;
-        __syncthreads();
-        Quad pre = carry_s;
-        for (int w = 0; w < wave; ++w) pre = add4(pre, wave_tot[w]);
-        inc = add4(inc, pre);
-        if (i < B) {
-            resp_off[i + 1] = inc.win;
-            sel_off[i + 1] = inc.keep;
-            if (chunks) {
-                const int first = inc.chunks - x.chunks, m0 = inc.keep - x.keep;
-                for (int c = 0; c < x.chunks; ++c) {
-                    Chunk d;
-                    d.start = m0 + c * kChunkTokens;
-                    d.pos_len = (c << 11) | (min(kChunkTokens, x.keep - c * kChunkTokens) - 1);
-                    d.seg = i;
-                    d.after = x.chunks - 1 - c;
-                    if (first + c < chunk_cap) chunks[first + c] = d;
-                }
+    for (int i = i_begin; i < i_end; ++i) {
+        const Quad x = lengths_of(cu_seqlens, ctx_len, done, i, n_tok, tail_drop, nullptr);
+        keep_len[i] = x.keep;
+        if (chunks) {
+            for (int c = 0; c < x.chunks; ++c) {
+                Chunk d;
+                d.start = run.keep + c * kChunkTokens;
+                d.pos_len = (c << 11) | (min(kChunkTokens, x.keep - c * kChunkTokens) - 1);
+                d.seg = i;
+                d.after = x.chunks - 1 - c;
+                if (run.chunks + c < chunk_cap) chunks[run.chunks + c] = d;
             }
         }
-        __syncthreads();
-        if (tid == kScanThreads - 1) carry_s = inc;
-        __syncthreads();
+        run = add4(run, x);
+        resp_off[i + 1] = run.win;
+        sel_off[i + 1] = run.keep;
     }
     if (tid == 0) {
-        counts[0] = carry_s.keep;
-        counts[1] = carry_s.win;
-        counts[2] = carry_s.val;
-        if (n_chunks) n_chunks[0] = min(carry_s.chunks, chunk_cap);
+        counts[0] = total.keep;
+        counts[1] = total.win;
+        counts[2] = total.val;
+        if (n_chunks) n_chunks[0] = min(total.chunks, chunk_cap);
     }
 }
 
