@@ -288,6 +288,8 @@ int tppo_ppo_losses_backward(const float* logp_new, const float* logp_old, const
  * out: grad_hidden[M, H]  device fp32, row t belongs to hidden row sel_rows[t];
  *      grad_w[V, H]       device fp32, overwritten, or added to when
  *                         accumulate_w != 0.  Either may be NULL to skip it.
+ * status is not written by this call (bad rows and targets were reported by
+ * the forward pass; rows are clamped, a bad target matches no column).
  * workspace: at least tppo_token_logprobs_backward_workspace_bytes; a larger
  *      one lets more tokens (up to 32768) go through per chunk.
  */
