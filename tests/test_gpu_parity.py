@@ -862,3 +862,55 @@ def test_whole_update_step_small(tp):
     tol_h = (DZ_RTOL + 4e-3) * abs_h + 1e-6 * abs_h.max()
     tol_w = (DZ_RTOL + 4e-3) * abs_w + 1e-6 * abs_w.max()
     assert np.all(np.abs(host(dh) - ref_h) <= tol_h) and np.all(np.abs(host(dw) - ref_w) <= tol_w)
+
+
+# ------------------------------------------------------------------ randomised batches
+@pytest.mark.parametrize("seed", range(12))
+def test_random_batches_all_stages(tp, seed):
+    """Random layouts (1..40 sequences, windows of 0..5000 tokens, contexts of 1..50, any
+    mix of finished / truncated, any tail_drop, chunk boundaries hit on purpose): select,
+    EGAE (dense and terminal rewards), losses and their derivatives against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    B = int(rng.integers(1, 41))
+    special = np.array([0, 1, 2, 2047, 2048, 2049, 4096, 4097])
+    win = np.where(rng.random(B) < 0.3, rng.choice(special, size=B), rng.integers(0, 5001, size=B))
+    ctx = rng.integers(1, 51, size=B)
+    done = (rng.random(B) < rng.random()).astype(np.int32)
+    cu = np.concatenate([[0], np.cumsum(ctx + win)]).astype(np.int32)
+    n_tok = int(cu[-1])
+    b = dict(cu_seqlens=cu, ctx_len=ctx.astype(np.int32), done=done, n_tok=n_tok,
+             input_ids=rng.integers(0, 1000, size=n_tok).astype(np.int32),
+             tail_drop=int(rng.choice([0, 1, 7, 1024, 6000])))
+    _, sel = check_select(tp, b)
+    off, keep, n = sel["resp_off"], sel["keep_len"], sel["N_resp"]
+    if n == 0:
+        return
+    gamma, lam = float(rng.choice([1.0, 0.99])), float(rng.choice([0.0, 0.95, 1.0]))
+    rewards = np.where(rng.random(n) < 0.05, rng.normal(size=n), 0.0).astype(np.float32)
+    values = rng.uniform(-1, 1, size=n).astype(np.float32)
+    boot = rng.uniform(-1, 1, size=B).astype(np.float32) if seed % 2 else None
+    adv, ret = check_egae(tp, rewards, values, off, done, gamma, lam, bootstrap=boot)
+    terminal = rng.choice([-1.0, 1.0], size=B).astype(np.float32)
+    dense = np.zeros(n, np.float32)
+    for i in range(B):
+        if done[i] and off[i + 1] > off[i]:
+            dense[off[i + 1] - 1] = terminal[i]
+    ta, tr = tp.tppo_egae_terminal(dev(terminal), dev(values), dev(off), dev(done), gamma, lam)
+    ref_a, ref_r = ofast.egae(dense, values, off, done, float(np.float32(gamma)), float(np.float32(lam)))
+    assert_egae_close(host(ta), ref_a, "adv")
+    assert_egae_close(host(tr), ref_r, "ret")
+    a = dict(logp_new=(-np.abs(rng.normal(size=n)) - 0.01).astype(np.float32), adv=adv, ret=ret,
+             v_new=(values + rng.normal(0, 0.3, size=n)).astype(np.float32), v_old=values)
+    a["logp_old"] = (a["logp_new"] + rng.normal(0, 0.1, size=n)).astype(np.float32)
+    bb = dict(resp_off=off, done=done, eps_low=0.2, eps_high=0.28, xi_low=0.5, xi_high=0.6)
+    ref = ofast.ppo_losses(a["logp_new"], a["logp_old"], a["adv"], a["v_new"], a["v_old"], a["ret"], off, keep, done,
+                           float(np.float32(0.2)), float(np.float32(0.28)), 0.5, float(np.float32(0.6)))
+    assert_loss_close(run_losses(tp, a, bb, keep), ref)
+    g_lp, g_v, losses, stats = run_loss_grads(tp, a, bb, keep)
+    og = ofast.ppo_loss_grads(a["logp_new"], a["logp_old"], a["adv"], a["v_new"], a["v_old"], a["ret"], off, keep, done,
+                              float(np.float32(0.2)), float(np.float32(0.28)), 0.5, float(np.float32(0.6)))
+    kp, kv = near_kinks(a, bb, keep)
+    f = {k: v.astype(np.float64) for k, v in a.items()}
+    assert_grads_close(g_lp, og["grad_logp"], kp, -np.exp(f["logp_new"] - f["logp_old"]) * f["adv"] / max(og["n_policy"], 1))
+    assert_grads_close(g_v, og["grad_v"], kv, (f["v_new"] - f["ret"]) / max(og["n_value"], 1))
+    assert_loss_close(losses, ref)
