@@ -9,10 +9,10 @@
 // 16 different vocabulary entries: the running maximum, the running sum of
 // exponentials and the target logit of a token live in that lane's registers
 // across all vocabulary tiles of the workgroup, with no cross-lane traffic
-// until the very end.  The grid is (token tiles) x (vocabulary splits); each
-// workgroup sweeps its share of vocabulary tiles and writes one
-// (max, sumexp, target logit) triple per token; a small kernel merges the
-// splits into logp and lse.
+// until the very end.  The work is (token tiles) x (vocabulary splits), handed
+// to a persistent grid (head_tile.h); each pair sweeps its share of vocabulary
+// tiles and writes one (max, sumexp, target logit) triple per token; a small
+// kernel merges the splits into logp and lse.
 //
 // Both operands are K-contiguous in memory ([V,H] and [rows,H]), which is the
 // layout the MFMA wants for both, so tiles are staged into LDS as 16-byte
