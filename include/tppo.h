@@ -358,8 +358,8 @@ int tppo_value_head(const void* hidden, int64_t n_rows, int64_t H, int64_t ld_hi
 
 /* ---------------------------------------------------------------------------
  * tppo_diag_mfma_rate -- a measuring stick, not a step of the method: runs the
- * inner loop of the LM-head kernel (v_mfma_f32_32x32x16_bf16, 8 wavefronts per
- * workgroup, one workgroup per CU, 16 MFMAs per wavefront and iteration) on
+ * inner loop of the LM-head kernel (v_mfma_f32_16x16x32_bf16, 8 wavefronts per
+ * workgroup, one workgroup per CU, 32 MFMAs per wavefront and iteration) on
  * operands held in registers, with no memory traffic.  Timing it gives the
  * matrix-core rate this chip sustains under its power limit, the practical
  * ceiling beside the datasheet peak in the benchmark's roofline entry.

@@ -1,6 +1,6 @@
 // tppo_diag_mfma_rate: the matrix-core rate this chip sustains with operands in
 // registers -- the inner loop of the LM-head kernel (8 wavefronts per
-// workgroup, each a 128 x 64 tile of v_mfma_f32_32x32x16_bf16, one workgroup
+// workgroup, each a 128 x 64 tile of v_mfma_f32_16x16x32_bf16, one workgroup
 // per CU) with no LDS, no global loads and no softmax.  A measuring stick for
 // the benchmark's roofline line, not a step of the method.
 #include "common.h"
@@ -8,47 +8,42 @@
 namespace tppo {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 diag_bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float diag_f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float diag_f32x4;
 
 constexpr int kDiagThreads = 512, kDiagGroups = 256;
-constexpr int kDiagFragsPerLane = 2 * (4 + 2);                 // two alternating operand sets
+constexpr int kDiagFragsPerLane = 8 + 4;                       // W-role and token-role fragments of one K step of 32
 constexpr int kDiagOperandElems = 64 * kDiagFragsPerLane * 8;  // bf16 values the caller provides
 
 __global__ __launch_bounds__(kDiagThreads, 2) void diag_mfma_rate_kernel(const uint16_t* __restrict__ operands,
                                                                         float* __restrict__ out, int iters) {
     const int lane = threadIdx.x & 63;
-    diag_bf16x8 fa[2][4], fb[2][2];
+    diag_bf16x8 fa[8], fb[4];
     const diag_bf16x8* src = reinterpret_cast<const diag_bf16x8*>(operands) + lane * kDiagFragsPerLane;
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
+    for (int i = 0; i < 8; ++i) fa[i] = src[i];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fa[s][i] = src[s * 6 + i];
+    for (int i = 0; i < 4; ++i) fb[i] = src[8 + i];
+    diag_f32x4 acc[8][4];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) fb[s][i] = src[s * 6 + 4 + i];
-    }
-    diag_f32x16 acc[4][2];
+    for (int vb = 0; vb < 8; ++vb)
 #pragma unroll
-    for (int vb = 0; vb < 4; ++vb)
+        for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
+            for (int e = 0; e < 4; ++e) acc[vb][tb][e] = 0.f;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
+        for (int vb = 0; vb < 8; ++vb)
 #pragma unroll
-            for (int vb = 0; vb < 4; ++vb)
-#pragma unroll
-                for (int tb = 0; tb < 2; ++tb)
-                    acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s][vb], fb[s][tb], acc[vb][tb], 0, 0, 0);
+            for (int tb = 0; tb < 4; ++tb)
+                acc[vb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[vb], fb[tb], acc[vb][tb], 0, 0, 0);
     }
     float sum = 0.f;
 #pragma unroll
-    for (int vb = 0; vb < 4; ++vb)
+    for (int vb = 0; vb < 8; ++vb)
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
+        for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) sum += acc[vb][tb][e];
+            for (int e = 0; e < 4; ++e) sum += acc[vb][tb][e];
     out[blockIdx.x * kDiagThreads + threadIdx.x] = sum;
 }
 
@@ -115,6 +110,6 @@ extern "C" int tppo_diag_mfma_rate(const void* operands, float* out, int64_t ite
     if (!is_aligned(operands, 16)) return TPPO_ERR_PARAM;
     hipLaunchKernelGGL(diag_mfma_rate_kernel, dim3(kDiagGroups), dim3(kDiagThreads), 0,
                        static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(operands), out, (int)iters);
-    if (flop) *flop = (double)kDiagGroups * (kDiagThreads / 64) * (double)iters * 16.0 * 32768.0;
+    if (flop) *flop = (double)kDiagGroups * (kDiagThreads / 64) * (double)iters * 32.0 * 16384.0;
     return launch_result();
 }

@@ -3,16 +3,16 @@
 // (the quantity inside the ratio of Eq. (ppoloss)); logits never reach memory.
 //
 // bf16 path (matrix cores).  The logits of a 256-token x 256-vocabulary tile
-// are accumulated with v_mfma_f32_32x32x16_bf16.  The MFMA "row" operand is the
-// W tile and the "column" operand the gathered hidden rows, so a lane's 16
-// accumulators of one 32x32 block all belong to ONE token (column lane%32) and
-// 16 different vocabulary entries: the running maximum, the running sum of
-// exponentials and the target logit of a token live in that lane's registers
-// across all vocabulary tiles of the workgroup, with no cross-lane traffic
-// until the very end.  The work is (token tiles) x (vocabulary splits), handed
-// to a persistent grid (head_tile.h); each pair sweeps its share of vocabulary
-// tiles and writes one (max, sumexp, target logit) triple per token; a small
-// kernel merges the splits into logp and lse.
+// are accumulated with v_mfma_f32_16x16x32_bf16 (or 32x32x16, see head_tile.h).
+// The MFMA "row" operand is the W tile and the "column" operand the gathered
+// hidden rows, so the accumulators a lane holds for one block all belong to ONE
+// token (column lane % 16) and to different vocabulary entries: the running
+// maximum, the running sum of exponentials and the target logit of a token
+// live in that lane's registers across all vocabulary tiles of the sweep, with
+// no cross-lane traffic until the very end.  The work is (token tiles) x
+// (vocabulary splits), handed to a persistent grid (head_tile.h); each pair
+// sweeps its share of vocabulary tiles and writes one (max, sumexp, target
+// logit) triple per token; a small kernel merges the splits into logp and lse.
 //
 // Both operands are K-contiguous in memory ([V,H] and [rows,H]), which is the
 // layout the MFMA wants for both, so tiles are staged into LDS as 16-byte
@@ -106,27 +106,26 @@ struct LaneSoftmax {
             run_max[tb] = kNegBig;
             run_sum[tb] = 0.f;
             tgt_logit[tb] = 0.f;
-            const int64_t t = tok0 + wt * C::kWaveT + tb * 32 + (lane & 31);
+            const int64_t t = tok0 + wt * C::kWaveT + tb * C::kMI + (lane % C::kMI);
             tgt[tb] = t < m_eff ? p.sel_targets[t] : -1;
         }
     }
 
     // acc holds logits: lane owns column lane%32 of block tb; entry e of block vb
     // is vocabulary id v_wave + vb*32 + (e/4)*8 + (lane/32)*4 + e%4.  Clears acc.
-    __device__ __forceinline__ void fold(f32x16 (&acc)[C::kVB][C::kTB], const HeadParams& p, int64_t, int64_t,
+    __device__ __forceinline__ void fold(typename C::Acc (&acc)[C::kVB][C::kTB], const HeadParams& p, int64_t, int64_t,
                                          int vt, int wv, int, int lane) {
-        constexpr int kVB = C::kVB, kTB = C::kTB;
-        const int frag_half = lane >> 5, V = p.V;
+        constexpr int kVB = C::kVB, kTB = C::kTB, kE = C::kAccElems;
+        const int grp = lane / C::kMI, V = p.V;
         const int v_wave = vt * C::kTileV + wv * C::kWaveV;
-        const int v_lane = v_wave + frag_half * 4;
         if (vt * C::kTileV + C::kTileV > V) {                       // ragged last tile: mask ids >= V
 #pragma unroll
             for (int vb = 0; vb < kVB; ++vb)
 #pragma unroll
                 for (int tb = 0; tb < kTB; ++tb)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        if (v_lane + vb * 32 + (e >> 2) * 8 + (e & 3) >= V) acc[vb][tb][e] = -INFINITY;
+                    for (int e = 0; e < kE; ++e)
+                        if (v_wave + C::row_in_wave(vb, e, grp) >= V) acc[vb][tb][e] = -INFINITY;
         }
 #pragma unroll
         for (int tb = 0; tb < kTB; ++tb) {
@@ -134,7 +133,7 @@ struct LaneSoftmax {
 #pragma unroll
             for (int vb = 0; vb < kVB; ++vb)
 #pragma unroll
-                for (int e = 0; e < 16; e += 2) {
+                for (int e = 0; e < kE; e += 2) {
                     mx0 = fmaxf(mx0, acc[vb][tb][e]);
                     mx1 = fmaxf(mx1, acc[vb][tb][e + 1]);
                 }
@@ -143,7 +142,7 @@ struct LaneSoftmax {
 #pragma unroll
             for (int vb = 0; vb < kVB; ++vb)
 #pragma unroll
-                for (int e = 0; e < 16; e += 4) {
+                for (int e = 0; e < kE; e += 4) {
                     s0 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e], kLog2e, -new_max));
                     s1 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e + 1], kLog2e, -new_max));
                     s2 += __builtin_amdgcn_exp2f(fmaf(acc[vb][tb][e + 2], kLog2e, -new_max));
@@ -152,25 +151,27 @@ struct LaneSoftmax {
             run_sum[tb] = fmaf(run_sum[tb], __builtin_amdgcn_exp2f(run_max[tb] - new_max), (s0 + s1) + (s2 + s3));
             run_max[tb] = new_max;
         }
-        // target logit: rare (a lane owns kVB*16 of V ids per tile), so only
-        // waves in which some lane hits take the register-select path
+        // target logit: rare (a lane owns kVB * kAccElems of V ids per tile), so only
+        // waves in which some lane hits take the register-select path.  Row r of
+        // a block belongs to lane group (r / 4) % kGroups, element (r / (4 kGroups)) * 4 + r % 4.
         bool hit = false;
 #pragma unroll
         for (int tb = 0; tb < kTB; ++tb) {
             const int d = tgt[tb] - v_wave;
-            hit |= d >= 0 && d < C::kWaveV && ((d >> 2) & 1) == frag_half;
+            hit |= d >= 0 && d < C::kWaveV && ((d >> 2) % C::kGroups) == grp;
         }
         if (__any(hit)) {
 #pragma unroll
             for (int tb = 0; tb < kTB; ++tb) {
                 const int d = tgt[tb] - v_wave;
-                if (d >= 0 && d < C::kWaveV && ((d >> 2) & 1) == frag_half) {
-                    const int vb_t = d >> 5, e_t = ((d >> 3) & 3) * 4 + (d & 3);
+                if (d >= 0 && d < C::kWaveV && ((d >> 2) % C::kGroups) == grp) {
+                    const int vb_t = d / C::kMI, r = d % C::kMI;
+                    const int e_t = (r / (4 * C::kGroups)) * 4 + (r & 3);
                     float z = 0.f;
 #pragma unroll
                     for (int vb = 0; vb < kVB; ++vb)
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) z = (vb == vb_t && e == e_t) ? acc[vb][tb][e] : z;
+                        for (int e = 0; e < kE; ++e) z = (vb == vb_t && e == e_t) ? acc[vb][tb][e] : z;
                     tgt_logit[tb] += z;
                 }
             }
@@ -180,28 +181,31 @@ struct LaneSoftmax {
 #pragma unroll
             for (int tb = 0; tb < kTB; ++tb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
+                for (int e = 0; e < kE; ++e) acc[vb][tb][e] = 0.f;
     }
 
-    // Merge the two lane halves (same token, different vocabulary rows), then
+    // Merge the lane groups (same token, different vocabulary rows), then
     // the kWavesV waves that share a token, and write the split's triple.
     // s_merge: LDS scratch [kWavesV][3][kTileT] floats, idle at this point.
     __device__ __forceinline__ void finish(const HeadParams& p, float* s_merge, int64_t tok0, int64_t m_eff,
                                                 int sp, int wv, int wt, int lane, int tid) {
         constexpr int kTileT = C::kTileT;
 #pragma unroll
-        for (int tb = 0; tb < C::kTB; ++tb) {
-            const float om = __shfl_xor(run_max[tb], 32), os = __shfl_xor(run_sum[tb], 32);
-            const float ot = __shfl_xor(tgt_logit[tb], 32);
-            const float nm = fmaxf(run_max[tb], om);
-            run_sum[tb] = run_sum[tb] * __builtin_amdgcn_exp2f(run_max[tb] - nm) + os * __builtin_amdgcn_exp2f(om - nm);
-            run_max[tb] = nm;
-            tgt_logit[tb] += ot;
-        }
-        if (lane < 32) {
+        for (int off = C::kMI; off < 64; off <<= 1) {            // butterfly over the 64 / kMI lane groups
 #pragma unroll
             for (int tb = 0; tb < C::kTB; ++tb) {
-                const int col = wt * C::kWaveT + tb * 32 + lane;
+                const float om = __shfl_xor(run_max[tb], off), os = __shfl_xor(run_sum[tb], off);
+                const float ot = __shfl_xor(tgt_logit[tb], off);
+                const float nm = fmaxf(run_max[tb], om);
+                run_sum[tb] = run_sum[tb] * __builtin_amdgcn_exp2f(run_max[tb] - nm) + os * __builtin_amdgcn_exp2f(om - nm);
+                run_max[tb] = nm;
+                tgt_logit[tb] += ot;
+            }
+        }
+        if (lane < C::kMI) {
+#pragma unroll
+            for (int tb = 0; tb < C::kTB; ++tb) {
+                const int col = wt * C::kWaveT + tb * C::kMI + lane;
                 s_merge[(wv * 3 + 0) * kTileT + col] = run_max[tb];
                 s_merge[(wv * 3 + 1) * kTileT + col] = run_sum[tb];
                 s_merge[(wv * 3 + 2) * kTileT + col] = tgt_logit[tb];
@@ -259,14 +263,15 @@ __global__ __launch_bounds__(256) void head_combine_kernel(
 }
 
 // Kernel variants (TPPO_HEAD_VARIANT selects one; 0 is the default).
-using Cfg0 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 16>;
-using Cfg1 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 0>;
+using Cfg0 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 32, 16, 8>;   // v_mfma_f32_16x16x32_bf16, one W block per MFMA step
+using Cfg1 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 16, 32>;      // v_mfma_f32_32x32x16_bf16
+using Cfg2 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 0, 32>;       // the same, transfers issued back to back
 
 template <class C>
 constexpr HeadVariant make_variant() {
     return {head_mfma_kernel<C, LaneSoftmax>, C::kTileV, C::kTileT, C::kThreads, C::kLdsBytes, C::kWgsPerCu};
 }
-static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>()};
+static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>(), make_variant<Cfg2>()};
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 static const HeadVariant& pick_variant() {

@@ -21,8 +21,8 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float x) {
 }
 
 // Epilogue 1: a finished 256 (vocabulary) x 256 (token) tile of logits becomes
-// dz; every lane owns one token column per 32-wide block and writes its 4
-// consecutive vocabulary entries as one 8-byte store into row t of out[.., ld_out].
+// dz; every lane owns one token column per block and writes each group of 4
+// consecutive vocabulary entries it holds as one 8-byte store into row t of out[.., ld_out].
 template <class C>
 struct DzEpilogue {
     float lse2[C::kTB], g[C::kTB];
@@ -31,7 +31,7 @@ struct DzEpilogue {
     __device__ __forceinline__ void init(const HeadParams& p, int64_t tok0, int64_t m_eff, int wt, int lane) {
 #pragma unroll
         for (int tb = 0; tb < C::kTB; ++tb) {
-            const int64_t t = tok0 + wt * C::kWaveT + tb * 32 + (lane & 31);
+            const int64_t t = tok0 + wt * C::kWaveT + tb * C::kMI + (lane % C::kMI);
             lse2[tb] = 0.f;
             g[tb] = 0.f;
             tgt[tb] = -1;
@@ -44,20 +44,20 @@ struct DzEpilogue {
         }
     }
 
-    __device__ __forceinline__ void fold(f32x16 (&acc)[C::kVB][C::kTB], const HeadParams& p, int64_t tok0,
+    __device__ __forceinline__ void fold(typename C::Acc (&acc)[C::kVB][C::kTB], const HeadParams& p, int64_t tok0,
                                          int64_t m_eff, int vt, int wv, int wt, int lane) {
-        const int v_lane = vt * C::kTileV + wv * C::kWaveV + (lane >> 5) * 4;
+        const int v_lane = vt * C::kTileV + wv * C::kWaveV + (lane / C::kMI) * 4;
         uint16_t* out = static_cast<uint16_t*>(p.out);
 #pragma unroll
         for (int tb = 0; tb < C::kTB; ++tb) {
-            const int64_t t = tok0 + wt * C::kWaveT + tb * 32 + (lane & 31);
+            const int64_t t = tok0 + wt * C::kWaveT + tb * C::kMI + (lane % C::kMI);
             if (t < m_eff) {
                 uint16_t* row = out + t * p.ld_out;
 #pragma unroll
                 for (int vb = 0; vb < C::kVB; ++vb)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int v0 = v_lane + vb * 32 + q * 8;
+                    for (int q = 0; q < C::kQuads; ++q) {
+                        const int v0 = v_lane + vb * C::kMI + q * (4 * C::kGroups);
                         if (v0 < p.out_cols) {
                             uint32_t h[4];
 #pragma unroll
@@ -81,7 +81,7 @@ struct DzEpilogue {
 #pragma unroll
             for (int tb = 0; tb < C::kTB; ++tb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
+                for (int e = 0; e < C::kAccElems; ++e) acc[vb][tb][e] = 0.f;
     }
 
     __device__ __forceinline__ void finish(const HeadParams&, float*, int64_t, int64_t, int, int, int, int, int) {}
@@ -93,20 +93,20 @@ template <class C>
 struct StoreEpilogue {
     __device__ __forceinline__ void init(const HeadParams&, int64_t, int64_t, int, int) {}
 
-    __device__ __forceinline__ void fold(f32x16 (&acc)[C::kVB][C::kTB], const HeadParams& p, int64_t tok0,
+    __device__ __forceinline__ void fold(typename C::Acc (&acc)[C::kVB][C::kTB], const HeadParams& p, int64_t tok0,
                                          int64_t m_eff, int vt, int wv, int wt, int lane) {
-        const int v_lane = vt * C::kTileV + wv * C::kWaveV + (lane >> 5) * 4;
+        const int v_lane = vt * C::kTileV + wv * C::kWaveV + (lane / C::kMI) * 4;
         float* out = static_cast<float*>(p.out);
 #pragma unroll
         for (int tb = 0; tb < C::kTB; ++tb) {
-            const int64_t t = tok0 + wt * C::kWaveT + tb * 32 + (lane & 31);
+            const int64_t t = tok0 + wt * C::kWaveT + tb * C::kMI + (lane % C::kMI);
             if (t < m_eff) {
                 float* row = out + t * p.ld_out;
 #pragma unroll
                 for (int vb = 0; vb < C::kVB; ++vb)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int v0 = v_lane + vb * 32 + q * 8;
+                    for (int q = 0; q < C::kQuads; ++q) {
+                        const int v0 = v_lane + vb * C::kMI + q * (4 * C::kGroups);
                         if (v0 < p.out_cols) {
                             float4 val = make_float4(acc[vb][tb][q * 4], acc[vb][tb][q * 4 + 1],
                                                      acc[vb][tb][q * 4 + 2], acc[vb][tb][q * 4 + 3]);
@@ -125,7 +125,7 @@ struct StoreEpilogue {
 #pragma unroll
             for (int tb = 0; tb < C::kTB; ++tb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
+                for (int e = 0; e < C::kAccElems; ++e) acc[vb][tb][e] = 0.f;
     }
 
     __device__ __forceinline__ void finish(const HeadParams&, float*, int64_t, int64_t, int, int, int, int, int) {}
@@ -181,7 +181,7 @@ static int launch_transpose(const uint16_t* src, int64_t rows, int64_t cols, int
     return launch_result();
 }
 
-using BwdCfg = HeadCfg<256, 256, 2, 4, 64, 2, 1, 16>;
+using BwdCfg = HeadCfg<256, 256, 2, 4, 64, 2, 1, 32, 16, 8>;
 static const HeadVariant kDzVariant = {head_mfma_kernel<BwdCfg, DzEpilogue>, BwdCfg::kTileV, BwdCfg::kTileT,
                                        BwdCfg::kThreads, BwdCfg::kLdsBytes, BwdCfg::kWgsPerCu};
 static const HeadVariant kGemmVariant = {head_mfma_kernel<BwdCfg, StoreEpilogue>, BwdCfg::kTileV, BwdCfg::kTileT,

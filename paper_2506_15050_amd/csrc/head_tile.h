@@ -49,8 +49,20 @@ struct HeadParams {
 // cycle, i.e. 16 lanes of a ds_read_b128; those 16 lanes read the same chunk
 // of 16 consecutive rows, and the swizzle spreads them over all 16 slots of
 // the 256-byte bank window (measured: SQ_LDS_BANK_CONFLICT = 0).
-template <int TV, int TT, int WV, int WT, int BK, int ST, int WGS_PER_CU, int SPREAD = 0>
+//
+// MI selects the MFMA instruction: 32 = v_mfma_f32_32x32x16_bf16, 16 =
+// v_mfma_f32_16x16x32_bf16.  Same flops per cycle and the same LDS bytes per
+// flop, but at the chip's power limit the 16x16x32 form sustains more (MFMA
+// loop on LDS-fed fragments: 1.65 vs 1.55 PFLOP/s; on register-resident ones 2.10
+// vs 1.83).  In both forms lane l of a wave holds, for an MI x MI block,
+// column l % MI (a token) and the rows (e/4)*(4G) + (l/MI)*4 + e%4 for
+// e < MI*MI/64, G = 64/MI lane groups (vocabulary entries), and reads its
+// operand fragments as 16 bytes: row l % MI, K chunk l / MI of the MFMA's K range.
+template <int TV, int TT, int WV, int WT, int BK, int ST, int WGS_PER_CU, int SPREAD = 0, int MI = 32, int SUBDIV = 2>
 struct HeadCfg {
+    static_assert(MI == 32 || MI == 16, "MFMA block shape");
+    static constexpr int kMI = MI, kGroups = 64 / MI, kAccElems = MI * MI / 64, kQuads = kAccElems / 4;
+    typedef float Acc __attribute__((__vector_size__(kAccElems * sizeof(float))));
     static constexpr int kTileV = TV, kTileT = TT, kWavesV = WV, kWavesT = WT, kBK = BK, kStages = ST;
     static constexpr int kWgsPerCu = WGS_PER_CU;
     // 0: a wave issues the transfers of a stage back to back; n > 0: one by one
@@ -58,7 +70,11 @@ struct HeadCfg {
     static constexpr int kSpread = SPREAD;
     static constexpr int kWaves = WV * WT, kThreads = kWaves * 64;
     static constexpr int kWaveV = TV / WV, kWaveT = TT / WT;              // wave tile
-    static constexpr int kVB = kWaveV / 32, kTB = kWaveT / 32;            // 32x32 blocks per wave
+    static constexpr int kVB = kWaveV / MI, kTB = kWaveT / MI;            // MI x MI blocks per wave
+    // an MFMA step: the 32x32x16 form covers all W blocks over 16 K; the 16x16x32 form 1/kSubdiv of them over 32 K
+    static constexpr int kSubdiv = MI == 32 ? 1 : SUBDIV;
+    static constexpr int kSubVB = kVB / kSubdiv;
+    static constexpr int kMfmaPerStep = kSubVB * kTB;
     static constexpr int kRowBytes = BK * 2, kChunks = BK / 8;
     static constexpr int kRows = TV + TT;
     static constexpr int kStageBytes = kRows * kRowBytes;
@@ -66,18 +82,23 @@ struct HeadCfg {
     static constexpr int kRowsPerDma = 1024 / kRowBytes;                  // one wave-wide 16 B/lane transfer
     static constexpr int kDmaPerStage = kRows / kRowsPerDma;
     static constexpr int kDmaPerWave = kDmaPerStage / kWaves;
-    static constexpr int kKSteps = BK / 16;
+    static constexpr int kKSteps = MI == 32 ? BK / 16 : (BK / 32) * kSubdiv;
     static_assert(kDmaPerWave * kWaves == kDmaPerStage, "transfers must divide evenly over the waves");
     static_assert(TV % kRowsPerDma == 0, "a transfer may not straddle W and token rows");
     static_assert(kKSteps % 2 == 0, "fragment double buffering assumes an even number of K steps");
     static_assert(WV * 3 * TT * 4 <= kLdsBytes, "merge buffer must fit in the idle stages");
-    static_assert(SPREAD == 0 || (ST == 2 && SPREAD <= kKSteps * kVB * kTB),
+    static_assert(MI == 32 || (kVB % kSubdiv == 0 && BK % 32 == 0), "16x16x32: W blocks in equal parts, K in steps of 32");
+    static_assert(SPREAD == 0 || (ST == 2 && SPREAD <= kKSteps * kMfmaPerStep),
                   "spread issue: two stages, at most one stage's worth of MFMAs");
     __device__ static __forceinline__ int swz(int r) {
         return BK == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3);
     }
     __device__ static __forceinline__ int chunk_off(int r, int c) {
         return r * kRowBytes + ((c ^ swz(r)) << 4);
+    }
+    // row (inside the wave tile's W rows) of accumulator element e of block vb, for lane group g = lane / MI
+    __device__ static __forceinline__ int row_in_wave(int vb, int e, int g) {
+        return vb * MI + (e >> 2) * (4 * kGroups) + g * 4 + (e & 3);
     }
 };
 
@@ -141,7 +162,7 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wv = wave / C::kWavesT, wt = wave % C::kWavesT;
-    const int frag_row = lane & 31, frag_half = lane >> 5;
+    const int frag_row = lane % C::kMI, frag_grp = lane / C::kMI;
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
     for (int unit = xcd; unit < p.n_units; unit += 8) {
@@ -216,47 +237,71 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
     Epi<C> epi;
     epi.init(p, tok0, m_eff, wt, lane);
 
-    f32x16 acc[kVB][kTB];
+    typename C::Acc acc[kVB][kTB];
 #pragma unroll
     for (int vb = 0; vb < kVB; ++vb)
 #pragma unroll
         for (int tb = 0; tb < kTB; ++tb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[vb][tb][e] = 0.f;
+            for (int e = 0; e < C::kAccElems; ++e) acc[vb][tb][e] = 0.f;
 
-    bf16x8 fa[2][kVB], fb[2][kTB];
-    auto load_frags = [&](int stage, int ks, int buf) {
+    // Fragments of MFMA step `step` of a stage (kKSteps steps per stage), double buffered.
+    //   32x32x16: step = K step of 16; all kVB W fragments and the kTB token fragments, K chunks 2*step + group.
+    //   16x16x32: step = (K step of 32) * kSubdiv + part; the W fragments of that part of the blocks, K chunks
+    //             4*(step/kSubdiv) + group; the token fragments once per K step of 32 (with part 0).
+    constexpr int kSubVB = C::kSubVB;
+    bf16x8 fa[2][kSubVB], fb[2][kTB];
+    auto load_frags = [&](int stage, int step) {
         const unsigned char* st = smem + stage * C::kStageBytes;
         const unsigned char* a_base = st + (wv * kWaveV) * C::kRowBytes;
         const unsigned char* b_base = st + (kTileV + wt * kWaveT) * C::kRowBytes;
-        const int c = ks * 2 + frag_half;
+        if (C::kMI == 32) {
+            const int c = step * 2 + frag_grp;
 #pragma unroll
-        for (int vb = 0; vb < kVB; ++vb)
-            fa[buf][vb] = *reinterpret_cast<const bf16x8*>(a_base + C::chunk_off(vb * 32 + frag_row, c));
-#pragma unroll
-        for (int tb = 0; tb < kTB; ++tb)
-            fb[buf][tb] = *reinterpret_cast<const bf16x8*>(b_base + C::chunk_off(tb * 32 + frag_row, c));
-    };
-    auto mfma_step = [&](int buf) {
-#pragma unroll
-        for (int vb = 0; vb < kVB; ++vb)
+            for (int vb = 0; vb < kSubVB; ++vb)
+                fa[step & 1][vb] = *reinterpret_cast<const bf16x8*>(a_base + C::chunk_off(vb * 32 + frag_row, c));
 #pragma unroll
             for (int tb = 0; tb < kTB; ++tb)
-                acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][vb], fb[buf][tb], acc[vb][tb], 0, 0, 0);
+                fb[step & 1][tb] = *reinterpret_cast<const bf16x8*>(b_base + C::chunk_off(tb * 32 + frag_row, c));
+        } else {
+            const int k32 = step / C::kSubdiv, part = step % C::kSubdiv, c = k32 * 4 + frag_grp;
+#pragma unroll
+            for (int j = 0; j < kSubVB; ++j)
+                fa[step & 1][j] = *reinterpret_cast<const bf16x8*>(a_base + C::chunk_off((part * kSubVB + j) * 16 + frag_row, c));
+            if (part == 0) {
+#pragma unroll
+                for (int tb = 0; tb < kTB; ++tb)
+                    fb[k32 & 1][tb] = *reinterpret_cast<const bf16x8*>(b_base + C::chunk_off(tb * 16 + frag_row, c));
+            }
+        }
+    };
+    auto mfma_one = [&](int step, int j, int tb) {
+        if constexpr (C::kMI == 32) {
+            acc[j][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[step & 1][j], fb[step & 1][tb], acc[j][tb], 0, 0, 0);
+        } else {
+            const int vb = (step % C::kSubdiv) * kSubVB + j;
+            acc[vb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[step & 1][j], fb[(step / C::kSubdiv) & 1][tb], acc[vb][tb], 0, 0, 0);
+        }
+    };
+    auto mfma_step = [&](int step) {
+#pragma unroll
+        for (int j = 0; j < kSubVB; ++j)
+#pragma unroll
+            for (int tb = 0; tb < kTB; ++tb) mfma_one(step, j, tb);
     };
     // The same K step with this wave's transfers first .. first + n - 1 of the
     // stage being refilled issued between the MFMAs (`on` is workgroup-uniform).
     // Transfer j of the stage being refilled follows MFMA number
     // floor(j * kSpread / kDmaPerWave), counted from the barrier that freed it.
-    constexpr int kMfmaPerStep = kVB * kTB;
-    constexpr int kSpreadSteps = (C::kSpread + kMfmaPerStep - 1) / kMfmaPerStep;   // K steps the issue touches
-    auto mfma_step_issuing = [&](int buf, int part, bool on) {
+    constexpr int kMfmaPerStep = C::kMfmaPerStep;
+    constexpr int kSpreadSteps = (C::kSpread + kMfmaPerStep - 1) / kMfmaPerStep;   // MFMA steps the issue touches
+    auto mfma_step_issuing = [&](int step, int part, bool on) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int vb = 0; vb < kVB; ++vb)
+        for (int vb = 0; vb < kSubVB; ++vb)
 #pragma unroll
             for (int tb = 0; tb < kTB; ++tb) {
-                acc[vb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][vb], fb[buf][tb], acc[vb][tb], 0, 0, 0);
+                mfma_one(step, vb, tb);
                 const int g = part * kMfmaPerStep + vb * kTB + tb;
                 if (on) {
 #pragma unroll
@@ -277,19 +322,19 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
     if (kStages - 1 < total_iters) issue();
-    load_frags(0, 0, 0);
+    load_frags(0, 0);
 
     int kt = 0, vt = vt_begin, stage = 0;
     bool refill = false;                // spread issue: transfers of the stage freed at the last barrier are pending
     for (int it = 0; it < total_iters; ++it) {
 #pragma unroll
         for (int ks = 0; ks + 1 < kKSteps; ++ks) {
-            load_frags(stage, ks + 1, (ks + 1) & 1);
+            load_frags(stage, ks + 1);
             if (C::kSpread && ks + 1 < kSpreadSteps) {
-                mfma_step_issuing(ks & 1, ks + 1, refill);
+                mfma_step_issuing(ks, ks + 1, refill);
                 if (ks + 2 == kSpreadSteps && refill) issue_advance();
             } else {
-                mfma_step(ks & 1);
+                mfma_step(ks);
             }
         }
         // The stage's last fragments are in registers.  Hand the stage back,
@@ -307,14 +352,14 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
                 if (C::kSpread) refill = true;
                 else issue();
             }
-            load_frags(next_stage, 0, 0);
+            load_frags(next_stage, 0);
         }
         if (C::kSpread) {
-            mfma_step_issuing((kKSteps - 1) & 1, 0, refill);
+            mfma_step_issuing(kKSteps - 1, 0, refill);
             if (kSpreadSteps == 1 && refill) issue_advance();
         } else {
             __builtin_amdgcn_sched_barrier(0);
-            mfma_step((kKSteps - 1) & 1);
+            mfma_step(kKSteps - 1);
         }
         stage = next_stage;
         if (++kt == k_tiles) {          // a vocabulary tile is complete
