@@ -55,17 +55,17 @@ __host__ __device__ __forceinline__ EgaeWs egae_ws(void* ws, int64_t cap) {
     return w;
 }
 
-// workgroup 0 builds the chunk list; the others clear the published words
+// the first `parts` workgroups build the chunk list; the others clear the published words
 __global__ __launch_bounds__(kBuildThreads) void egae_init_kernel(const int32_t* __restrict__ resp_off,
-                                                                  int B, int n_resp, int cap, void* ws_raw,
-                                                                  int32_t* status) {
+                                                                  int B, int n_resp, int cap, int parts,
+                                                                  void* ws_raw, int32_t* status) {
     EgaeWs ws = egae_ws(ws_raw, cap);
-    if (blockIdx.x == 0) {
-        build_chunks(resp_off, B, n_resp, ws.chunks, cap, ws.n_chunks, status);
+    if ((int)blockIdx.x < parts) {
+        build_chunks(resp_off, B, n_resp, ws.chunks, cap, ws.n_chunks, status, blockIdx.x, parts);
     } else {
         const int64_t words = (int64_t)cap * 4;
-        for (int64_t i = (int64_t)(blockIdx.x - 1) * kBuildThreads + threadIdx.x; i < words;
-             i += (int64_t)(gridDim.x - 1) * kBuildThreads)
+        for (int64_t i = (int64_t)(blockIdx.x - parts) * kBuildThreads + threadIdx.x; i < words;
+             i += (int64_t)(gridDim.x - parts) * kBuildThreads)
             ws.agg[i] = 0ull;
     }
 }
@@ -447,8 +447,9 @@ static int egae_launch(const float* rewards, bool terminal_mode, const float* va
     if (cap64 > INT32_MAX / 4) return TPPO_ERR_SIZE;
     const int cap = (int)cap64;
     const int clear_groups = (int)((cap64 * 4 + kBuildThreads * 8 - 1) / (kBuildThreads * 8));
-    hipLaunchKernelGGL(egae_init_kernel, dim3(1 + (clear_groups < 1 ? 1 : clear_groups)), dim3(kBuildThreads),
-                       0, s, resp_off, (int)B, (int)n_resp, cap, workspace, status);
+    const int parts = build_parts(B);
+    hipLaunchKernelGGL(egae_init_kernel, dim3(parts + (clear_groups < 1 ? 1 : clear_groups)), dim3(kBuildThreads),
+                       0, s, resp_off, (int)B, (int)n_resp, cap, parts, workspace, status);
     if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
     const double g = (double)gamma, c = (double)gamma * (double)lambda;
     // weight of a whole chunk in the carry: (gamma*lambda)^2048 resp. gamma^2048

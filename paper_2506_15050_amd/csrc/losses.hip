@@ -19,6 +19,7 @@ constexpr int kLossMaxGroups = 2048;
 struct LossWs {
     Chunk* chunks;        // [cap]
     double* partials;     // [kLossMaxGroups][2]
+    long long* counts;    // [2]: tokens in the policy set, in the value set
     int32_t* n_chunks;    // [1]
 };
 
@@ -33,7 +34,8 @@ __host__ __device__ __forceinline__ LossWs loss_ws(void* ws, int64_t cap) {
     p += ((size_t)cap * sizeof(Chunk) + 255) / 256 * 256;
     w.partials = reinterpret_cast<double*>(p);
     p += (size_t)kLossMaxGroups * 2 * sizeof(double);
-    w.n_chunks = reinterpret_cast<int32_t*>(p);
+    w.counts = reinterpret_cast<long long*>(p);
+    w.n_chunks = reinterpret_cast<int32_t*>(p + 2 * sizeof(long long));
     return w;
 }
 
@@ -44,11 +46,52 @@ struct LossParams {
     float ratio_lo, ratio_hi, xi_low, xi_high;
 };
 
-__global__ __launch_bounds__(kBuildThreads) void loss_init_kernel(const int32_t* __restrict__ resp_off, int B,
-                                                                  int n_resp, int cap, void* ws_raw,
+// Sizes of the two token sets (Sec. 3.2), from the metadata alone; one workgroup, result valid in thread 0.
+__device__ __forceinline__ void count_sets(const int32_t* __restrict__ resp_off, const int32_t* __restrict__ keep_len,
+                                           const int32_t* __restrict__ done, int B, long long& n_pol, long long& n_val) {
+    __shared__ long long s_cnt[2][kBuildThreads / kWave];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, waves = blockDim.x >> 6;
+    long long np = 0, nv = 0;
+    for (int i = tid; i < B; i += blockDim.x) {
+        const int win = max(resp_off[i + 1] - resp_off[i], 0);
+        np += min(max(keep_len[i], 0), win);
+        nv += done[i] != 0 ? win : 0;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        np += __shfl_down(np, off);
+        nv += __shfl_down(nv, off);
+    }
+    if (lane == 0) {
+        s_cnt[0][wave] = np;
+        s_cnt[1][wave] = nv;
+    }
+    __syncthreads();
+    n_pol = n_val = 0;
+    if (tid == 0)
+        for (int w = 0; w < waves; ++w) {
+            n_pol += s_cnt[0][w];
+            n_val += s_cnt[1][w];
+        }
+}
+
+// workgroups 0 .. parts-1 build the chunk list, workgroup `parts` counts the two sets meanwhile
+__global__ __launch_bounds__(kBuildThreads) void loss_init_kernel(const int32_t* __restrict__ resp_off,
+                                                                  const int32_t* __restrict__ keep_len,
+                                                                  const int32_t* __restrict__ done, int B,
+                                                                  int n_resp, int cap, int parts, void* ws_raw,
                                                                   int32_t* status) {
     LossWs ws = loss_ws(ws_raw, cap);
-    build_chunks(resp_off, B, n_resp, ws.chunks, cap, ws.n_chunks, status);
+    if ((int)blockIdx.x < parts) {
+        build_chunks(resp_off, B, n_resp, ws.chunks, cap, ws.n_chunks, status, blockIdx.x, parts);
+    } else {
+        long long np, nv;
+        count_sets(resp_off, keep_len, done, B, np, nv);
+        if (threadIdx.x == 0) {
+            ws.counts[0] = np;
+            ws.counts[1] = nv;
+        }
+    }
 }
 
 typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte access, 4-byte aligned
@@ -196,13 +239,12 @@ __global__ __launch_bounds__(kChunkThreads) void loss_partial_kernel(LossParams 
     }
 }
 
+// `counts`: the set sizes the list-building kernel left (NULL: that kernel did not run, both sets are empty)
 __global__ __launch_bounds__(kChunkThreads) void loss_final_kernel(
-    const double* __restrict__ partials, int groups, const int32_t* __restrict__ resp_off,
-    const int32_t* __restrict__ keep_len, const int32_t* __restrict__ done, int B, int has_pol,
+    const double* __restrict__ partials, int groups, const long long* __restrict__ counts, int has_pol,
     int has_val, tppo_loss_out* __restrict__ out) {
     __shared__ double s_red[kChunkThreads / kWave];
-    __shared__ long long s_cnt[2][kChunkThreads / kWave];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     double ps = 0.0, vs = 0.0;
     for (int g = tid; g < groups; g += kChunkThreads) {
         ps += partials[2 * g];
@@ -210,30 +252,8 @@ __global__ __launch_bounds__(kChunkThreads) void loss_final_kernel(
     }
     ps = block_sum(ps, s_red);
     vs = block_sum(vs, s_red);
-    long long np = 0, nv = 0;
-    for (int i = tid; i < B; i += kChunkThreads) {
-        const int win = max(resp_off[i + 1] - resp_off[i], 0);
-        np += min(max(keep_len[i], 0), win);
-        nv += done[i] != 0 ? win : 0;
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        np += __shfl_down(np, off);
-        nv += __shfl_down(nv, off);
-    }
-    if (lane == 0) {
-        s_cnt[0][wave] = np;
-        s_cnt[1][wave] = nv;
-    }
-    __syncthreads();
     if (tid == 0) {
-        np = nv = 0;
-        for (int w = 0; w < kChunkThreads / kWave; ++w) {
-            np += s_cnt[0][w];
-            nv += s_cnt[1][w];
-        }
-        if (!has_pol) np = 0;
-        if (!has_val) nv = 0;
+        const long long np = (counts && has_pol) ? counts[0] : 0, nv = (counts && has_val) ? counts[1] : 0;
         const double policy_sum = -ps, value_sum = 0.5 * vs;
         out->policy_sum = (float)policy_sum;
         out->value_sum = (float)value_sum;
@@ -292,38 +312,21 @@ struct GradParams {
     long long policy_denominator, value_denominator;     // <= 0: the call's own token counts
 };
 
+// workgroups 0 .. parts-1 build the chunk list, workgroup `parts` counts the two sets meanwhile
 __global__ __launch_bounds__(kBuildThreads) void loss_grad_init_kernel(
     const int32_t* __restrict__ resp_off, const int32_t* __restrict__ keep_len,
-    const int32_t* __restrict__ done, int B, int n_resp, int cap, int has_pol, int has_val, void* ws_raw,
-    int32_t* status) {
-    __shared__ long long s_cnt[2][kBuildThreads / kWave];
+    const int32_t* __restrict__ done, int B, int n_resp, int cap, int parts, int has_pol, int has_val,
+    void* ws_raw, int32_t* status) {
     GradWs ws = grad_ws(ws_raw, cap);
-    build_chunks(resp_off, B, n_resp, ws.chunks, cap, ws.n_chunks, status);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    long long np = 0, nv = 0;
-    for (int i = tid; i < B; i += kBuildThreads) {
-        const int win = max(resp_off[i + 1] - resp_off[i], 0);
-        np += min(max(keep_len[i], 0), win);
-        nv += done[i] != 0 ? win : 0;
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        np += __shfl_down(np, off);
-        nv += __shfl_down(nv, off);
-    }
-    if (lane == 0) {
-        s_cnt[0][wave] = np;
-        s_cnt[1][wave] = nv;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        np = nv = 0;
-        for (int w = 0; w < kBuildThreads / kWave; ++w) {
-            np += s_cnt[0][w];
-            nv += s_cnt[1][w];
+    if ((int)blockIdx.x < parts) {
+        build_chunks(resp_off, B, n_resp, ws.chunks, cap, ws.n_chunks, status, blockIdx.x, parts);
+    } else {
+        long long np, nv;
+        count_sets(resp_off, keep_len, done, B, np, nv);
+        if (threadIdx.x == 0) {
+            ws.counts[0] = has_pol ? np : 0;
+            ws.counts[1] = has_val ? nv : 0;
         }
-        ws.counts[0] = has_pol ? np : 0;
-        ws.counts[1] = has_val ? nv : 0;
     }
 }
 
@@ -541,8 +544,9 @@ extern "C" int tppo_ppo_losses(const float* logp_new, const float* logp_old, con
 
     int groups = 0;
     if (n_resp > 0 && (n_pol_ptr || n_val_ptr)) {
-        hipLaunchKernelGGL(loss_init_kernel, dim3(1), dim3(kBuildThreads), 0, s, resp_off, (int)B,
-                           (int)n_resp, cap, workspace, status);
+        const int parts = build_parts(B);
+        hipLaunchKernelGGL(loss_init_kernel, dim3(parts + 1), dim3(kBuildThreads), 0, s, resp_off, keep_len, done,
+                           (int)B, (int)n_resp, cap, parts, workspace, status);
         if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
         LossParams p;
         p.logp_new = logp_new; p.logp_old = logp_old; p.adv = adv;
@@ -558,7 +562,7 @@ extern "C" int tppo_ppo_losses(const float* logp_new, const float* logp_old, con
         if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
     }
     hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(kChunkThreads), 0, s, ws.partials, groups,
-                       resp_off, keep_len, done, (int)B, n_pol_ptr ? 1 : 0, n_val_ptr ? 1 : 0, out);
+                       groups > 0 ? ws.counts : nullptr, n_pol_ptr ? 1 : 0, n_val_ptr ? 1 : 0, out);
     return launch_result();
 }
 
@@ -598,8 +602,9 @@ extern "C" int tppo_ppo_losses_backward(const float* logp_new, const float* logp
     // the list-building kernel also counts the two sets; it runs for an empty batch too (B = 0: zero counts)
     int groups = 0;
     if (B > 0) {
-        hipLaunchKernelGGL(loss_grad_init_kernel, dim3(1), dim3(kBuildThreads), 0, s, resp_off, keep_len, done,
-                           (int)B, (int)n_resp, cap, n_pol_ptr ? 1 : 0, n_val_ptr ? 1 : 0, workspace, status);
+        const int parts = build_parts(B);
+        hipLaunchKernelGGL(loss_grad_init_kernel, dim3(parts + 1), dim3(kBuildThreads), 0, s, resp_off, keep_len, done,
+                           (int)B, (int)n_resp, cap, parts, n_pol_ptr ? 1 : 0, n_val_ptr ? 1 : 0, workspace, status);
         if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
         if (n_resp > 0 && (n_pol_ptr || n_val_ptr)) {
             GradParams gp;

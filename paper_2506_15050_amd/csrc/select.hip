@@ -36,20 +36,27 @@ __device__ __forceinline__ Quad lengths_of(const int32_t* __restrict__ cu_seqlen
     return {win, keep, fin ? win : 0, (keep + kChunkTokens - 1) / kChunkTokens};
 }
 
-// Thread t owns a contiguous block of sequences, so there is one workgroup-wide prefix sum whatever B is:
+// gridDim.x workgroups share the sequences (one up to a few thousand of them): workgroup g owns a contiguous
+// range and, inside it, thread t a contiguous block, so there is one workgroup-wide prefix sum whatever B is:
 // pass A adds up the block, the scan gives the block's starting offsets, pass B re-reads the (cache-resident)
-// metadata and writes the per-sequence outputs and chunk descriptors.
+// metadata and writes the per-sequence outputs and chunk descriptors.  Where its range starts a workgroup
+// finds out by adding up, by itself, the lengths of all sequences before the range.
 __global__ __launch_bounds__(kScanThreads) void select_scan_kernel(
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ ctx_len,
     const int32_t* __restrict__ done, int B, int n_tok, int tail_drop,
     int32_t* __restrict__ resp_off, int32_t* __restrict__ sel_off,
     int32_t* __restrict__ keep_len, int64_t* __restrict__ counts, Chunk* __restrict__ chunks,
     int chunk_cap, int32_t* __restrict__ n_chunks, int32_t* status) {
-    __shared__ Quad wave_tot[kScanThreads / kWave];
+    __shared__ Quad wave_tot[2][kScanThreads / kWave];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int per = (B + kScanThreads - 1) / kScanThreads;
-    const int i_begin = min(tid * per, B), i_end = min(i_begin + per, B);
-    Quad mine = {0, 0, 0, 0};
+    const int part = blockIdx.x, parts = gridDim.x;
+    const int range = (B + parts - 1) / parts;
+    const int p_begin = min(part * range, B), p_end = min(p_begin + range, B);
+    const int per = (p_end - p_begin + kScanThreads - 1) / kScanThreads;
+    const int i_begin = min(p_begin + tid * per, p_end), i_end = min(i_begin + per, p_end);
+    Quad mine = {0, 0, 0, 0}, ahead = {0, 0, 0, 0};
+    for (int i = tid; i < p_begin; i += kScanThreads)
+        ahead = add4(ahead, lengths_of(cu_seqlens, ctx_len, done, i, n_tok, tail_drop, nullptr));
     for (int i = i_begin; i < i_end; ++i) mine = add4(mine, lengths_of(cu_seqlens, ctx_len, done, i, n_tok, tail_drop, status));
     Quad inc = mine;
 #pragma unroll
@@ -57,16 +64,20 @@ __global__ __launch_bounds__(kScanThreads) void select_scan_kernel(
         Quad y = {__shfl_up(inc.win, off), __shfl_up(inc.keep, off), __shfl_up(inc.val, off),
                   __shfl_up(inc.chunks, off)};
         if (lane >= off) inc = add4(inc, y);
+        ahead = add4(ahead, {__shfl_xor(ahead.win, off), __shfl_xor(ahead.keep, off), __shfl_xor(ahead.val, off),
+                             __shfl_xor(ahead.chunks, off)});
     }
-    if (lane == kWave - 1) wave_tot[wave] = inc;
+    if (lane == kWave - 1) wave_tot[0][wave] = inc;
+    if (lane == 0) wave_tot[1][wave] = ahead;
     __syncthreads();
     Quad run = {inc.win - mine.win, inc.keep - mine.keep, inc.val - mine.val, inc.chunks - mine.chunks};
     Quad total = {0, 0, 0, 0};
     for (int w = 0; w < kScanThreads / kWave; ++w) {
-        if (w < wave) run = add4(run, wave_tot[w]);
-        total = add4(total, wave_tot[w]);
+        if (w < wave) run = add4(run, wave_tot[0][w]);
+        run = add4(run, wave_tot[1][w]);
+        total = add4(total, add4(wave_tot[0][w], wave_tot[1][w]));
     }
-    if (tid == 0) {
+    if (part == 0 && tid == 0) {
         resp_off[0] = 0;
         sel_off[0] = 0;
     }
@@ -87,7 +98,7 @@ __global__ __launch_bounds__(kScanThreads) void select_scan_kernel(
         resp_off[i + 1] = run.win;
         sel_off[i + 1] = run.keep;
     }
-    if (tid == 0) {
+    if (part == parts - 1 && tid == 0) {                // the last range ends where the batch ends
         counts[0] = total.keep;
         counts[1] = total.win;
         counts[2] = total.val;
@@ -158,7 +169,7 @@ extern "C" int tppo_select(const int32_t* cu_seqlens, const int32_t* ctx_len, co
     int32_t* n_chunks = want_fill ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) +
                                                                round_up((size_t)cap64 * sizeof(Chunk), 256))
                                   : nullptr;
-    hipLaunchKernelGGL(select_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, cu_seqlens, ctx_len,
+    hipLaunchKernelGGL(select_scan_kernel, dim3(build_parts(B)), dim3(kScanThreads), 0, s, cu_seqlens, ctx_len,
                        done, (int)B, (int)n_tok, (int)tail_drop, resp_off, sel_off, keep_len, counts,
                        chunks, (int)cap64, n_chunks, status);
     if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;

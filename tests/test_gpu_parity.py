@@ -865,6 +865,9 @@ def test_whole_update_step_small(tp):
 
 
 # ------------------------------------------------------------------ randomised batches
+SPECIAL_WINDOWS = np.array([0, 1, 2, 2047, 2048, 2049, 4096, 4097])
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_batches_all_stages(tp, seed):
     """Random layouts (1..40 sequences, windows of 0..5000 tokens, contexts of 1..50, any
@@ -872,8 +875,21 @@ def test_random_batches_all_stages(tp, seed):
     EGAE (dense and terminal rewards), losses and their derivatives against the oracle."""
     rng = np.random.default_rng(1000 + seed)
     B = int(rng.integers(1, 41))
-    special = np.array([0, 1, 2, 2047, 2048, 2049, 4096, 4097])
-    win = np.where(rng.random(B) < 0.3, rng.choice(special, size=B), rng.integers(0, 5001, size=B))
+    win = np.where(rng.random(B) < 0.3, rng.choice(SPECIAL_WINDOWS, size=B), rng.integers(0, 5001, size=B))
+    all_stages_against_oracle(tp, rng, win, seed)
+
+
+@pytest.mark.parametrize("B", [2048, 2049, 5000, 17001])
+def test_many_sequences_all_stages(tp, B):
+    """Thousands of short sequences (empty ones and a few longer than a chunk among them):
+    the work lists are then built by several workgroups, each for its own range of sequences."""
+    rng = np.random.default_rng(2000 + B)
+    win = np.where(rng.random(B) < 0.01, rng.choice(SPECIAL_WINDOWS, size=B), rng.integers(0, 200, size=B))
+    all_stages_against_oracle(tp, rng, win, B)
+
+
+def all_stages_against_oracle(tp, rng, win, seed):
+    B = win.size
     ctx = rng.integers(1, 51, size=B)
     done = (rng.random(B) < rng.random()).astype(np.int32)
     cu = np.concatenate([[0], np.cumsum(ctx + win)]).astype(np.int32)
