@@ -864,6 +864,62 @@ def test_whole_update_step_small(tp):
     assert np.all(np.abs(host(dh) - ref_h) <= tol_h) and np.all(np.abs(host(dw) - ref_w) <= tol_w)
 
 
+def test_whole_step_captured_in_a_graph_replays_like_eager(tp):
+    """The library neither allocates nor synchronises nor clears memory with memset nodes, so a whole
+    step (select -> log-probs -> EGAE -> losses) can be captured in a HIP graph.  Every replay, with the
+    inputs changed in place and eager work in between, must reproduce the eager step bit for bit."""
+    import torch
+    b = synth.make_batch("small", B=4, V=2000, H=256)
+    n_resp, n_tok = b["n_resp"], b["n_tok"]
+    rng = np.random.default_rng(77)
+    cu, ctx, done, ids = dev(b["cu_seqlens"]), dev(b["ctx_len"]), dev(b["done"]), dev(b["input_ids"])
+    hidden, w = dev(b["hidden"]), dev(b["w_head"])
+    rewards, values, v_new = dev(b["rewards"]), dev(b["values"]), dev(b["v_new"])
+    logp_old = dev((-np.abs(rng.normal(size=n_resp)) - 6.0).astype(np.float32))
+
+    def step():
+        sel = tp.tppo_select(cu, ctx, done, ids, b["tail_drop"])
+        logp, _ = tp.tppo_token_logprobs(hidden, w, sel["sel_rows"], sel["sel_targets"], M=n_tok,
+                                         m_actual=sel["counts"], out_index=sel["sel_resp_idx"], out_size=n_resp)
+        adv, ret = tp.tppo_egae(rewards, values, sel["resp_off"], done, b["gamma"], b["lam"])
+        res = tp.tppo_ppo_losses(logp, logp_old, adv, v_new, values, ret, sel["resp_off"], sel["keep_len"], done,
+                                 b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"])
+        return sel, logp, adv, ret, res
+
+    step()                                                    # first calls (occupancy queries, attributes) outside
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            g_sel, g_logp, g_adv, g_ret, g_res = step()
+    torch.cuda.current_stream().wait_stream(side)
+    for trial in range(4):
+        if trial:                                             # new inputs, same buffers
+            hidden.copy_(dev(synth.f32_to_bf16_bits(rng.normal(size=b["hidden"].shape).astype(np.float32))))
+            values.copy_(dev(rng.uniform(-1, 1, size=n_resp).astype(np.float32)))
+            rewards.copy_(dev(np.where(rng.random(n_resp) < 0.01, 1.0, 0.0).astype(np.float32)))
+            ids.copy_(dev(rng.integers(0, 2000, size=n_tok).astype(np.int32)))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [host(t).copy() for t in (g_sel["sel_resp_idx"], g_sel["counts"], g_logp, g_adv, g_ret, g_res)]
+        e_sel, e_logp, e_adv, e_ret, e_res = step()           # eager work between the replays
+        torch.cuda.synchronize()
+        M = int(got[1][0])
+        assert M > 0 and np.array_equal(got[1], host(e_sel["counts"]))
+        kept = got[0][:M]
+        assert np.array_equal(kept, host(e_sel["sel_resp_idx"])[:M])
+        assert np.array_equal(got[2][kept], host(e_logp)[kept]), trial
+        assert np.array_equal(got[3], host(e_adv)) and np.array_equal(got[4], host(e_ret)), trial
+        assert np.array_equal(got[5], host(e_res)), trial
+    # and the last replay against the oracle
+    osel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], host(ids), b["tail_drop"])
+    olp, _ = ofast.token_logprobs(host(hidden.view(torch.int16)).view(np.uint16), b["w_head"], osel["sel_rows"],
+                                  osel["sel_targets"])
+    assert np.max(np.abs(got[2][osel["sel_resp_idx"]] - olp)) <= LOGP_ATOL
+
+
 # ------------------------------------------------------------------ randomised batches
 SPECIAL_WINDOWS = np.array([0, 1, 2, 2047, 2048, 2049, 4096, 4097])
 
