@@ -986,3 +986,105 @@ def all_stages_against_oracle(tp, rng, win, seed):
     assert_grads_close(g_lp, og["grad_logp"], kp, -np.exp(f["logp_new"] - f["logp_old"]) * f["adv"] / max(og["n_policy"], 1))
     assert_grads_close(g_v, og["grad_v"], kv, (f["v_new"] - f["ret"]) / max(og["n_value"], 1))
     assert_loss_close(losses, ref)
+
+
+# ------------------------------------------------------------------ maximum sizes
+@pytest.mark.timeout(600)
+def test_all_stages_at_the_largest_batch_the_abi_takes(tp):
+    """~2^31 window tokens (the ABI's 32-bit token indices end there): a sub-batch of 40 sequences -- two
+    of them hundreds of chunks long -- repeated 1800-odd times.  Every copy must reproduce the first one
+    bit for bit (indices shifted by the copy's offset), the first and last copy are compared with the
+    oracle element by element, and the loss sums with the oracle's sums for the sub-batch times the copies."""
+    import torch
+    rng = np.random.default_rng(4242)
+    win = np.concatenate([[700001, 0, 300007], np.exp(rng.uniform(np.log(256), np.log(20480), size=37)).astype(np.int64)])
+    Bs = win.size
+    done_s = (rng.random(Bs) < 0.4).astype(np.int32)
+    done_s[0], done_s[2] = 1, 0                               # one long finished, one long truncated sequence
+    ctx_s = rng.integers(1, 4, size=Bs)
+    n_sub, n_tok_sub = int(win.sum()), int((win + ctx_s).sum())
+    copies = (2**31 - 4096 - 2048) // n_tok_sub
+    B, n, n_tok = Bs * copies, n_sub * copies, n_tok_sub * copies
+    assert n_tok < 2**31 - 2048 and n > 2**31 - 3 * n_tok_sub
+    tail_drop = 1024
+    off_s = np.concatenate([[0], np.cumsum(win)]).astype(np.int64)
+    cu_s = np.concatenate([[0], np.cumsum(win + ctx_s)]).astype(np.int64)
+    keep_s = np.where(done_s != 0, win, np.maximum(win - tail_drop, 0)).astype(np.int32)
+    tile_off = lambda o, step: torch.from_numpy(np.concatenate(
+        [(o[:-1][None, :] + step * np.arange(copies)[:, None]).ravel(), [step * copies]]).astype(np.int32)).cuda()
+    rep = lambda a: dev(a).repeat(copies)
+    done, keep = rep(done_s), rep(keep_s)
+    resp_off = tile_off(off_s, n_sub)
+
+    def same_in_every_copy(t, width, shift=0):
+        """t[c*width + k] == t[k] + c*shift for every copy c, checked on the device in slices"""
+        first = t[:width]
+        for c0 in range(0, copies, 64):
+            c1 = min(c0 + 64, copies)
+            block = t[c0 * width:c1 * width].view(c1 - c0, width)
+            if shift:
+                block = block - (torch.arange(c0, c1, device="cuda", dtype=t.dtype) * shift)[:, None]
+            if not torch.equal(block, first.expand(c1 - c0, width)):
+                return False
+        return True
+
+    # ---- select
+    ids_s = rng.integers(0, 50000, size=n_tok_sub).astype(np.int32)
+    st = tp.new_status("cuda")
+    sel = tp.tppo_select(tile_off(cu_s, n_tok_sub), rep(ctx_s.astype(np.int32)), done, rep(ids_s), tail_drop, status=st)
+    osel = ofast.select(cu_s.astype(np.int32), ctx_s.astype(np.int32), done_s, ids_s, tail_drop)
+    M_s = osel["M"]
+    assert int(host(st)[0]) == 0
+    assert host(sel["counts"]).tolist() == [M_s * copies, n, osel["N_val"] * copies]
+    assert torch.equal(sel["resp_off"], resp_off) and torch.equal(sel["keep_len"], keep)
+    for k, shift in (("sel_rows", n_tok_sub), ("sel_targets", 0), ("sel_resp_idx", n_sub)):
+        assert np.array_equal(host(sel[k][:M_s]), osel[k]), k
+        assert same_in_every_copy(sel[k][:M_s * copies], M_s, shift), k
+    del sel
+    torch.cuda.empty_cache()
+
+    # ---- EGAE
+    r_s = np.where(rng.random(n_sub) < 0.01, rng.normal(size=n_sub), 0.0).astype(np.float32)
+    v_s = rng.uniform(-1, 1, size=n_sub).astype(np.float32)
+    gamma, lam = 1.0, 0.95
+    values = rep(v_s)
+    adv, ret = tp.tppo_egae(rep(r_s), values, resp_off, done, gamma, lam, status=st)
+    ref_a, ref_r = ofast.egae(r_s, v_s, off_s.astype(np.int32), done_s, gamma, float(np.float32(lam)))
+    assert int(host(st)[0]) == 0
+    for c in (0, copies - 1):
+        assert_egae_close(host(adv[c * n_sub:(c + 1) * n_sub]), ref_a, "adv")
+        assert_egae_close(host(ret[c * n_sub:(c + 1) * n_sub]), ref_r, "ret")
+    assert same_in_every_copy(adv, n_sub) and same_in_every_copy(ret, n_sub)
+    del adv, ret
+    torch.cuda.empty_cache()
+
+    # ---- losses and their derivatives (advantages and returns: the oracle's, rounded to fp32)
+    a_s = dict(logp_new=(-np.abs(rng.normal(size=n_sub)) - 0.01).astype(np.float32), adv=ref_a.astype(np.float32),
+               ret=ref_r.astype(np.float32), v_new=(v_s + rng.normal(0, 0.3, size=n_sub)).astype(np.float32), v_old=v_s)
+    a_s["logp_old"] = (a_s["logp_new"] + rng.normal(0, 0.1, size=n_sub)).astype(np.float32)
+    eps = (float(np.float32(0.2)), float(np.float32(0.28)), 0.5, float(np.float32(0.6)))
+    order = ("logp_new", "logp_old", "adv", "v_new", "v_old", "ret")
+    ref = ofast.ppo_losses(*(a_s[k] for k in order), off_s.astype(np.int32), keep_s, done_s, *eps)
+    og = ofast.ppo_loss_grads(*(a_s[k] for k in order), off_s.astype(np.int32), keep_s, done_s, *eps)
+    d = dict(logp_new=rep(a_s["logp_new"]), logp_old=rep(a_s["logp_old"]), adv=rep(a_s["adv"]),
+             v_new=rep(a_s["v_new"]), v_old=values, ret=rep(a_s["ret"]))
+    got = tp.read_loss_out(tp.tppo_ppo_losses(*(d[k] for k in order), resp_off, keep, done, 0.2, 0.28, 0.5, 0.6, status=st))
+    whole = dict(ref, policy_sum=ref["policy_sum"] * copies, value_sum=ref["value_sum"] * copies,
+                 n_policy=ref["n_policy"] * copies, n_value=ref["n_value"] * copies)
+    assert_loss_close(got, whole)
+    g_lp, g_v, res, stats = tp.tppo_ppo_losses_backward(*(d[k] for k in order), resp_off, keep, done, 0.2, 0.28, 0.5, 0.6,
+                                                        status=st)
+    assert int(host(st)[0]) == 0
+    assert_loss_close(tp.read_loss_out(res), whole)
+    bb = dict(resp_off=off_s.astype(np.int32), done=done_s, eps_low=0.2, eps_high=0.28, xi_low=0.5, xi_high=0.6)
+    kp, kv = near_kinks(a_s, bb, keep_s)
+    f = {k: v.astype(np.float64) for k, v in a_s.items()}
+    free_p = -np.exp(f["logp_new"] - f["logp_old"]) * f["adv"] / whole["n_policy"]
+    free_v = (f["v_new"] - f["ret"]) / whole["n_value"]
+    for c in (0, copies - 1):
+        assert_grads_close(host(g_lp[c * n_sub:(c + 1) * n_sub]), og["grad_logp"] / copies, kp, free_p)
+        assert_grads_close(host(g_v[c * n_sub:(c + 1) * n_sub]), og["grad_v"] / copies, kv, free_v)
+    assert same_in_every_copy(g_lp, n_sub) and same_in_every_copy(g_v, n_sub)
+    assert tp.read_loss_stats(stats)["n_policy_clipped"] % copies == 0
+    del d, g_lp, g_v, values
+    torch.cuda.empty_cache()
