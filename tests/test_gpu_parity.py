@@ -482,6 +482,44 @@ def test_value_head_32b_shape_value_tokens(tp):
     check_value_head(tp, b["hidden"], w, 0.0, rows)
 
 
+@pytest.mark.timeout(600)
+def test_hidden_matrix_beyond_4_GiB(tp):
+    """Rows of a 9.2 GB hidden matrix (byte offsets past 2^32 and 2^33): log-probs, their derivatives
+    and the value head gather rows through 64-bit arithmetic.  The matrix is drawn on the device; the
+    picked rows travel to the host for the oracle."""
+    import torch
+    N, H, V, M = 900_001, 5120, 32000, 320
+    rng = np.random.default_rng(31)
+    gen = torch.Generator(device="cuda").manual_seed(31)
+    hidden = torch.empty(N, H, dtype=torch.bfloat16, device="cuda")
+    for r0 in range(0, N, 100_000):
+        hidden[r0:r0 + 100_000].normal_(generator=gen)
+    edge = [0, 1, N - 2, N - 1] + [2**32 // (2 * H) + d for d in (-1, 0, 1)] + [2**33 // (2 * H) + d for d in (-1, 0, 1)]
+    rows = np.unique(np.concatenate([edge, rng.integers(0, N, size=M - len(edge))])).astype(np.int32)
+    rng.shuffle(rows)
+    M = rows.size
+    picked = host(hidden[torch.from_numpy(rows.astype(np.int64)).cuda()].view(torch.int16)).view(np.uint16)
+    w = synth.f32_to_bf16_bits((rng.normal(size=(V, H)) * 0.02).astype(np.float32))
+    targets = rng.integers(0, V, size=M).astype(np.int32)
+    ident = np.arange(M)
+    st = tp.new_status("cuda")
+    logp, lse = tp.tppo_token_logprobs(hidden, dev(w), dev(rows), dev(targets), status=st)
+    ref, ref_lse = ofast.token_logprobs(picked, w, ident, targets)
+    assert int(host(st)[0]) == 0
+    assert np.abs(host(logp) - ref).max() <= LOGP_ATOL and np.abs(host(lse) - ref_lse).max() <= LOGP_ATOL
+    g = rng.normal(size=M).astype(np.float32)
+    dh, dw = tp.tppo_token_logprobs_backward(hidden, dev(w), dev(rows), dev(targets), dev(ref_lse.astype(np.float32)), dev(g))
+    ref_h, ref_w, abs_h, abs_w = ofast.token_logprob_grads(picked, w, ident, targets, g, return_abs_bounds=True)
+    assert_within_term_bound(host(dh), ref_h, abs_h, "grad_hidden")
+    assert_within_term_bound(host(dw), ref_w, abs_w, "grad_w")
+    wv = synth.f32_to_bf16_bits((rng.normal(size=H) / np.sqrt(H)).astype(np.float32))
+    got_v = host(tp.tppo_value_head(hidden, dev(wv), 0.25, dev(rows)))
+    ref_v, bound = ofast.value_head(picked, wv, 0.25, ident, return_abs_bound=True)
+    assert np.all(np.abs(got_v - ref_v) <= 1e-5 * (bound + 0.25))
+    del hidden
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ EGAE
 def check_egae(tp, rewards, values, resp_off, done, gamma, lam, bootstrap=None):
     st = tp.new_status("cuda")
