@@ -1,5 +1,5 @@
 // tppo_select: token filter of Sec. 3.2 as a segmented compaction.
-//   kernel 1 (one workgroup): per-sequence window / keep lengths, their prefix
+//   kernel 1 (one workgroup per 1024 sequences): per-sequence window / keep lengths, their prefix
 //            sums (resp_off, sel_off), the counts, and a list of chunks of the
 //            compact output (<= 2048 kept tokens of one sequence each);
 //   kernel 2 (persistent grid): walks the chunk list; a chunk's descriptor says
