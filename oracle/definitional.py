@@ -147,7 +147,9 @@ def ppo_losses(logp_new, logp_old, adv, v_new, v_old, ret,
     """Token-level means (Sec. 4.1.1) over the policy set and the value set.
 
     policy_loss = -J_PPO (the paper maximises J_PPO), value_loss = +J_value.
-    Empty sets give 0.  Tokens outside a set are never touched.
+    Empty sets give 0.  Tokens outside a set are never touched.  A token of a
+    set with a NaN among its three inputs has the term NaN (Python's min / max
+    would return either operand depending on the order, so the rule is spelled out).
     """
     pol_terms, val_terms = [], []
     for i in range(len(done)):
@@ -157,12 +159,18 @@ def ppo_losses(logp_new, logp_old, adv, v_new, v_old, ret,
             if t < int(keep_len[i]):
                 ratio = math.exp(float(logp_new[j]) - float(logp_old[j]))
                 a = float(adv[j])
-                pol_terms.append(min(ratio * a,
-                                     _clip(ratio, 1.0 - eps_low, 1.0 + eps_high) * a))
+                if math.isnan(ratio) or math.isnan(a):        # not a number in, not a number out
+                    pol_terms.append(math.nan)
+                else:
+                    pol_terms.append(min(ratio * a,
+                                         _clip(ratio, 1.0 - eps_low, 1.0 + eps_high) * a))
             if int(done[i]) != 0:
                 v, vo, r = float(v_new[j]), float(v_old[j]), float(ret[j])
-                v_clip = _clip(v, vo - xi_low, vo + xi_high)
-                val_terms.append(max((v - r) ** 2, (v_clip - r) ** 2))
+                if math.isnan(v) or math.isnan(vo) or math.isnan(r):
+                    val_terms.append(math.nan)
+                else:
+                    v_clip = _clip(v, vo - xi_low, vo + xi_high)
+                    val_terms.append(max((v - r) ** 2, (v_clip - r) ** 2))
     policy_sum = -math.fsum(pol_terms)
     value_sum = 0.5 * math.fsum(val_terms)
     n_pol, n_val = len(pol_terms), len(val_terms)
@@ -197,7 +205,9 @@ def ppo_loss_grads(logp_new, logp_old, adv, v_new, v_old, ret,
     Token-level means: each derivative is divided by the number of tokens of
     its set (or by the given denominator, for a batch spread over several
     calls).  policy_loss = -J_PPO, hence the minus sign.  Entries outside a set
-    get 0.  Also returns the clipped-token counts and the mean ratio.
+    get 0.  Also returns the clipped-token counts and the mean ratio.  A token
+    of a set with a NaN among its inputs gets the derivative NaN and is counted
+    neither as clipped nor as unclipped.
     """
     n = int(resp_off[len(done)])
     g_lp, g_v = [0.0] * n, [0.0] * n
@@ -217,7 +227,9 @@ def ppo_loss_grads(logp_new, logp_old, adv, v_new, v_old, ret,
                 u = ratio * a
                 c = _clip(ratio, 1.0 - eps_low, 1.0 + eps_high) * a
                 ratios.append(ratio)
-                if u <= c:
+                if math.isnan(u):                             # undefined term: neither branch
+                    g_lp[j] = math.nan
+                elif u <= c:
                     g_lp[j] = -policy_scale * ratio * a / den_p
                 else:
                     pol_clipped += 1
@@ -225,7 +237,9 @@ def ppo_loss_grads(logp_new, logp_old, adv, v_new, v_old, ret,
                 v, vo, r = float(v_new[j]), float(v_old[j]), float(ret[j])
                 d0 = v - r
                 d1 = _clip(v, vo - xi_low, vo + xi_high) - r
-                if d0 * d0 >= d1 * d1:
+                if math.isnan(d0) or math.isnan(vo):
+                    g_v[j] = math.nan
+                elif d0 * d0 >= d1 * d1:
                     g_v[j] = value_scale * d0 / den_v
                 else:
                     val_clipped += 1

@@ -161,7 +161,9 @@ def ppo_losses(logp_new, logp_old, adv, v_new, v_old, ret,
     value_loss = 1/2 mean_value max((V-R)^2, (V_clip-R)^2) with V_clip from
     Eq. (valueclip)  (Eq. (valueloss)).  Token-level means (Sec. 4.1.1).
     Masked-out entries are selected away before any arithmetic, so whatever
-    they hold (NaN, Inf) cannot reach the result.
+    they hold (NaN, Inf) cannot reach the result.  An entry INSIDE a set that
+    is not a number makes its term, and hence that loss, not a number (the
+    paper is silent; min, max and clip here all propagate NaN).
     """
     pol, val = loss_masks(resp_off, keep_len, done)
     n_pol, n_val = int(pol.sum()), int(val.sum())
@@ -192,7 +194,9 @@ def ppo_loss_grads(logp_new, logp_old, adv, v_new, v_old, ret,
     Eqs. (valueclip), (valueloss); token-level means), zero outside the sets:
     -rho A / N where the unclipped surrogate is the minimum, 0 where the clip is
     saturated; (V - R) / N where the unclipped square is the maximum, 0 where
-    the clipped one is.  Plus clipped-token counts and the mean ratio."""
+    the clipped one is.  Plus clipped-token counts and the mean ratio.
+    A token of a set with a NaN among its inputs has an undefined term: its
+    derivative is NaN and it is counted neither as clipped nor as unclipped."""
     pol, val = loss_masks(resp_off, keep_len, done)
     n = pol.shape[0]
     n_pol, n_val = int(pol.sum()), int(val.sum())
@@ -204,17 +208,19 @@ def ppo_loss_grads(logp_new, logp_old, adv, v_new, v_old, ret,
     if n_pol:
         ln, lo_, a = (decode(x)[pol] for x in (logp_new, logp_old, adv))
         rho = np.exp(ln - lo_)
+        undefined = np.isnan(rho * a)
         unclipped = rho * a <= np.clip(rho, 1.0 - eps_low, 1.0 + eps_high) * a
-        g_lp[pol] = np.where(unclipped, -policy_scale * rho * a / den_p, 0.0)
-        pol_clipped = int((~unclipped).sum())
+        g_lp[pol] = np.where(undefined, np.nan, np.where(unclipped, -policy_scale * rho * a / den_p, 0.0))
+        pol_clipped = int((~unclipped & ~undefined).sum())
         ratio_mean = float(rho.mean())
     if n_val:
         v, vo, r = (decode(x)[val] for x in (v_new, v_old, ret))
         d0 = v - r
         d1 = np.clip(v, vo - xi_low, vo + xi_high) - r
+        undefined = np.isnan(d0) | np.isnan(d1)
         unclipped = d0 * d0 >= d1 * d1
-        g_v[val] = np.where(unclipped, value_scale * d0 / den_v, 0.0)
-        val_clipped = int((~unclipped).sum())
+        g_v[val] = np.where(undefined, np.nan, np.where(unclipped, value_scale * d0 / den_v, 0.0))
+        val_clipped = int((~unclipped & ~undefined).sum())
     return dict(grad_logp=g_lp, grad_v=g_v, n_policy=n_pol, n_value=n_val,
                 n_policy_clipped=pol_clipped, n_value_clipped=val_clipped, ratio_mean=ratio_mean)
 

@@ -643,6 +643,71 @@ def test_successive_batching_paper_example():
     assert sb.layout()[4] == rows["step1"]
 
 
+def test_successive_batching_worked_example():
+    """Three steps worked by hand (lengths included): context accumulation, both ending rules,
+    refill order and id numbering, and the calls the rules forbid."""
+    g = {}
+    for line in open(os.path.join(GOLDEN, "successive_batching_worked.txt")):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            k, v = line.split(":")
+            g[k] = [int(x) for x in v.split()]
+    sb = odef.SuccessiveBatch(g["slots"][0], g["window"][0], g["max_response"][0])
+    for step in (1, 2, 3):
+        assert sb.refill(g[f"refill{step - 1}"]) == g[f"taken{step - 1}"][0]
+        if step == 1:
+            with pytest.raises(ValueError):
+                sb.advance([5, 4, 4], [0, 0, 0])                    # one step adds at most `window` tokens
+        sb.advance(g[f"gen{step}"], g[f"eos{step}"])
+        cu, ctx, prompt, done, ids = sb.layout()
+        assert [list(map(int, x)) for x in (cu, ctx, prompt, done, ids)] == \
+               [g[f"cu{step}"], g[f"ctx{step}"], g[f"prompt{step}"], g[f"done{step}"], g[f"ids{step}"]], step
+    # value tokens of the sequence that ended at the maximum length: its whole response, 10 tokens over 3 windows
+    assert cu[1] - cu[0] - prompt[0] == 10 and done[0] == 1 and g["eos3"][0] == 0
+    with pytest.raises(ValueError):
+        sb.advance([1, 1, 1], [0, 0, 0])                            # slots 0 and 2 hold ended sequences
+    sb.refill([4, 4])
+    with pytest.raises(ValueError):
+        sb.advance([4, 3, 4], [0, 0, 0])                            # slot 1 would pass max_response (8 + 3)
+    with pytest.raises(ValueError):
+        sb.advance([3, 2, 4], [0, 1, 0])                            # slot 0 stops short of the window without ending
+    sb.advance([4, 2, 4], [0, 0, 0])                                # slot 1 reaches max_response exactly
+    assert list(sb.layout()[3]) == [0, 1, 0]
+
+
+def test_nan_inside_a_set_makes_the_loss_and_its_derivative_nan():
+    """The paper is silent on inputs that are not numbers.  Reading: inside a token set a NaN is never
+    clipped away -- the term and its derivative are NaN, the token counts towards N but is neither
+    clipped nor unclipped; outside the sets it still cannot reach anything."""
+    rng = np.random.default_rng(61)
+    off, keep, done, a = _random_loss_inputs(rng, B=9)
+    pol, val = ofast.loss_masks(off, keep, done)
+    for impl in (odef, ofast):
+        clean, gclean = _call(impl, a, off, keep, done), _grad_call(impl, a, off, keep, done)
+        for key, mask, bad, good, gkey, gother in (
+                ("logp_new", pol, "policy_loss", "value_loss", "grad_logp", "grad_v"),
+                ("logp_old", pol, "policy_loss", "value_loss", "grad_logp", "grad_v"),
+                ("adv", pol, "policy_loss", "value_loss", "grad_logp", "grad_v"),
+                ("v_new", val, "value_loss", "policy_loss", "grad_v", "grad_logp"),
+                ("v_old", val, "value_loss", "policy_loss", "grad_v", "grad_logp"),
+                ("ret", val, "value_loss", "policy_loss", "grad_v", "grad_logp")):
+            j = int(np.flatnonzero(mask)[3])
+            c = {k: np.array(v, dtype=np.float64) for k, v in a.items()}
+            c[key][j] = np.nan
+            out, g = _call(impl, c, off, keep, done), _grad_call(impl, c, off, keep, done)
+            assert math.isnan(out[bad]) and out[good] == clean[good], (key, out)
+            assert out["n_policy"] == clean["n_policy"] and out["n_value"] == clean["n_value"]
+            gv, gc = np.asarray(g[gkey], dtype=np.float64), np.asarray(gclean[gkey], dtype=np.float64)
+            assert math.isnan(gv[j]), key
+            others = np.arange(gv.size) != j
+            assert np.array_equal(gv[others], gc[others])
+            assert np.array_equal(np.asarray(g[gother]), np.asarray(gclean[gother]))
+            # the undefined token leaves the clipped counts of everybody else alone
+            was_clipped = gc[j] == 0.0
+            n_key = "n_policy_clipped" if gkey == "grad_logp" else "n_value_clipped"
+            assert g[n_key] == gclean[n_key] - (1 if was_clipped else 0)
+
+
 def test_successive_batching_invariants():
     rng = np.random.default_rng(51)
     K, l, L = 6, 8, 24
