@@ -110,15 +110,23 @@ __device__ __forceinline__ float clampf(float x, float lo, float hi) {
     return fminf(fmaxf(x, lo), hi);
 }
 
+// fminf / fmaxf return the operand that IS a number, so a NaN input would be clipped away; inside a token set
+// it must reach the result instead (the term of such a token is undefined), hence the explicit tests.
 __device__ __forceinline__ float surrogate(float ln, float lo, float a, float rlo, float rhi) {
     const float rho = ratio_exp(ln - lo);
-    return fminf(rho * a, clampf(rho, rlo, rhi) * a);
+    const float u = rho * a;
+    const float t = fminf(u, clampf(rho, rlo, rhi) * a);
+    return u != u ? u : t;
+}
+
+__device__ __forceinline__ bool value_undefined(float d0, float d1, float vo) {
+    return d0 != d0 || d1 != d1 || vo != vo;
 }
 
 __device__ __forceinline__ float value_term(float v, float vo, float r, float xl, float xh) {
     const float d0 = v - r;
     const float d1 = clampf(v, vo - xl, vo + xh) - r;
-    return fmaxf(d0 * d0, d1 * d1);
+    return value_undefined(d0, d1, vo) ? __builtin_nanf("") : fmaxf(d0 * d0, d1 * d1);
 }
 
 __device__ __forceinline__ double block_sum(double x, double* s_red) {
@@ -408,11 +416,11 @@ __global__ __launch_bounds__(kChunkThreads) void loss_grad_kernel(GradParams gp,
                         const float rho = ratio_exp(ln[g][e] - lo[g][e]);
                         const float u = rho * a[g][e];
                         const float c = clampf(rho, p.ratio_lo, p.ratio_hi) * a[g][e];
-                        const bool in_set = e < n_pol[g], unclipped = u <= c;
-                        pol_acc += in_set ? fminf(u, c) : 0.f;     // select, never multiply by a mask
+                        const bool in_set = e < n_pol[g], unclipped = u <= c, undefined = u != u;
+                        pol_acc += in_set ? (undefined ? u : fminf(u, c)) : 0.f;     // select, never multiply by a mask
                         ratio_acc += in_set ? rho : 0.f;
-                        pol_clipped += (in_set && !unclipped) ? 1 : 0;
-                        gl[e] = (in_set && unclipped) ? pol_coef * u : 0.f;
+                        pol_clipped += (in_set && !unclipped && !undefined) ? 1 : 0;
+                        gl[e] = in_set ? (undefined ? u : unclipped ? pol_coef * u : 0.f) : 0.f;
                     }
                 }
                 store4(gp.grad_logp, start + k0, gl, n_tok[g]);
@@ -426,9 +434,11 @@ __global__ __launch_bounds__(kChunkThreads) void loss_grad_kernel(GradParams gp,
                         const float d1 = clampf(v[g][e], vo[g][e] - p.xi_low, vo[g][e] + p.xi_high) - r[g][e];
                         const float q0 = d0 * d0, q1 = d1 * d1;
                         const bool in_set = e < n_val[g], unclipped = q0 >= q1;
-                        val_acc += in_set ? fmaxf(q0, q1) : 0.f;
-                        val_clipped += (in_set && !unclipped) ? 1 : 0;
-                        gv[e] = (in_set && unclipped) ? val_coef * d0 : 0.f;
+                        const bool undefined = value_undefined(d0, d1, vo[g][e]);
+                        const float nan = __builtin_nanf("");
+                        val_acc += in_set ? (undefined ? nan : fmaxf(q0, q1)) : 0.f;
+                        val_clipped += (in_set && !unclipped && !undefined) ? 1 : 0;
+                        gv[e] = in_set ? (undefined ? nan : unclipped ? val_coef * d0 : 0.f) : 0.f;
                     }
                 }
                 store4(gp.grad_v, start + k0, gv, n_tok[g]);

@@ -1,0 +1,135 @@
+// Work plan shared by the EGAE scan and the loss kernels.
+//
+// The response-packed token array is cut into tiles of at most kTileTokens
+// tokens that never straddle two sequences.  A tile is described by 16 bytes,
+// so a wavefront learns everything about its tokens (which sequence, how far
+// into it, how many tiles follow) from ONE load instead of a chain of dependent
+// look-ups in the offset arrays.  Tiles are listed in token order: sequence 0
+// first and, inside a sequence, its first tile first.
+//
+// A plan is one block of device memory:
+//   header (256 B)   tile count, the sizes it was built for, the sizes of the
+//                    policy / value token sets of Sec. 3.2
+//   tiles[cap]       the descriptors
+//   scan_words[cap][4]   what a tile of the scan publishes for the tiles to its
+//                    left: {tag << 32 | float bits} for A hi, A lo, R hi, R lo
+//   finish_words[kFinishGroups][kFinishWords]   partial sums of a reduction
+//                    kernel's workgroups, in the same tagged form
+// Whoever builds the list (tppo_select, tppo_plan_build, or an entry point that
+// was given no plan and builds its own in its workspace) zeroes all tagged
+// words.  Every later launch tags what it writes with its own call number
+// (never 0, never repeated inside a process), so words left by earlier calls
+// on the same plan never look ready and a plan needs no clearing between calls.
+#pragma once
+#include "common.h"
+
+namespace tppo {
+
+constexpr int kTileTokens = 1024;
+constexpr int kTileShift = 11;                 // pos_len keeps (tokens - 1) in the low bits
+constexpr int kBuildThreads = 1024;
+constexpr int kFinishGroups = 2048;            // most workgroups a reduction kernel may launch
+constexpr int kFinishWords = 10;               // tagged words per workgroup: five sums as hi + lo
+
+static_assert(kTileTokens <= (1 << kTileShift), "Tile::pos_len packs the length below the tile number");
+
+struct Tile {
+    int32_t start;     // response-packed index of the tile's first token
+    int32_t pos_len;   // (tile number inside the sequence << 11) | (tokens in the tile - 1)
+    int32_t seg;       // sequence the tile belongs to
+    int32_t after;     // tiles after it in the same sequence (0: it holds the sequence's last token)
+    __device__ __forceinline__ int len() const { return (pos_len & ((1 << kTileShift) - 1)) + 1; }
+    __device__ __forceinline__ int number() const { return pos_len >> kTileShift; }
+};
+
+struct PlanHeader {
+    int32_t n_tiles;               // tiles in the list
+    int32_t B, n_resp;             // what the plan was built for; a consumer called with other sizes refuses it
+    int32_t has_sets;              // n_policy / n_value are valid (the builder knew keep_len)
+    long long n_policy, n_value;   // tokens in the policy set / the value set (Sec. 3.2)
+};
+
+struct Plan {
+    PlanHeader* hdr;
+    Tile* tiles;
+    unsigned long long* scan_words;      // [cap][4]
+    unsigned long long* finish_words;    // [kFinishGroups][kFinishWords]
+};
+
+static inline int64_t plan_max_tiles(int64_t n_resp, int64_t B) { return n_resp / kTileTokens + B + 1; }
+
+static inline size_t plan_bytes_for(int64_t cap) {
+    return 256 + round_up((size_t)cap * sizeof(Tile), 256) + round_up((size_t)cap * 32, 256) +
+           (size_t)kFinishGroups * kFinishWords * sizeof(unsigned long long);
+}
+
+__host__ __device__ __forceinline__ Plan plan_view(void* raw, int64_t cap) {
+    char* p = static_cast<char*>(raw);
+    Plan pl;
+    pl.hdr = reinterpret_cast<PlanHeader*>(p);
+    p += 256;
+    pl.tiles = reinterpret_cast<Tile*>(p);
+    p += ((size_t)cap * sizeof(Tile) + 255) / 256 * 256;
+    pl.scan_words = reinterpret_cast<unsigned long long*>(p);
+    p += ((size_t)cap * 32 + 255) / 256 * 256;
+    pl.finish_words = reinterpret_cast<unsigned long long*>(p);
+    return pl;
+}
+
+// number of 8-byte tagged words of a plan (scan words, then finish words: contiguous but for padding)
+static inline int64_t plan_words(int64_t cap) {
+    return (int64_t)(((size_t)cap * 32 + 255) / 256 * 256) / 8 + (int64_t)kFinishGroups * kFinishWords;
+}
+
+// One workgroup per 1024 sequences builds the list (measured on 8704 sequences: the descriptor stores, one
+// cache line per lane, are what takes the time, which is why large batches spread them over several).
+constexpr int kBuildSeqsPerPart = 1024, kBuildMaxParts = 16;
+static inline int build_parts(int64_t B) {
+    const int64_t n = (B + kBuildSeqsPerPart - 1) / kBuildSeqsPerPart;
+    return n < 1 ? 1 : n > kBuildMaxParts ? kBuildMaxParts : (int)n;
+}
+
+__device__ __forceinline__ int tiles_of(int len) { return (len + kTileTokens - 1) / kTileTokens; }
+
+// the descriptors of one sequence: tokens [lo, lo + len) of the response-packed domain, list positions
+// first .. first + tiles_of(len) - 1
+__device__ __forceinline__ void emit_tiles(Tile* __restrict__ tiles, int cap, int first, int seg, int lo, int len) {
+    const int cnt = tiles_of(len);
+    for (int c = 0; c < cnt; ++c) {
+        Tile d;
+        d.start = lo + c * kTileTokens;
+        d.pos_len = (c << kTileShift) | (min(kTileTokens, len - c * kTileTokens) - 1);
+        d.seg = seg;
+        d.after = cnt - 1 - c;
+        if (first + c < cap) tiles[first + c] = d;             // overlapping sequences cannot overflow the list
+    }
+}
+
+// a tagged word: {tag, float}.  A double travels as two of them (hi + lo).
+__device__ __forceinline__ unsigned long long pack_word(uint32_t tag, float v) {
+    return ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v);
+}
+
+__device__ __forceinline__ void publish(unsigned long long* p, uint32_t tag, double x) {
+    const float hi = (float)x, lo = (float)(x - (double)hi);
+    __hip_atomic_store(p, pack_word(tag, hi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 1, pack_word(tag, lo), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One poll of a published double; true when both halves carry this call's tag.
+__device__ __forceinline__ bool poll(const unsigned long long* p, uint32_t tag, double& x) {
+    const unsigned long long w0 = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long w1 = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    x = (double)__uint_as_float((unsigned)w0) + (double)__uint_as_float((unsigned)w1);
+    return (uint32_t)(w0 >> 32) == tag && (uint32_t)(w1 >> 32) == tag;
+}
+
+// The next call number (host side; never 0).
+uint32_t next_call_tag();
+
+// Enqueue the kernel that builds a plan for (resp_off, done[, keep_len]) in `plan_raw` (plan_bytes_for(cap)
+// bytes, cap = plan_max_tiles(n_resp, B)) and zeroes its tagged words.  keep_len may be NULL (no set sizes).
+int launch_plan_build(const int32_t* resp_off, const int32_t* keep_len, const int32_t* done, int64_t B,
+                      int64_t n_resp, void* plan_raw, int32_t* status, hipStream_t s);
+
+}  // namespace tppo

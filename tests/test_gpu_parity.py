@@ -216,11 +216,46 @@ def test_logprobs_every_target_of_one_row_sums_to_one(tp):
     assert np.abs(lp - ref).max() <= LOGP_ATOL
 
 
-def test_logprobs_small_config_slice(tp):
-    b = synth.make_batch("small", B=6)
-    sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
-    assert sel["M"] > 1024
-    check_logprobs(tp, b["hidden"], b["w_head"], sel["sel_rows"], sel["sel_targets"])
+_SMALL_FULL = {}
+
+
+def small_full_oracle():
+    """Config 2 at its own size (32 sequences, H = 1024, V = 32000): batch, oracle selection and oracle
+    log-probs of every kept token, computed once per test session."""
+    if not _SMALL_FULL:
+        b = synth.make_batch("small")
+        sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+        lp, lse = ofast.token_logprobs(b["hidden"], b["w_head"], sel["sel_rows"], sel["sel_targets"])
+        _SMALL_FULL.update(b=b, sel=sel, logp=lp, lse=lse)
+    return _SMALL_FULL["b"], _SMALL_FULL["sel"], _SMALL_FULL["logp"], _SMALL_FULL["lse"]
+
+
+@pytest.mark.timeout(600)
+def test_logprobs_small_config_full(tp):
+    """Config 2 with all 32 sequences: every kept token against the oracle."""
+    b, sel, ref_lp, ref_lse = small_full_oracle()
+    assert sel["M"] > 12000
+    st = tp.new_status("cuda")
+    logp, lse = tp.tppo_token_logprobs(dev(b["hidden"]), dev(b["w_head"]), dev(sel["sel_rows"]),
+                                       dev(sel["sel_targets"]), status=st)
+    assert int(host(st)[0]) == 0
+    assert np.abs(host(logp) - ref_lp).max() <= LOGP_ATOL
+    assert np.abs(host(lse) - ref_lse).max() <= LOGP_ATOL
+
+
+@pytest.mark.parametrize("M,V,H", [(18600, 2048, 64), (21000, 1100, 128), (4200, 9000, 64)])
+def test_logprobs_many_token_tiles_every_output(tp, M, V, H):
+    """Many 256-token tiles against a small vocabulary and hidden size, so the oracle can afford
+    every output: the persistent schedule then has several rounds of units per XCD, more than one
+    unit column, a ragged last group of unit rows and a ragged last token tile."""
+    rng = np.random.default_rng(M)
+    N = M // 3 + 11                                       # rows are revisited, in no order
+    hidden = synth.f32_to_bf16_bits(rng.normal(size=(N, H)).astype(np.float32))
+    w = synth.f32_to_bf16_bits((rng.normal(size=(V, H)) / np.sqrt(H)).astype(np.float32))
+    rows = rng.integers(0, N, size=M)
+    targets = rng.integers(0, V, size=M)
+    targets[:V] = np.arange(V)[:M]                        # every vocabulary id is some token's target
+    check_logprobs(tp, hidden, w, rows, targets)
 
 
 def test_logprobs_scatter_count_and_status(tp):
@@ -263,19 +298,57 @@ def _sampled_rows(sel, n, seed):
     return np.array(sorted(pick))
 
 
-@pytest.mark.timeout(900)
+def _stratified_rows(sel, seed):
+    """One kept token out of every run of 16 consecutive compact indices (so every 256-token tile of the
+    MFMA sweep contributes 16 outputs, one per 16-column accumulator block, at positions that rotate through
+    all 16 columns), plus the first and last kept token of every sequence and of the batch."""
+    rng = np.random.default_rng(seed)
+    M = sel["M"]
+    starts = np.arange(0, M, 16)
+    pick = set(np.minimum(starts + (starts // 16 + rng.integers(0, 16)) % 16, M - 1).tolist())
+    so = sel["sel_off"]
+    for i in range(len(so) - 1):
+        if so[i + 1] > so[i]:
+            pick.add(int(so[i])); pick.add(int(so[i + 1] - 1))
+    pick.update((0, M - 1))
+    return np.array(sorted(pick))
+
+
+def _split_edge_targets(V, tile=256):
+    """Vocabulary ids on both sides of every boundary between vocabulary splits, for every split count
+    the kernel may choose (a split owns tiles [tiles*s/S, tiles*(s+1)/S) of `tile` ids), and both ends."""
+    tiles = (V + tile - 1) // tile
+    edges = set()
+    for S in (1, 2, 3) + tuple(range(4, 65, 4)):
+        for s in range(1, S):
+            edges.add((tiles * s // S) * tile)
+    ids = {0, V - 1}
+    for e in edges:
+        if 0 < e < V:
+            ids.update((e - 1, e))
+    return np.array(sorted(ids))
+
+
+@pytest.mark.timeout(1200)
 @pytest.mark.parametrize("name", ["head7b", "head32b"])
-def test_logprobs_full_size_sampled(tp, name):
-    """Full-size shapes in the launch configuration the benchmark times; the
-    oracle checks a seeded sample of outputs (plus each sequence's first and
-    last kept token) one by one."""
+def test_logprobs_full_size_stratified(tp, name):
+    """Full-size shapes in the launch configuration the benchmark times.  The oracle checks, one by
+    one, a stratified sample of the outputs: 16 per 256-token tile (one per accumulator block), each
+    sequence's first and last kept token; a few hundred of the sampled tokens get their target moved
+    onto the edges of the vocabulary splits."""
     import torch
     b = synth.make_batch(name)
     if b["cfg"].get("ids_from_policy"):
         synth.sample_ids_from_policy(b, device="cuda")
     sel = ofast.select(b["cu_seqlens"], b["ctx_len"], b["done"], b["input_ids"], b["tail_drop"])
+    pick = _stratified_rows(sel, seed=1)
+    assert pick.size >= 2048 and pick.size >= sel["M"] // 16
+    targets = sel["sel_targets"].copy()
+    edge_ids = _split_edge_targets(b["V"])
+    moved = pick[np.linspace(0, pick.size - 1, edge_ids.size).astype(np.int64)]
+    targets[moved] = edge_ids
     hidden, w = dev(b["hidden"]), dev(b["w_head"])
-    rows, tg = dev(sel["sel_rows"]), dev(sel["sel_targets"])
+    rows, tg = dev(sel["sel_rows"]), dev(targets)
     st = tp.new_status("cuda")
     logp, lse = tp.tppo_token_logprobs(hidden, w, rows, tg, status=st)
     logp2, _ = tp.tppo_token_logprobs(hidden, w, rows, tg)
@@ -284,9 +357,7 @@ def test_logprobs_full_size_sampled(tp, name):
     got, got_lse = host(logp), host(lse)
     assert np.array_equal(got, host(logp2))               # deterministic
     assert np.isfinite(got).all() and (got <= 0).all()
-    pick = _sampled_rows(sel, 96, seed=1)
-    ref, ref_lse = ofast.token_logprobs(b["hidden"], b["w_head"], sel["sel_rows"][pick],
-                                        sel["sel_targets"][pick])
+    ref, ref_lse = ofast.token_logprobs(b["hidden"], b["w_head"], sel["sel_rows"][pick], targets[pick])
     assert np.abs(got[pick] - ref).max() <= LOGP_ATOL, np.abs(got[pick] - ref).max()
     assert np.abs(got_lse[pick] - ref_lse).max() <= LOGP_ATOL
 
@@ -536,11 +607,35 @@ def check_egae(tp, rewards, values, resp_off, done, gamma, lam, bootstrap=None):
 
 
 @pytest.mark.timeout(300)
-@pytest.mark.parametrize("name", ["tiny", "small", "longcot"])
+@pytest.mark.parametrize("name", ["tiny", "small", "head7b", "head32b", "longcot"])
 @pytest.mark.parametrize("lam", [0.0, 0.95, 1.0])
 def test_egae_configs(tp, name, lam):
     b = synth.make_batch(name, with_head=False)
     check_egae(tp, b["rewards"], b["values"], b["resp_off"], b["done"], b["gamma"], lam)
+
+
+@pytest.mark.timeout(600)
+def test_egae_longcot5x(tp):
+    """The 10.5 M-token reading of the long-CoT workload (2176 sequences), paper rule and bootstrap array."""
+    b = synth.make_batch("longcot5x", with_head=False)
+    check_egae(tp, b["rewards"], b["values"], b["resp_off"], b["done"], b["gamma"], b["lam"])
+    check_egae(tp, b["rewards"], b["values"], b["resp_off"], b["done"], b["gamma"], 1.0, b["bootstrap"])
+
+
+def test_egae_one_very_long_sequence(tp):
+    """Sequences of 140 k - 300 k tokens between short ones: the carry of such a sequence is
+    collected from well over a hundred work units to its right."""
+    rng = np.random.default_rng(21)
+    lens = np.array([5, 140001, 1, 2048, 300017, 1024, 3, 163840])
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    n = int(off[-1])
+    done = np.array([1, 0, 1, 0, 1, 1, 0, 0], np.int32)
+    r = np.where(rng.random(n) < 0.01, rng.normal(size=n), 0.0).astype(np.float32)
+    v = rng.uniform(-1, 1, size=n).astype(np.float32)
+    boot = rng.uniform(-1, 1, size=lens.size).astype(np.float32)
+    for g, l in ((1.0, 1.0), (1.0, 0.95), (0.9999, 1.0)):
+        check_egae(tp, r, v, off, done, g, l)
+        check_egae(tp, r, v, off, done, g, l, boot)
 
 
 def test_egae_bootstrap_and_discount(tp):
@@ -654,7 +749,8 @@ def assert_loss_close(got, ref):
     assert got["n_policy"] == ref["n_policy"] and got["n_value"] == ref["n_value"]
 
 
-@pytest.mark.parametrize("name", ["tiny", "small", "longcot"])
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["tiny", "small", "head7b", "head32b", "longcot", "longcot5x"])
 def test_losses_configs(tp, name):
     b = synth.make_batch(name, with_head=False)
     a, keep = loss_inputs(b)
@@ -680,6 +776,39 @@ def test_losses_masked_entries_contribute_exactly_zero(tp):
     for k in ("v_new", "v_old", "ret"):
         p[k][~val] = np.inf
     assert run_losses(tp, p, b, keep) == clean            # bit-identical
+
+
+def test_nan_inside_a_set_reaches_the_loss_and_its_derivative(tp):
+    """A NaN in an entry that IS in a token set (a diverged model, a bad log-prob) must not be clipped
+    away: the loss of that half is NaN, the derivative at that token is NaN, every other derivative and
+    the other half are untouched.  Entries outside the sets still cannot reach anything."""
+    b = synth.make_batch("small", with_head=False)
+    a, keep = loss_inputs(b)
+    pol, val = ofast.loss_masks(b["resp_off"], keep, b["done"])
+    clean = run_losses(tp, a, b, keep)
+    g_lp, g_v, _, _ = run_loss_grads(tp, a, b, keep)
+    ip, iv = int(np.flatnonzero(pol)[777]), int(np.flatnonzero(val)[555])
+    for key, idx, half in (("logp_new", ip, "policy"), ("logp_old", ip, "policy"), ("adv", ip, "policy"),
+                           ("v_new", iv, "value"), ("v_old", iv, "value"), ("ret", iv, "value")):
+        p = {k: v.copy() for k, v in a.items()}
+        p[key][idx] = np.nan
+        ref = ofast.ppo_losses(p["logp_new"], p["logp_old"], p["adv"], p["v_new"], p["v_old"], p["ret"],
+                               b["resp_off"], keep, b["done"], b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"])
+        og = ofast.ppo_loss_grads(p["logp_new"], p["logp_old"], p["adv"], p["v_new"], p["v_old"], p["ret"],
+                                  b["resp_off"], keep, b["done"], b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"])
+        got = run_losses(tp, p, b, keep)
+        q_lp, q_v, q_loss, q_stats = run_loss_grads(tp, p, b, keep)
+        bad, good = (("policy_loss", "value_loss") if half == "policy" else ("value_loss", "policy_loss"))
+        assert np.isnan(ref[bad]) and np.isnan(got[bad]) and np.isnan(q_loss[bad]), (key, got)
+        assert got[good] == clean[good] and not np.isnan(ref[good])
+        assert got["n_policy"] == clean["n_policy"] and got["n_value"] == clean["n_value"]
+        g_bad, g_ref, g_clean = (q_lp, og["grad_logp"], g_lp) if half == "policy" else (q_v, og["grad_v"], g_v)
+        assert np.isnan(g_ref[idx]) and np.isnan(g_bad[idx]), key
+        others = np.arange(g_bad.size) != idx
+        assert np.array_equal(g_bad[others], g_clean[others])
+        assert np.array_equal(q_v if half == "policy" else q_lp, g_v if half == "policy" else g_lp)
+        # a token whose inputs are NaN is neither "clipped" nor "unclipped"
+        assert q_stats["n_policy_clipped"] == og["n_policy_clipped"] and q_stats["n_value_clipped"] == og["n_value_clipped"]
 
 
 def test_losses_halves_and_empty_sets(tp):
@@ -762,7 +891,8 @@ def assert_grads_close(got, ref, kink, unclipped_value):
     assert not bad.any(), (int(bad.sum()), np.flatnonzero(bad)[:5], got[bad][:5], ref[bad][:5])
 
 
-@pytest.mark.parametrize("name", ["tiny", "small", "longcot"])
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["tiny", "small", "head7b", "head32b", "longcot", "longcot5x"])
 def test_loss_grads_configs(tp, name):
     b = synth.make_batch(name, with_head=False)
     a, keep = loss_inputs(b)
@@ -854,6 +984,36 @@ def test_whole_path_tiny(tp):
                                b["xi_low"], b["xi_high"])
         assert_loss_close(got, ref)
     torch.cuda.synchronize()
+
+
+@pytest.mark.timeout(600)
+def test_whole_path_small_config_full(tp):
+    """Config 2 at its own size (bf16, H = 1024, V = 32000, 32 sequences), every stage fed by the stage
+    before it on device buffers, lambda in {0, 0.95, 1}; against the same chain in the oracle."""
+    b, osel, olp, _ = small_full_oracle()
+    n_resp = b["n_resp"]
+    st = tp.new_status("cuda")
+    sel = tp.tppo_select(dev(b["cu_seqlens"]), dev(b["ctx_len"]), dev(b["done"]), dev(b["input_ids"]),
+                         b["tail_drop"], status=st)
+    logp, _ = tp.tppo_token_logprobs(dev(b["hidden"]), dev(b["w_head"]), sel["sel_rows"], sel["sel_targets"],
+                                     M=b["n_tok"], m_actual=sel["counts"], out_index=sel["sel_resp_idx"],
+                                     out_size=n_resp, status=st)
+    o_new = np.zeros(n_resp); o_new[osel["sel_resp_idx"]] = olp
+    o_old = (o_new + b["logp_gap"]).astype(np.float32)
+    logp_old = dev(o_old)
+    for lam in (0.0, 0.95, 1.0):
+        adv, ret = tp.tppo_egae(dev(b["rewards"]), dev(b["values"]), sel["resp_off"], dev(b["done"]),
+                                b["gamma"], lam, status=st)
+        res = tp.tppo_ppo_losses(logp, logp_old, adv, dev(b["v_new"]), dev(b["values"]), ret, sel["resp_off"],
+                                 sel["keep_len"], dev(b["done"]), b["eps_low"], b["eps_high"], b["xi_low"],
+                                 b["xi_high"], status=st)
+        oadv, oret = ofast.egae(b["rewards"], b["values"], osel["resp_off"], b["done"], b["gamma"],
+                                float(np.float32(lam)))
+        ref = ofast.ppo_losses(o_new, o_old, oadv, b["v_new"], b["values"], oret, osel["resp_off"],
+                               osel["keep_len"], b["done"], b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"])
+        assert_egae_close(host(adv), oadv, "adv")
+        assert_loss_close(tp.read_loss_out(res), ref)
+    assert int(host(st)[0]) == 0
 
 
 def test_whole_update_step_small(tp):
