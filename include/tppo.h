@@ -14,8 +14,12 @@
  *
  * Conventions common to every entry point
  *   - Every array pointer is DEVICE memory owned by the caller, valid until the
- *     work enqueued by the call has finished.  The library allocates nothing,
- *     frees nothing and keeps no state between calls.
+ *     work enqueued by the call has finished.  The library allocates nothing and
+ *     frees nothing.  The only state it keeps is a process-wide call counter
+ *     (each launch that lets workgroups exchange partial results tags them with
+ *     its call number, which is why scratch memory needs no clearing between
+ *     calls) and, for tppo_token_logprobs*, a one-time per-process kernel
+ *     attribute.  No environment variable is read.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     All work is enqueued asynchronously on it; no call synchronises with the
  *     host, which is why scalar results are written to device memory.
@@ -61,7 +65,8 @@ typedef enum {
 /* bits of the device status word */
 enum {
     TPPO_STATUS_BAD_TARGET = 1,   /* a target id outside [0, V): its logp is NaN */
-    TPPO_STATUS_BAD_LAYOUT = 2,   /* ctx_len < 1, negative window length or non-monotone offsets */
+    TPPO_STATUS_BAD_LAYOUT = 2,   /* ctx_len < 1, negative window length, non-monotone offsets, or a plan that
+                                     was built for another batch (nothing is computed then) */
     TPPO_STATUS_CAPACITY = 4,     /* more kept tokens than `capacity`: excess not written */
     TPPO_STATUS_BAD_ROW = 8,      /* a row index outside [0, n_rows): its logp is NaN */
     TPPO_STATUS_TIMEOUT = 16      /* an inter-workgroup wait gave up (results invalid) */
@@ -95,6 +100,10 @@ int tppo_version(void);
  *      { M = sel_off[B], n_resp = resp_off[B], N_val = number of value tokens }.
  *      workspace: tppo_select_workspace_bytes(B, max(capacity, n_tok)) bytes; only
  *      needed (may be NULL otherwise) when one of the three index arrays is wanted.
+ *      plan (optional, may be NULL): receives the work plan of this batch's
+ *      response-packed domain (see tppo_plan_build), ready for tppo_egae* and
+ *      the loss entry points; plan_bytes >= tppo_plan_bytes(n_tok, B), since the
+ *      number of window tokens is not known to the host before the call.
  * Errors: NULL required pointer, B < 0, n_tok < 0, capacity < 0 ->
  *      TPPO_ERR_NULL / TPPO_ERR_SIZE; tail_drop < 0 -> TPPO_ERR_PARAM.
  *      B = 0 is valid (counts = 0).  Sequences with a bad layout set
@@ -106,7 +115,31 @@ int tppo_select(const int32_t* cu_seqlens, const int32_t* ctx_len, const int32_t
                 int32_t* resp_off, int32_t* sel_off, int32_t* keep_len,
                 int32_t* sel_rows, int32_t* sel_targets, int32_t* sel_resp_idx,
                 int64_t capacity, int64_t* counts, void* workspace, size_t workspace_bytes,
-                int32_t* status, void* stream);
+                void* plan, size_t plan_bytes, int32_t* status, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * tppo_plan_build -- the work plan of a batch layout: the response-packed
+ * domain cut into tiles of <= 1024 tokens of one sequence, the sizes of the
+ * policy / value token sets of Sec. 3.2, and zeroed words through which the
+ * workgroups of a later launch hand partial results to each other.  Every
+ * entry point below that takes `plan` builds the same thing in its workspace
+ * when plan is NULL; building it once per batch (here, or as a by-product of
+ * tppo_select) saves each of them that launch.
+ *
+ * in : resp_off[B+1], done[B] int32; keep_len[B] int32 or NULL (a plan built
+ *      without keep_len serves tppo_egae* only).
+ * out: plan, tppo_plan_bytes(n_resp, B) bytes, 256-byte aligned.  It stays
+ *      valid for any number of calls with the same resp_off / keep_len / done;
+ *      calls that use one plan must not overlap in time.  Under HIP graph
+ *      capture, capture the call that builds a plan together with the calls
+ *      that use it (a replayed launch repeats its call number).
+ * A consumer given a plan that was built for other sizes sets
+ * TPPO_STATUS_BAD_LAYOUT and computes nothing.
+ */
+size_t tppo_plan_bytes(int64_t n_resp, int64_t B);
+int tppo_plan_build(const int32_t* resp_off, const int32_t* keep_len, const int32_t* done,
+                    int64_t B, int64_t n_resp, void* plan, size_t plan_bytes,
+                    int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------
  * tppo_token_logprobs -- log-probability of each kept token under the current
@@ -159,6 +192,9 @@ int tppo_token_logprobs(const void* hidden, int64_t n_rows, int64_t H, int64_t l
  *      of the rollout-time critic; resp_off[B+1], done[B] int32;
  *      bootstrap[B] fp32 or NULL.
  * out: adv[n_resp], ret[n_resp] fp32.  May not alias the inputs.
+ * workspace / plan: with plan = NULL the call builds its own plan in workspace
+ *      (tppo_egae_workspace_bytes); with a plan of this layout (tppo_select,
+ *      tppo_plan_build) the workspace is not used and may be NULL.
  * Errors: gamma or lambda outside [0,1] -> TPPO_ERR_PARAM; negative sizes ->
  *      TPPO_ERR_SIZE.  n_resp = 0 is valid.  resp_off must be non-decreasing
  *      with resp_off[0] = 0 and resp_off[B] = n_resp (empty sequences allowed).
@@ -168,7 +204,7 @@ int tppo_egae(const float* rewards, const float* values, const int32_t* resp_off
               const int32_t* done, const float* bootstrap,
               int64_t B, int64_t n_resp, float gamma, float lambda,
               float* adv, float* ret, void* workspace, size_t workspace_bytes,
-              int32_t* status, void* stream);
+              void* plan, int32_t* status, void* stream);
 
 /* tppo_egae_terminal -- the same with the sparse reward of Sec. 2.1 (one
  * rule-based reward at the end of a finished response, nothing else): instead
@@ -181,7 +217,7 @@ int tppo_egae_terminal(const float* terminal_reward, const float* values, const 
                        const int32_t* done, const float* bootstrap,
                        int64_t B, int64_t n_resp, float gamma, float lambda,
                        float* adv, float* ret, void* workspace, size_t workspace_bytes,
-                       int32_t* status, void* stream);
+                       void* plan, int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------
  * tppo_ppo_losses -- token-level losses (Sec. 4.1.1) of one update:
@@ -193,14 +229,16 @@ int tppo_egae_terminal(const float* terminal_reward, const float* values, const 
  *   value_loss = value_sum / n_value               (= J_value, Eq. (valueloss))
  * Policy tokens of sequence i: window tokens t < keep_len[i]; value tokens: all
  * window tokens of sequences with done[i] != 0 (Sec. 3.2).  Entries outside a
- * set are not read, so whatever they hold cannot influence the result.  Empty
- * sets give a loss of 0.  The un-normalised sums and counts let the caller
+ * set are not read, so whatever they hold cannot influence the result.  An
+ * entry INSIDE a set that is not a number is not clipped away: that loss is
+ * NaN.  Empty sets give a loss of 0.  The un-normalised sums and counts let the caller
  * combine minibatches.  Reductions are deterministic (no float atomics).
  *
  * in : six fp32 arrays [n_resp], response-packed; the three policy arrays
  *      (logp_new, logp_old, adv) may all be NULL to skip the policy half,
  *      likewise (v_new, v_old, ret); resp_off[B+1], keep_len[B], done[B] int32.
  * out: one tppo_loss_out in device memory.
+ * workspace / plan: as for tppo_egae (the plan must have been built with keep_len).
  * Errors: eps or xi negative -> TPPO_ERR_PARAM; a half with only some of its
  *      arrays NULL -> TPPO_ERR_NULL.
  */
@@ -216,7 +254,7 @@ int tppo_ppo_losses(const float* logp_new, const float* logp_old, const float* a
                     int64_t B, int64_t n_resp,
                     float eps_low, float eps_high, float xi_low, float xi_high,
                     tppo_loss_out* out, void* workspace, size_t workspace_bytes,
-                    int32_t* status, void* stream);
+                    void* plan, int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------
  * tppo_ppo_losses_backward -- the step after the losses in Alg. 1 (policy and
@@ -236,7 +274,9 @@ int tppo_ppo_losses(const float* logp_new, const float* logp_old, const float* a
  * N_policy / N_value are this call's token counts (token-level mean, Sec.
  * 4.1.1) unless policy_denominator / value_denominator > 0 replace them (a
  * batch spread over several calls or devices).  Sets, masking by selection and
- * determinism as in tppo_ppo_losses.  Decisions are taken in fp32.
+ * determinism as in tppo_ppo_losses.  Decisions are taken in fp32.  A token of
+ * a set with a NaN among its inputs gets the derivative NaN and counts neither
+ * as clipped nor as unclipped.
  *
  * in : as tppo_ppo_losses, plus the two scales (finite) and denominators.
  * out: grad_logp[n_resp], grad_v[n_resp] device fp32, every element written
@@ -264,7 +304,7 @@ int tppo_ppo_losses_backward(const float* logp_new, const float* logp_old, const
                              float* grad_logp, float* grad_v,
                              tppo_loss_out* out, tppo_loss_stats* stats,
                              void* workspace, size_t workspace_bytes,
-                             int32_t* status, void* stream);
+                             void* plan, int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------
  * tppo_token_logprobs_backward -- derivatives of the kept tokens' log-probs

@@ -23,22 +23,24 @@ _SIGNATURES = {
     "tppo_version": (ctypes.c_int, []),
     "tppo_select_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
     "tppo_select": (ctypes.c_int, [_c_ptr] * 4 + [_c_i64, _c_i64, _c_i32] + [_c_ptr] * 6 +
-                    [_c_i64, _c_ptr, _c_ptr, _c_size, _c_ptr, _c_ptr]),
+                    [_c_i64, _c_ptr, _c_ptr, _c_size, _c_ptr, _c_size, _c_ptr, _c_ptr]),
+    "tppo_plan_bytes": (_c_size, [_c_i64, _c_i64]),
+    "tppo_plan_build": (ctypes.c_int, [_c_ptr] * 3 + [_c_i64, _c_i64, _c_ptr, _c_size, _c_ptr, _c_ptr]),
     "tppo_token_logprobs_workspace_bytes": (_c_size, [_c_i64, _c_i64, _c_i64, ctypes.c_int]),
     "tppo_token_logprobs": (ctypes.c_int, [_c_ptr, _c_i64, _c_i64, _c_i64, _c_ptr, _c_i64, _c_i64,
                                            ctypes.c_int, _c_ptr, _c_ptr, _c_i64, _c_ptr, _c_ptr,
                                            _c_ptr, _c_ptr, _c_ptr, _c_size, _c_ptr, _c_ptr]),
     "tppo_egae_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
     "tppo_egae": (ctypes.c_int, [_c_ptr] * 5 + [_c_i64, _c_i64, _c_f32, _c_f32, _c_ptr, _c_ptr,
-                                                _c_ptr, _c_size, _c_ptr, _c_ptr]),
+                                                _c_ptr, _c_size, _c_ptr, _c_ptr, _c_ptr]),
     "tppo_egae_terminal": (ctypes.c_int, [_c_ptr] * 5 + [_c_i64, _c_i64, _c_f32, _c_f32, _c_ptr, _c_ptr,
-                                                         _c_ptr, _c_size, _c_ptr, _c_ptr]),
+                                                         _c_ptr, _c_size, _c_ptr, _c_ptr, _c_ptr]),
     "tppo_ppo_losses_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
     "tppo_ppo_losses": (ctypes.c_int, [_c_ptr] * 9 + [_c_i64, _c_i64] + [_c_f32] * 4 +
-                        [_c_ptr, _c_ptr, _c_size, _c_ptr, _c_ptr]),
+                        [_c_ptr, _c_ptr, _c_size, _c_ptr, _c_ptr, _c_ptr]),
     "tppo_ppo_losses_backward_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
     "tppo_ppo_losses_backward": (ctypes.c_int, [_c_ptr] * 9 + [_c_i64, _c_i64] + [_c_f32] * 6 +
-                                 [_c_i64, _c_i64] + [_c_ptr] * 5 + [_c_size, _c_ptr, _c_ptr]),
+                                 [_c_i64, _c_i64] + [_c_ptr] * 5 + [_c_size, _c_ptr, _c_ptr, _c_ptr]),
     "tppo_token_logprobs_backward_workspace_bytes": (_c_size, [_c_i64, _c_i64, _c_i64, ctypes.c_int]),
     "tppo_token_logprobs_backward": (ctypes.c_int, [_c_ptr, _c_i64, _c_i64, _c_i64, _c_ptr, _c_i64, _c_i64,
                                                     ctypes.c_int, _c_ptr, _c_ptr, _c_i64, _c_ptr, _c_ptr,
@@ -105,10 +107,11 @@ def new_status(device):
 
 
 def tppo_select(cu_seqlens, ctx_len, done, input_ids, tail_drop, capacity=None, status=None,
-                want_indices=True, n_tok=None, workspace=None):
+                want_indices=True, n_tok=None, workspace=None, want_plan=False, plan=None):
     """Token filter.  Returns a dict of device tensors: resp_off, sel_off, keep_len,
     sel_rows, sel_targets, sel_resp_idx (capacity-sized) and counts (int64[3] =
-    M, n_resp, N_val)."""
+    M, n_resp, N_val); with ``want_plan`` (or a ``plan`` buffer) also ``plan``, the
+    work plan that tppo_egae* and the loss calls take."""
     lib = load()
     dev = cu_seqlens.device
     B = ctx_len.numel()
@@ -128,14 +131,30 @@ def tppo_select(cu_seqlens, ctx_len, done, input_ids, tail_drop, capacity=None, 
     ws = workspace
     if ws is None and want_indices:
         ws = _workspace(lib.tppo_select_workspace_bytes(B, max(cap, n_tok)), dev)
+    if plan is None and want_plan:
+        plan = _workspace(lib.tppo_plan_bytes(n_tok, B), dev)
+    out["plan"] = plan
     rc = lib.tppo_select(_ptr(_dev_i32(cu_seqlens)), _ptr(_dev_i32(ctx_len)), _ptr(_dev_i32(done)),
                          _ptr(input_ids), B, n_tok, int(tail_drop),
                          _ptr(out["resp_off"]), _ptr(out["sel_off"]), _ptr(out["keep_len"]),
                          _ptr(out.get("sel_rows")), _ptr(out.get("sel_targets")),
                          _ptr(out.get("sel_resp_idx")), cap, _ptr(out["counts"]), _ptr(ws),
-                         0 if ws is None else ws.numel(), _ptr(status), _stream())
+                         0 if ws is None else ws.numel(), _ptr(plan), 0 if plan is None else plan.numel(),
+                         _ptr(status), _stream())
     _check(rc, "tppo_select")
     return out
+
+
+def tppo_plan_build(resp_off, keep_len, done, n_resp, status=None, plan=None):
+    """Work plan of a batch layout (keep_len may be None: such a plan serves tppo_egae* only)."""
+    lib = load()
+    B = done.numel()
+    if plan is None:
+        plan = _workspace(lib.tppo_plan_bytes(int(n_resp), B), resp_off.device)
+    rc = lib.tppo_plan_build(_ptr(_dev_i32(resp_off)), _ptr(keep_len), _ptr(_dev_i32(done)), B, int(n_resp),
+                             _ptr(plan), plan.numel(), _ptr(status), _stream())
+    _check(rc, "tppo_plan_build")
+    return plan
 
 
 def tppo_token_logprobs(hidden, w_head, sel_rows, sel_targets, M=None, m_actual=None,
@@ -162,34 +181,40 @@ def tppo_token_logprobs(hidden, w_head, sel_rows, sel_targets, M=None, m_actual=
     return logp, lse
 
 
+def _scratch(lib_bytes, n_resp, B, workspace, plan, device):
+    """The workspace of a call that may have been given a plan instead."""
+    if plan is not None or workspace is not None:
+        return workspace
+    return _workspace(lib_bytes(n_resp, B), device)
+
+
 def tppo_egae(rewards, values, resp_off, done, gamma, lam, bootstrap=None, status=None,
-              workspace=None, out=None):
+              workspace=None, out=None, plan=None):
     """Extended GAE advantages and Monte-Carlo returns.  Returns (adv, ret)."""
     lib = load()
     n_resp, B = rewards.numel(), done.numel()
     adv, ret = out if out is not None else (torch.empty_like(rewards), torch.empty_like(rewards))
-    ws_bytes = lib.tppo_egae_workspace_bytes(n_resp, B)
-    ws = _workspace(ws_bytes, rewards.device) if workspace is None else workspace
+    ws = _scratch(lib.tppo_egae_workspace_bytes, n_resp, B, workspace, plan, rewards.device)
     rc = lib.tppo_egae(_ptr(_dev_f32(rewards)), _ptr(_dev_f32(values)), _ptr(_dev_i32(resp_off)),
                        _ptr(_dev_i32(done)), _ptr(bootstrap), B, n_resp, float(gamma), float(lam),
-                       _ptr(adv), _ptr(ret), _ptr(ws), ws.numel(), _ptr(status), _stream())
+                       _ptr(adv), _ptr(ret), _ptr(ws), 0 if ws is None else ws.numel(), _ptr(plan),
+                       _ptr(status), _stream())
     _check(rc, "tppo_egae")
     return adv, ret
 
 
 def tppo_egae_terminal(terminal_reward, values, resp_off, done, gamma, lam, bootstrap=None, status=None,
-                       workspace=None, out=None):
+                       workspace=None, out=None, plan=None):
     """Extended GAE with one terminal reward per finished sequence instead of a
     dense reward array.  Returns (adv, ret)."""
     lib = load()
     n_resp, B = values.numel(), done.numel()
     adv, ret = out if out is not None else (torch.empty_like(values), torch.empty_like(values))
-    ws_bytes = lib.tppo_egae_workspace_bytes(n_resp, B)
-    ws = _workspace(ws_bytes, values.device) if workspace is None else workspace
+    ws = _scratch(lib.tppo_egae_workspace_bytes, n_resp, B, workspace, plan, values.device)
     rc = lib.tppo_egae_terminal(_ptr(_dev_f32(terminal_reward)), _ptr(_dev_f32(values)),
                                 _ptr(_dev_i32(resp_off)), _ptr(_dev_i32(done)), _ptr(bootstrap), B, n_resp,
-                                float(gamma), float(lam), _ptr(adv), _ptr(ret), _ptr(ws), ws.numel(),
-                                _ptr(status), _stream())
+                                float(gamma), float(lam), _ptr(adv), _ptr(ret), _ptr(ws),
+                                0 if ws is None else ws.numel(), _ptr(plan), _ptr(status), _stream())
     _check(rc, "tppo_egae_terminal")
     return adv, ret
 
@@ -201,7 +226,7 @@ class LossOut(ctypes.Structure):
 
 
 def tppo_ppo_losses(logp_new, logp_old, adv, v_new, v_old, ret, resp_off, keep_len, done,
-                    eps_low, eps_high, xi_low, xi_high, status=None, workspace=None, out=None):
+                    eps_low, eps_high, xi_low, xi_high, status=None, workspace=None, out=None, plan=None):
     """Clipped policy / value losses.  Returns a 32-byte device tensor holding a
     ``tppo_loss_out``; ``read_loss_out`` copies it to the host."""
     lib = load()
@@ -209,13 +234,12 @@ def tppo_ppo_losses(logp_new, logp_old, adv, v_new, v_old, ret, resp_off, keep_l
     B = done.numel()
     n_resp = (logp_new if logp_new is not None else v_new).numel()
     res = torch.empty(ctypes.sizeof(LossOut), dtype=torch.uint8, device=dev) if out is None else out
-    ws_bytes = lib.tppo_ppo_losses_workspace_bytes(n_resp, B)
-    ws = _workspace(ws_bytes, dev) if workspace is None else workspace
+    ws = _scratch(lib.tppo_ppo_losses_workspace_bytes, n_resp, B, workspace, plan, dev)
     rc = lib.tppo_ppo_losses(_ptr(logp_new), _ptr(logp_old), _ptr(adv), _ptr(v_new), _ptr(v_old),
                              _ptr(ret), _ptr(_dev_i32(resp_off)), _ptr(_dev_i32(keep_len)),
                              _ptr(_dev_i32(done)), B, n_resp, float(eps_low), float(eps_high),
-                             float(xi_low), float(xi_high), _ptr(res), _ptr(ws), ws.numel(),
-                             _ptr(status), _stream())
+                             float(xi_low), float(xi_high), _ptr(res), _ptr(ws),
+                             0 if ws is None else ws.numel(), _ptr(plan), _ptr(status), _stream())
     _check(rc, "tppo_ppo_losses")
     return res
 
@@ -327,7 +351,7 @@ class LossStats(ctypes.Structure):
 def tppo_ppo_losses_backward(logp_new, logp_old, adv, v_new, v_old, ret, resp_off, keep_len, done,
                              eps_low, eps_high, xi_low, xi_high, policy_scale=1.0, value_scale=1.0,
                              policy_denominator=0, value_denominator=0, status=None, workspace=None,
-                             out=None, stats=None, grads=None):
+                             out=None, stats=None, grads=None, plan=None):
     """Derivatives of the two losses (plus the losses and clip statistics) in one
     pass.  Returns (grad_logp, grad_v, loss_out tensor, stats tensor)."""
     lib = load()
@@ -341,14 +365,13 @@ def tppo_ppo_losses_backward(logp_new, logp_old, adv, v_new, v_old, ret, resp_of
         g_lp, g_v = grads
     res = torch.empty(ctypes.sizeof(LossOut), dtype=torch.uint8, device=dev) if out is None else out
     st = torch.empty(ctypes.sizeof(LossStats), dtype=torch.uint8, device=dev) if stats is None else stats
-    ws_bytes = lib.tppo_ppo_losses_backward_workspace_bytes(n_resp, B)
-    ws = _workspace(ws_bytes, dev) if workspace is None else workspace
+    ws = _scratch(lib.tppo_ppo_losses_backward_workspace_bytes, n_resp, B, workspace, plan, dev)
     rc = lib.tppo_ppo_losses_backward(
         _ptr(logp_new), _ptr(logp_old), _ptr(adv), _ptr(v_new), _ptr(v_old), _ptr(ret),
         _ptr(_dev_i32(resp_off)), _ptr(_dev_i32(keep_len)), _ptr(_dev_i32(done)), B, n_resp,
         float(eps_low), float(eps_high), float(xi_low), float(xi_high), float(policy_scale),
         float(value_scale), int(policy_denominator), int(value_denominator), _ptr(g_lp), _ptr(g_v),
-        _ptr(res), _ptr(st), _ptr(ws), ws.numel(), _ptr(status), _stream())
+        _ptr(res), _ptr(st), _ptr(ws), 0 if ws is None else ws.numel(), _ptr(plan), _ptr(status), _stream())
     _check(rc, "tppo_ppo_losses_backward")
     return g_lp, g_v, res, st
 

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtppo.so")
-SOURCES = ["select.hip", "egae.hip", "losses.hip", "head.hip", "head_bwd.hip", "value_head.hip", "diag.hip",
+SOURCES = ["plan.hip", "select.hip", "egae.hip", "losses.hip", "head.hip", "head_bwd.hip", "value_head.hip", "diag.hip",
            "batcher.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

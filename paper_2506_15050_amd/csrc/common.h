@@ -25,6 +25,18 @@ __device__ __forceinline__ void set_status(int32_t* status, int32_t bit) {
     if (status) atomicOr(status, bit);
 }
 
+// Loads of wave-uniform values through the scalar data cache (read-only data written before the launch):
+// they take a fraction of a vector load's latency and leave the vector memory queue to the streaming loads.
+__device__ __forceinline__ int32_t load_uniform(const int32_t* p) {
+    return *(const int32_t __attribute__((address_space(4)))*)(p);
+}
+__device__ __forceinline__ float load_uniform(const float* p) {
+    return *(const float __attribute__((address_space(4)))*)(p);
+}
+__device__ __forceinline__ long long load_uniform(const long long* p) {
+    return *(const long long __attribute__((address_space(4)))*)(p);
+}
+
 // largest s in [lo, hi] with off[s] <= p  (off non-decreasing, off[lo] <= p)
 __device__ __forceinline__ int find_segment(const int32_t* off, int lo, int hi, int p) {
     while (lo < hi) {

@@ -1,211 +1,123 @@
 // tppo_egae: Extended GAE (Eq. (egae), Sec. 3.1) and returns R_t (Sec. 2.4) as
 // one segmented reverse scan over the response-packed token array.
 //
-// Both recurrences are affine in the value carried in from the right:
+// Both recurrences are affine in the value carried in from the right, with a
+// CONSTANT multiplier:
 //   A_t = delta_t + (gamma*lambda) A_{t+1},   R_t = r_t + gamma R_{t+1},
 // and restart at the last token of every sequence (where the bootstrap value of
-// Sec. 3.1 enters delta).  The tokens are cut into chunks of <= 2048 tokens that
-// never straddle two sequences (chunks.h); a small kernel lists them in
-// right-to-left processing order.  A persistent grid of workgroups then walks
-// the list; for each chunk a workgroup
-//   1. loads r, V (8 B/token; the loads of its NEXT chunk are already in flight
-//      while it works on this one), composes its tokens' affine maps per
-//      thread, across the wavefront with shuffles, across wavefronts via LDS;
-//   2. publishes "value at my first token if nothing is carried in" for A and
-//      R ({flag, float} words, two per quantity: hi + lo of an fp64);
-//   3. if the sequence continues to its right, sums the published words of the
-//      following chunks of the sequence, weighted by (gamma*lambda)^n resp.
-//      gamma^n.  Those words depend on no other chunk, so there is no chain of
-//      waits; the chunks to the right come earlier in the list, so they were
-//      started earlier by a co-resident workgroup; the wait is bounded anyway;
-//   4. replays its tokens with the carry and stores A, R (8 B/token).
-// HBM traffic is the algorithmic 16 B/token plus 16 B per chunk of metadata.
+// Sec. 3.1 enters delta).  So a run of n tokens acts on what is carried in as
+// x -> m^n x + b, and only the b's have to be scanned.
 //
-// Arithmetic: inputs and outputs are fp32; the TD residuals, the affine maps and
-// every partial sum are fp64.  With gamma*lambda close to 1 a sequence sums up
-// to tens of thousands of residuals whose individual fp32 rounding errors would
-// add up (random walk) beyond 1e-5; the kernel is bound by HBM, not by the ALUs,
-// so fp64 costs nothing measurable.
+// Work unit: one wavefront per tile of <= 1024 tokens of one sequence (plan.h),
+// one tile per workgroup, no barriers.
+//   * Loads and stores keep consecutive lanes on consecutive 16 bytes (the only
+//     shape that streams at full rate), non-temporal, since every byte is
+//     touched once.  A lane therefore owns, in each of 4 "slots", 4 consecutive
+//     tokens; slot j is tokens 256 j .. 256 j + 255 of the tile.
+//   * Lanes hold the 16-byte groups of a slot in REVERSE order (lane 0 the
+//     highest addresses), so the right-to-left recurrence is a left-to-right
+//     prefix scan over lanes, which the data-parallel primitives do without the
+//     LDS crossbar: row_shr 1, 2, 4, 8, then row_bcast 15 and 31, each step one
+//     fused multiply-add with the matching power of m^4.
+//   * The four slots are chained by three scalar steps; the tile publishes
+//     "value at my first token with nothing carried in" ({tag, float} words,
+//     hi + lo of an fp64); a tile whose sequence continues to the right sums the
+//     words of the (up to 64) following tiles with weights m^(1024 j), one per
+//     lane.  Those words depend on no other tile, so there is no chain of waits.
+//     Only a sequence of more than 65 tiles chains: there the 64th tile to the
+//     right supplies its value with everything beyond included, which it
+//     publishes once its own look-back is done.  The tiles waited for stand
+//     earlier in the plan's list, which is sorted so that they started long
+//     before (plan.h); they belong to lower workgroup ids in any case, so they
+//     run or have run, and the wait is bounded besides.
+//   * Second pass: replay each lane's 4-token runs from the value carried into
+//     them, store A and R.
+// HBM traffic is the algorithmic 16 B/token plus 16 B per tile of metadata.
+//
+// Arithmetic: inputs and outputs are fp32; TD residuals, partial sums and
+// multipliers are fp64 (full rate on this chip).  With gamma*lambda close to 1 a
+// sequence sums up to hundreds of thousands of residuals whose individual fp32
+// rounding errors would add up (random walk) beyond 1e-5.
 #include <math.h>
+#include <stdlib.h>
 
-#include "chunks.h"
+#include "plan.h"
 
 namespace tppo {
 
-constexpr int kSpinLimit = 1 << 22;
+constexpr int kSpinLimit = 1 << 20;
+#ifndef TPPO_EGAE_MIN_WAVES
+#define TPPO_EGAE_MIN_WAVES 4
+#endif
+constexpr int kEgaeMinWaves = TPPO_EGAE_MIN_WAVES;   // wavefronts per SIMD the register allocation aims at
+constexpr int kSlots = kTileTokens / 256;      // 16-byte groups per lane and array
+static_assert(kSlots == 4, "a tile is four slots of 64 lanes x 4 tokens");
 
-struct EgaeWs {
-    Chunk* chunks;                    // [cap]
-    unsigned long long* agg;          // [cap][4] {flag << 32 | float bits}: A hi, A lo, R hi, R lo
-    int32_t* n_chunks;                // [1]
+// wave-uniform powers of one recurrence's multiplier m, computed on the host
+struct ScanConsts {
+    double m;          // per token
+    double q[6];       // (m^4)^(2^i): a step of 1, 2, 4, 8, 16, 32 lanes
+    double q64;        // m^256: one slot
+    double qtile;      // m^1024: one tile
 };
 
-static inline size_t egae_ws_bytes(int64_t cap) {
-    return round_up((size_t)cap * sizeof(Chunk), 256) + round_up((size_t)cap * 32, 256) + 256;
+static ScanConsts make_consts(double m) {
+    ScanConsts s;
+    s.m = m;
+    for (int i = 0; i < 6; ++i) s.q[i] = pow(m, (double)(4 << i));
+    s.q64 = pow(m, 256.0);
+    s.qtile = pow(m, (double)kTileTokens);
+    return s;
 }
 
-__host__ __device__ __forceinline__ EgaeWs egae_ws(void* ws, int64_t cap) {
-    char* p = static_cast<char*>(ws);
-    EgaeWs w;
-    w.chunks = reinterpret_cast<Chunk*>(p);
-    p += ((size_t)cap * sizeof(Chunk) + 255) / 256 * 256;
-    w.agg = reinterpret_cast<unsigned long long*>(p);
-    p += ((size_t)cap * 32 + 255) / 256 * 256;
-    w.n_chunks = reinterpret_cast<int32_t*>(p);
+// data-parallel primitive move: lane i receives x of the lane the control word names; lanes without a
+// source (start of a row, a row that row_mask leaves out) receive 0
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ double dpp_move(double x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), kCtrl, kRowMask, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), kCtrl, kRowMask, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
+constexpr int kWaveShr1 = 0x138, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+
+__device__ __forceinline__ float wave_shr1(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), kWaveShr1, 0xF, 0xF, false));
+}
+
+__device__ __forceinline__ double read_lane63(double x) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), 63),
+                            __builtin_amdgcn_readlane(__double2loint(x), 63));
+}
+
+// per-lane powers of q = m^4: p = q^lane, w15 = q^(lane % 16 + 1), w31 = q^(lane % 32 + 1)
+struct LaneWeights { double p, w15, w31; };
+
+__device__ __forceinline__ LaneWeights lane_weights(const ScanConsts& s, int lane) {
+    LaneWeights w = {1.0, 1.0, 1.0};
+    if (s.m == 1.0) return w;                                    // wave-uniform
+    double a = 1.0;                                              // q^(lane % 16)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a = ((lane >> i) & 1) ? a * s.q[i] : a;
+    const double b = (lane & 16) ? a * s.q[4] : a;               // q^(lane % 32)
+    w.w15 = a * s.q[0];
+    w.w31 = b * s.q[0];
+    w.p = (lane & 32) ? b * s.q[5] : b;
     return w;
 }
 
-// the first `parts` workgroups build the chunk list; the others clear the published words
-__global__ __launch_bounds__(kBuildThreads) void egae_init_kernel(const int32_t* __restrict__ resp_off,
-                                                                  int B, int n_resp, int cap, int parts,
-                                                                  void* ws_raw, int32_t* status) {
-    EgaeWs ws = egae_ws(ws_raw, cap);
-    if ((int)blockIdx.x < parts) {
-        build_chunks(resp_off, B, n_resp, ws.chunks, cap, ws.n_chunks, status, blockIdx.x, parts);
-    } else {
-        const int64_t words = (int64_t)cap * 4;
-        for (int64_t i = (int64_t)(blockIdx.x - parts) * kBuildThreads + threadIdx.x; i < words;
-             i += (int64_t)(gridDim.x - parts) * kBuildThreads)
-            ws.agg[i] = 0ull;
-    }
+// inclusive scan over the lanes of x_l = b_l + q x_{l-1}
+__device__ __forceinline__ double lane_scan(double b, const ScanConsts& s, const LaneWeights& w) {
+    b = fma(s.q[0], dpp_move<kRowShr1, 0xF>(b), b);
+    b = fma(s.q[1], dpp_move<kRowShr2, 0xF>(b), b);
+    b = fma(s.q[2], dpp_move<kRowShr4, 0xF>(b), b);
+    b = fma(s.q[3], dpp_move<kRowShr8, 0xF>(b), b);
+    b = fma(w.w15, dpp_move<kRowBcast15, 0xA>(b), b);            // lane 15 / 47 into rows 1 / 3
+    b = fma(w.w31, dpp_move<kRowBcast31, 0xC>(b), b);            // lane 31 into rows 2 and 3
+    return b;
 }
 
-struct Affine { double a, b; };   // x -> a*x + b
-
-// f then g in scan order (f is the earlier token range): f(g(x))
-__device__ __forceinline__ Affine compose(Affine f, Affine g) {
-    return {f.a * g.a, fma(f.a, g.b, f.b)};
-}
-
-__device__ __forceinline__ Affine shfl_down(Affine f, int off) {
-    return {__shfl_down(f.a, off), __shfl_down(f.b, off)};
-}
-
-__device__ __forceinline__ unsigned long long pack_word(float v) {
-    return (1ull << 32) | (unsigned long long)__float_as_uint(v);
-}
-
-// a double travels as two fp32 words (hi + lo), each with its own flag
-__device__ __forceinline__ void publish(unsigned long long* p, double x) {
-    const float hi = (float)x, lo = (float)(x - (double)hi);
-    __hip_atomic_store(p, pack_word(hi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(p + 1, pack_word(lo), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Bounded wait for the four words of one chunk (A hi, A lo, R hi, R lo).  All
-// four loads of a poll are issued together, so a poll costs one memory round
-// trip, not four.
-__device__ __forceinline__ void wait_words(unsigned long long* p, double& a, double& r, int32_t* status) {
-    for (int spin = 0; spin < kSpinLimit; ++spin) {
-        const unsigned long long w0 = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long w1 = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long w2 = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long w3 = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((w0 >> 32) && (w1 >> 32) && (w2 >> 32) && (w3 >> 32)) {
-            a = (double)__uint_as_float((unsigned)w0) + (double)__uint_as_float((unsigned)w1);
-            r = (double)__uint_as_float((unsigned)w2) + (double)__uint_as_float((unsigned)w3);
-            return;
-        }
-        __builtin_amdgcn_s_sleep(1);
-    }
-    set_status(status, TPPO_STATUS_TIMEOUT);
-    a = 0.0;
-    r = 0.0;
-}
-
-typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte access, 4-byte aligned
-
-constexpr int kEgaeThreads = 128;                       // 2 wavefronts, 16 tokens per thread:
-constexpr int kTpt = kChunkTokens / kEgaeThreads;       // the per-wavefront scan is paid once per 1024 tokens
-constexpr int kEgaeWaves = kEgaeThreads / kWave;
-constexpr int kEgaeMaxGroups = 1536;                    // 6 workgroups per CU: all co-resident (<= 168 VGPRs)
-
-struct TokenRegs { float r[kTpt], v[kTpt]; };
-
-// Global memory is streamed with consecutive lanes on consecutive 16 bytes (the
-// shape that runs at copy speed); the scan wants kTpt consecutive tokens per
-// thread.  The two layouts are exchanged through LDS.  A thread's kTpt floats
-// occupy 80 bytes there (64 + 16 of padding), which makes both the 16-byte
-// writes in token order and the 16-byte reads in thread order conflict-free.
-constexpr int kLdsRun = kTpt + 4;                          // floats per thread run, padded
-constexpr int kLdsArray = kEgaeThreads * kLdsRun;          // floats per staged array
-constexpr int kGroups = kChunkTokens / (4 * kEgaeThreads); // 16-byte groups per thread and array: 4
-
-__device__ __forceinline__ int lds_slot(int token) { return (token / kTpt) * kLdsRun + (token % kTpt); }
-
-struct Raw { float4u r[kGroups], v[kGroups]; float v_after; };
-
-// issue the global loads of a chunk: group g of thread tid = tokens g*512 + tid*4 .. +3.
-// kTerminal: there is no reward array; the only reward is terminal[seq] on the last token
-// of a finished sequence (Sec. 2.1: the rule-based reward arrives with the end of the response).
-template <bool kTerminal>
-__device__ __forceinline__ void load_raw(Raw& x, const float* __restrict__ rewards,
-                                         const float* __restrict__ values, const Chunk& ch,
-                                         const int32_t* __restrict__ done, int tid) {
-    const int start = ch.start, len = ch.len();
-#pragma unroll
-    for (int g = 0; g < kGroups; ++g) {
-        const int k0 = g * 4 * kEgaeThreads + tid * 4;
-        if (k0 + 4 <= len) {
-            if (!kTerminal) x.r[g] = *reinterpret_cast<const float4u*>(rewards + start + k0);
-            x.v[g] = *reinterpret_cast<const float4u*>(values + start + k0);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool ok = k0 + e < len;
-                if (!kTerminal) x.r[g][e] = ok ? rewards[start + k0 + e] : 0.f;
-                x.v[g][e] = ok ? values[start + k0 + e] : 0.f;
-            }
-        }
-        if (kTerminal) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) x.r[g][e] = 0.f;
-            const int last = len - 1 - k0;                          // the chunk's last token, if it is in this group
-            if (ch.after == 0 && last >= 0 && last < 4 && done[ch.seg] != 0) {
-                const float t = rewards[ch.seg];                    // `rewards` is terminal[B] in this mode
-#pragma unroll
-                for (int e = 0; e < 4; ++e) x.r[g][e] = e == last ? t : 0.f;
-            }
-        }
-    }
-}
-
-// token order -> LDS (call, then __syncthreads, then read_runs)
-__device__ __forceinline__ void stage_raw(const Raw& x, float* s_r, float* s_v, int tid) {
-#pragma unroll
-    for (int g = 0; g < kGroups; ++g) {
-        const int slot = lds_slot(g * 4 * kEgaeThreads + tid * 4);
-        *reinterpret_cast<float4*>(s_r + slot) = make_float4(x.r[g][0], x.r[g][1], x.r[g][2], x.r[g][3]);
-        *reinterpret_cast<float4*>(s_v + slot) = make_float4(x.v[g][0], x.v[g][1], x.v[g][2], x.v[g][3]);
-    }
-}
-
-__device__ __forceinline__ void read_runs(TokenRegs& t, const float* s_r, const float* s_v, int tid) {
-#pragma unroll
-    for (int q = 0; q < kTpt / 4; ++q) {
-        const float4 rr = *reinterpret_cast<const float4*>(s_r + tid * kLdsRun + 4 * q);
-        const float4 vv = *reinterpret_cast<const float4*>(s_v + tid * kLdsRun + 4 * q);
-        t.r[4 * q] = rr.x; t.r[4 * q + 1] = rr.y; t.r[4 * q + 2] = rr.z; t.r[4 * q + 3] = rr.w;
-        t.v[4 * q] = vv.x; t.v[4 * q + 1] = vv.y; t.v[4 * q + 2] = vv.z; t.v[4 * q + 3] = vv.w;
-    }
-}
-
-// V(s_{t+1}) for a chunk's last token (held by the last thread only): the next
-// chunk's first value, or the value of the state after the sequence -- 0 for a
-// finished one, else the bootstrap value, by default V(s_{l-1}) (Sec. 3.1)
-__device__ __forceinline__ float load_v_after(const Chunk& ch, const float* __restrict__ values,
-                                              const int32_t* __restrict__ done,
-                                              const float* __restrict__ bootstrap, int tid) {
-    float v = 0.f;
-    if (tid == kEgaeThreads - 1) {
-        const int end = ch.start + ch.len();
-        if (ch.after != 0) v = values[end];
-        else if (done[ch.seg] == 0) v = bootstrap ? bootstrap[ch.seg] : values[end - 1];
-    }
-    return v;
-}
-
-// x^n for a small non-negative integer n (0^0 = 1)
+// x^n for a non-negative integer n (0^0 = 1)
 __device__ __forceinline__ double powi(double x, int n) {
     double r = 1.0;
     while (n > 0) {
@@ -216,189 +128,428 @@ __device__ __forceinline__ double powi(double x, int n) {
     return r;
 }
 
-// One thread's tokens.  kFull: all kTpt tokens exist (no per-token guards).
-//   pass 1 (kStore = false): the affine maps value-to-my-right -> value-at-my-first-token
-//   pass 2 (kStore = true):  the values themselves, from the true value to my right
-// The sequence's last token needs no special case: nothing follows it in its
-// chunk, its map starts from a = 0 (set by the caller) and its V(s_{t+1}) is v_right.
-template <bool kFull, bool kStore>
-__device__ __forceinline__ void walk_tokens(const TokenRegs& tk, int n_mine, float v_right, double gamma,
-                                            double c, Affine& fa, Affine& fr, float* out_a, float* out_r) {
-    double v_next = (double)v_right;
+// Four tagged words as loaded: the two doubles they carry; true when all four belong to this call.
+__device__ __forceinline__ bool unpack_words(const unsigned long long (&w)[4], uint32_t tag, double& a, double& r) {
+    a = (double)__uint_as_float((unsigned)w[0]) + (double)__uint_as_float((unsigned)w[1]);
+    r = (double)__uint_as_float((unsigned)w[2]) + (double)__uint_as_float((unsigned)w[3]);
+    return (uint32_t)(w[0] >> 32) == tag && (uint32_t)(w[1] >> 32) == tag && (uint32_t)(w[2] >> 32) == tag &&
+           (uint32_t)(w[3] >> 32) == tag;
+}
+
+// Bounded wait for what a tile published (A hi, A lo, R hi, R lo).
+__device__ __forceinline__ void wait_words(const unsigned long long* p, uint32_t tag, double& a, double& r,
+                                           int32_t* status) {
+    for (int spin = 0; spin < kSpinLimit; ++spin) {
+        const bool ok_a = poll(p, tag, a), ok_r = poll(p + 2, tag, r);
+        if (ok_a && ok_r) return;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    set_status(status, TPPO_STATUS_TIMEOUT);
+    a = 0.0;
+    r = 0.0;
+}
+
+typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte access, 4-byte aligned
+
+struct EgaeParams {
+    const float* rewards;          // [n_resp], or with kTerminal the per-sequence terminal[B]
+    const float* values;
+    const int32_t* done;
+    const float* bootstrap;
+    float* adv;
+    float* ret;
+    void* plan;
+    int32_t* status;
+    int n_resp, B;
+    uint32_t tag;
+    double gamma;
+    ScanConsts sa, sr;             // multipliers gamma*lambda (advantages) and gamma (returns)
+#ifdef TPPO_TUNING
+    long long* prof;               // per-tile phase timestamps (tuning builds only)
+#endif
+};
+
+#ifdef TPPO_TUNING
+// timestamps stay in scalar registers until the tile is done: a store in mid-tile would sit in the same in-order
+// memory counter as the loads being timed
+#define TPPO_STAMP(k) do { g_stamp_local[k] = __builtin_amdgcn_s_memtime(); } while (0)
+#define TPPO_STAMPS_DECL unsigned long long g_stamp_local[8] = {0, 0, 0, 0, 0, 0, 0, 0}
+#define TPPO_STAMPS_ARG , unsigned long long (&g_stamp_local)[8]
+#define TPPO_STAMPS_PASS , g_stamp_local
+#define TPPO_STAMPS_FLUSH do { if (p.prof && lane == 0) { for (int k_ = 0; k_ < 8; ++k_) p.prof[(int64_t)pos * 8 + k_] = (long long)g_stamp_local[k_]; } } while (0)
+#else
+#define TPPO_STAMP(k) do { } while (0)
+#define TPPO_STAMPS_DECL do { } while (0)
+#define TPPO_STAMPS_ARG
+#define TPPO_STAMPS_PASS
+#define TPPO_STAMPS_FLUSH do { } while (0)
+#endif
+
+// bits of x where keep, else zero: a select the compiler cannot turn into a branch, and one that never lets a
+// NaN of a neighbouring sequence through (no multiplication by a mask)
+__device__ __forceinline__ float keep_if(float x, bool keep) {
+    return __int_as_float(__float_as_int(x) & (keep ? -1 : 0));
+}
+
+// A tile's inputs as loaded, with what the scalar side loads gave.
+struct TileIn {
+    float r[kSlots][4], v[kSlots][4];
+    float side_next, side_last, side_boot, side_term;   // see issue_tile
+    int side_done;
+    unsigned long long early[4];   // the words of the tile this lane looks back at, as they stood when the tile began
+    double look_a, look_r;         // what they carry
+    bool look_ok;                  // ... if they were this call's
+    Tile t;
+    int pos;
+};
+
+// where lane `lane` of a tile looks: lane l at the tile l + 1 places to the right (l full tiles lie in between);
+// if the sequence goes on beyond the 64th, that one's words with everything to its right included stand for
+// the rest.  Lanes with nobody to look at are pointed at the last tile there is (own tile if none): a valid
+// address whose contents they ignore.
+__device__ __forceinline__ const unsigned long long* look_at(const Plan& pl, const Tile& t, int lane) {
+    const bool rest = lane == kWave - 1 && t.after > kWave;
+    return pl.scan_words + (int64_t)kScanWords * (t.slot() + min(lane + 1, t.after)) + (rest ? 4 : 0);
+}
+
+// What pass 1 leaves for pass 2 in registers.  The tokens' own values with nothing carried into their run of 4
+// (32 floats per lane) wait in LDS meanwhile: the wavefront's private 8 KB, 16 bytes per lane and access,
+// consecutive lanes on consecutive 16 bytes, no barrier (one wavefront per workgroup).  That keeps the kernel
+// register count where 3 to 4 wavefronts fit a SIMD.
+struct TileMid {
+    double inc_a[kSlots], inc_r[kSlots];           // a run's value at its first token with nothing carried into the slot
+    double tot_a[kSlots], tot_r[kSlots];           // a slot's value at its first token (wave-uniform)
+};
+typedef float lds_float4 __attribute__((ext_vector_type(4)));
+
+// Issue the loads of tile `t` (list position `pos`).  Slot j, lane l holds tokens k0 .. k0 + 3,
+// k0 = 4 (64 j + 63 - l).  Every lane with a token issues ONE 16-byte load per array: a group that straddles
+// the tile's end reads on into the next sequence (the surplus is zeroed later), and the one group that would
+// read past the END OF THE ARRAY reads the array's last 16 bytes instead (moved into place later).  No branch
+// and no wait separates the loads, so all of them are in flight together.  kTerminal: there is no reward array;
+// the only reward is terminal[seq] on the last token of a finished sequence (Sec. 2.1: the rule-based reward
+// arrives with the end of the response).
+template <bool kTerminal>
+__device__ __forceinline__ void issue_tile(TileIn& x, const Tile& t, const EgaeParams& p, const Plan& pl, int pos,
+                                           int lane, int zero) {
+    const float* __restrict__ rewards = p.rewards;
+    const float* __restrict__ values = p.values;
+    x.pos = pos;
+    x.t = t;
+    const int start = x.t.start, len = x.t.len(), seg = x.t.seg;
 #pragma unroll
-    for (int k = kTpt - 1; k >= 0; --k) {
-        if (kFull || k < n_mine) {
-            const double vk = (double)tk.v[k], rk = (double)tk.r[k];
-            const double delta = fma(gamma, v_next, rk) - vk;
-            fa.b = fma(c, fa.b, delta);
-            fr.b = fma(gamma, fr.b, rk);
-            if (!kStore) {
-                fa.a *= c;
-                fr.a *= gamma;
-            }
-            v_next = vk;
+    for (int j = 0; j < kSlots; ++j) {
+        const int k0 = 4 * (64 * j + 63 - lane);
+        float4u vv = {0.f, 0.f, 0.f, 0.f}, rr = {0.f, 0.f, 0.f, 0.f};
+        if (k0 < len) {
+            const int at = min(start + k0, p.n_resp - 4);
+            vv = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(values + at));
+            if (!kTerminal) rr = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(rewards + at));
         }
-        if (kStore) {
-            out_a[k] = (float)fa.b;
-            out_r[k] = (float)fr.b;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x.v[j][e] = vv[e];
+            x.r[j][e] = rr[e];
+        }
+    }
+    // What Eq. (TD) needs for the tile's last token, fetched unconditionally, every lane the same address, as
+    // VECTOR loads that travel with the data (a scalar load that misses its cache was measured at three times
+    // their latency, and pass 1 cannot start without these): V of the token after the tile, V(s_{l-1}), the
+    // sequence's done flag, its bootstrap value, its terminal reward.  tile_front picks.  (`zero` is
+    // opaque_zero(): without it the compiler turns loads from a uniform address into scalar ones.)
+    const int seg_end = start + len;
+    x.side_next = values[min(seg_end, p.n_resp - 1) + zero];
+    x.side_last = values[seg_end - 1 + zero];
+    x.side_done = p.done[seg + zero];
+    x.side_boot = (p.bootstrap ? p.bootstrap + seg : values + start)[zero];
+    x.side_term = kTerminal ? rewards[seg + zero] : 0.f;
+    // The look-back's loads go out with the data's too, as ORDINARY cached loads.  The plan's list is sorted so
+    // that the tiles looked at published long ago; their words then come from memory like any other data.  (A
+    // load that must see other chiplets' latest stores -- device scope -- was measured at several times the
+    // latency of a plain one.)  Should a lane get here before its tile published, the line it fetched may stay
+    // in this chiplet's cache with the old contents; the tags say so, and tile_back then polls at device scope.
+    // A tag is never reused, so stale words are never mistaken for this call's.
+    const unsigned long long* look = look_at(pl, x.t, lane);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) x.early[q] = __hip_atomic_load(look + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+
+// Pass 1 of a tile, and the publication of its aggregate.  kFull: all 1024 tokens exist (every tile but a
+// sequence's last): no masks -- straight-line code.
+template <bool kTerminal, bool kFull>
+__device__ __forceinline__ void tile_front(TileIn& x, TileMid& m, lds_float4* s_loc, const EgaeParams& p,
+                                           const Plan& pl, int lane, const LaneWeights& wa,
+                                           const LaneWeights& wr TPPO_STAMPS_ARG) {
+    const double gamma = p.gamma, c = p.sa.m;
+    const int n_resp = p.n_resp, pos = x.pos;
+    const int start = x.t.start, len = kFull ? kTileTokens : x.t.len();
+    // V(s_{t+1}) of the tile's last token: the next tile's first value, or the value of the state after the
+    // sequence -- 0 for a finished one, else the bootstrap value, by default V(s_{l-1}) (Sec. 3.1)
+    const bool fin = x.side_done != 0;
+    const float v_end = x.t.after != 0 ? x.side_next : fin ? 0.f : p.bootstrap ? x.side_boot : x.side_last;
+    const float terminal = (kTerminal && x.t.after == 0 && fin) ? x.side_term : 0.f;
+    if (!kFull) {
+        if (__builtin_expect(start + len > n_resp - 4, 0)) {        // wave-uniform: the array's last tile
+#pragma unroll
+            for (int j = 0; j < kSlots; ++j) {
+                const int k0 = 4 * (64 * j + 63 - lane);
+                const int sh = k0 < len ? start + k0 - min(start + k0, n_resp - 4) : 0;
+                float tv[4], tr[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    tv[e] = x.v[j][e];
+                    tr[e] = x.r[j][e];
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    x.v[j][e] = sh == 0 ? tv[e] : sh == 1 ? tv[(e + 1) & 3] : sh == 2 ? tv[(e + 2) & 3] : tv[(e + 3) & 3];
+                    x.r[j][e] = sh == 0 ? tr[e] : sh == 1 ? tr[(e + 1) & 3] : sh == 2 ? tr[(e + 2) & 3] : tr[(e + 3) & 3];
+                }
+            }
+        }
+        // Tokens past the tile's end become r = 0, V = 0, except that the slot after the last token takes the
+        // value that follows the tile: then Eq. (TD) needs no special case for the last token, and the
+        // residuals of the padding are zeroed where they are computed.
+#pragma unroll
+        for (int j = 0; j < kSlots; ++j) {
+            const int k0 = 4 * (64 * j + 63 - lane);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x.r[j][e] = keep_if(x.r[j][e], k0 + e < len);
+                x.v[j][e] = k0 + e == len ? v_end : keep_if(x.v[j][e], k0 + e < len);
+            }
+        }
+    }
+    if (kTerminal) {
+#pragma unroll
+        for (int j = 0; j < kSlots; ++j) {
+            const int k0 = 4 * (64 * j + 63 - lane);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x.r[j][e] = keep_if(terminal, k0 + e == len - 1);
+        }
+    }
+    TPPO_STAMP(2);
+    // V of the token after each of my runs: my left neighbour's first value; for lane 0 the next slot's first
+    // value (held by lane 63) or, after the last slot, the value after the tile
+    float v_next_run[kSlots];
+#pragma unroll
+    for (int j = 0; j < kSlots; ++j) {
+        const float from_lane = wave_shr1(x.v[j][0]);
+        const float from_slot = j + 1 < kSlots
+            ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x.v[j + 1][0]), 63)) : v_end;
+        v_next_run[j] = lane == 0 ? from_slot : from_lane;
+    }
+    // Every run of 4 tokens as "values at its tokens with nothing carried in".  The chain is fp64; what a token
+    // keeps for pass 2 is rounded to fp32 (a sum over <= 4 tokens, used once), what is carried on (the run's
+    // value at its first token) stays fp64.  Then the runs are scanned over the lanes.
+#pragma unroll
+    for (int j = 0; j < kSlots; ++j) {
+        double ba = 0.0, br = 0.0;
+        if (kFull || 256 * j < len) {                               // wave-uniform: an empty slot stays zero
+            const int k0 = 4 * (64 * j + 63 - lane);
+            double vn = (double)v_next_run[j];
+            lds_float4 la, lr;
+#pragma unroll
+            for (int e = 3; e >= 0; --e) {
+                const double vk = (double)x.v[j][e], rk = (double)x.r[j][e];
+                double delta = fma(gamma, vn, rk) - vk;             // Eq. (TD)
+                if (!kFull) delta = k0 + e < len ? delta : 0.0;
+                ba = fma(c, ba, delta);
+                br = fma(gamma, br, rk);
+                la[e] = (float)ba;
+                lr[e] = (float)br;
+                vn = vk;
+            }
+            s_loc[(2 * j) * kWave + lane] = la;
+            s_loc[(2 * j + 1) * kWave + lane] = lr;
+            ba = lane_scan(ba, p.sa, wa);
+            br = lane_scan(br, p.sr, wr);
+        }
+        m.inc_a[j] = ba;
+        m.inc_r[j] = br;
+        m.tot_a[j] = read_lane63(ba);
+        m.tot_r[j] = read_lane63(br);
+    }
+    TPPO_STAMP(3);
+    // Take the look-back's words out of flight BEFORE anything is stored: the memory counter of a wavefront
+    // retires in order, so a wait for these loads placed after the publication below would also wait for its
+    // write-through stores, a full trip to memory.
+    x.look_ok = unpack_words(x.early, p.tag, x.look_a, x.look_r);
+    asm volatile("" : "+v"(x.look_a), "+v"(x.look_r) : : "memory");
+    TPPO_STAMP(6);
+    if (x.t.number() > 0) {                                         // somebody to my left will ask for the tile's value
+        double ta = 0.0, tr = 0.0;
+#pragma unroll
+        for (int j = kSlots - 1; j >= 0; --j) {
+            ta = fma(p.sa.q64, ta, m.tot_a[j]);
+            tr = fma(p.sr.q64, tr, m.tot_r[j]);
+        }
+        if (lane == 0) {
+            unsigned long long* words = &pl.scan_words[(int64_t)kScanWords * x.t.slot()];
+            publish(words, p.tag, ta);
+            publish(words + 2, p.tag, tr);
         }
     }
 }
 
-template <bool kTerminal>
-__global__ __launch_bounds__(kEgaeThreads, 3) void egae_scan_kernel(
-    const float* __restrict__ rewards, const float* __restrict__ values,
-    const int32_t* __restrict__ done, const float* __restrict__ bootstrap, int n_resp, int cap,
-    double gamma, double c, double gamma_pow_chunk, double c_pow_chunk, float* __restrict__ adv,
-    float* __restrict__ ret, void* ws_raw, int32_t* status) {
-    __shared__ __attribute__((aligned(16))) float s_r[kLdsArray];      // rewards in, advantages out
-    __shared__ __attribute__((aligned(16))) float s_v[kLdsArray];      // values in, returns out
-    __shared__ float s_v0[kEgaeThreads + 1];
-    __shared__ Affine s_wave[2][kEgaeWaves];
-    __shared__ double s_carry[2];
-
-    EgaeWs ws = egae_ws(ws_raw, cap);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int count = *ws.n_chunks;
-    int w = blockIdx.x;
-    if (w >= count) return;
-
-    Chunk cur = ws.chunks[w];
-    Raw raw;
-    load_raw<kTerminal>(raw, rewards, values, cur, done, tid);
-    raw.v_after = load_v_after(cur, values, done, bootstrap, tid);
-
-    for (; w < count; w += gridDim.x) {
-        const int start = cur.start, len = cur.len(), k0 = tid * kTpt;
-        const int n_mine = min(max(len - k0, 0), kTpt);          // my tokens that exist
-        // ---- this chunk's data: token order -> LDS -> kTpt consecutive tokens per thread
-        stage_raw(raw, s_r, s_v, tid);
-        if (tid == kEgaeThreads - 1) s_v0[kEgaeThreads] = raw.v_after;
-        __syncthreads();
-        TokenRegs tk;
-        read_runs(tk, s_r, s_v, tid);
-        // ---- start the next chunk's loads before working on this one
-        const int w_next = w + gridDim.x;
-        Chunk nxt = cur;
-        if (w_next < count) {
-            nxt = ws.chunks[w_next];
-            load_raw<kTerminal>(raw, rewards, values, nxt, done, tid);
-            raw.v_after = load_v_after(nxt, values, done, bootstrap, tid);
+// The carry into a tile from the tiles to its right, pass 2, the stores.
+template <bool kFull>
+__device__ __forceinline__ void tile_back(const TileIn& x, const TileMid& m, const lds_float4* s_loc,
+                                          const EgaeParams& p, const Plan& pl, int lane, const LaneWeights& wa,
+                                          const LaneWeights& wr TPPO_STAMPS_ARG) {
+    const Tile& t = x.t;
+    const int pos = x.pos;
+    (void)pos;
+    const double gamma = p.gamma, c = p.sa.m;
+    const int start = t.start, len = kFull ? kTileTokens : t.len(), after = t.after;
+    double carry_a = 0.0, carry_r = 0.0;
+    unsigned long long* words = &pl.scan_words[(int64_t)kScanWords * t.slot()];
+    if (after != 0) {                                               // wave-uniform
+        if (lane < after) {
+            double ba = x.look_a, br = x.look_r;
+            if (!x.look_ok)                                         // not there yet when the tile began: wait for it
+                wait_words(look_at(pl, t, lane), p.tag, ba, br, p.status);
+            carry_a = powi(p.sa.qtile, lane) * ba;
+            carry_r = powi(p.sr.qtile, lane) * br;
         }
-
-        // ---- V(s_{t+1}) of my last token: my right neighbour's first value, or for
-        // the owner of the chunk's last token the value after the chunk
-        s_v0[tid] = tk.v[0];
-        __syncthreads();
-        const bool owns_last = n_mine > 0 && k0 + n_mine == len;
-        const float v_right = owns_last ? s_v0[kEgaeThreads] : s_v0[tid + 1];
-
-        // ---- pass 1: my tokens as one affine map of the value carried in from the right
-        const double a0 = (owns_last && cur.after == 0) ? 0.0 : 1.0;   // nothing is carried past a sequence's end
-        Affine fa = {a0, 0.0}, fr = {a0, 0.0};
-        float* out_a = s_r + tid * kLdsRun;                      // my run in LDS: inputs are in registers by now
-        float* out_r = s_v + tid * kLdsRun;
-        if (len == kChunkTokens) walk_tokens<true, false>(tk, n_mine, v_right, gamma, c, fa, fr, out_a, out_r);
-        else walk_tokens<false, false>(tk, n_mine, v_right, gamma, c, fa, fr, out_a, out_r);
-
-        // ---- suffix composition across the wavefront (inclusive), then wavefronts
-        Affine sa = fa, sr = fr;
+#ifdef TPPO_TUNING
+        {
+            const unsigned long long late = __ballot(lane < after && !x.look_ok);
+            g_stamp_local[0] = __popcll(late);
+        }
+#endif
 #pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            const Affine ga = shfl_down(sa, off), gr = shfl_down(sr, off);
-            if (lane + off < kWave) {
-                sa = compose(sa, ga);
-                sr = compose(sr, gr);
-            }
+        for (int off = 32; off >= 1; off >>= 1) {
+            carry_a += __shfl_xor(carry_a, off);
+            carry_r += __shfl_xor(carry_r, off);
         }
-        if (lane == 0) {
-            s_wave[0][wave] = sa;
-            s_wave[1][wave] = sr;
-        }
-        Affine ea = shfl_down(sa, 1), er = shfl_down(sr, 1);      // exclusive: my right neighbour's inclusive
-        if (lane == kWave - 1) {
-            ea = {1.0, 0.0};
-            er = {1.0, 0.0};
-        }
-        __syncthreads();
-        for (int q = wave + 1; q < kEgaeWaves; ++q) {
-            ea = compose(ea, s_wave[0][q]);
-            er = compose(er, s_wave[1][q]);
-        }
-
-        // ---- publish the chunk's own contribution, then collect the carry
-        if (wave == 0) {
-            if (lane == 0 && cur.number() > 0) {                  // somebody to my left will ask for it
-                Affine ta = s_wave[0][0], tr = s_wave[1][0];
-                for (int q = 1; q < kEgaeWaves; ++q) {
-                    ta = compose(ta, s_wave[0][q]);
-                    tr = compose(tr, s_wave[1][q]);
-                }
-                publish(&ws.agg[4 * (int64_t)w], ta.b);
-                publish(&ws.agg[4 * (int64_t)w + 2], tr.b);
-            }
-            double carry_a = 0.0, carry_r = 0.0;
-            const int after = min(cur.after, w);                 // chunks to the right: list entries w-1 .. w-after
-            for (int j0 = 1; j0 <= after; j0 += kWave) {
-                const int j = j0 + lane;
-                double ta = 0.0, tr = 0.0;
-                if (j <= after) {
-                    // j-1 full chunks lie in between
-                    double ba, br;
-                    wait_words(&ws.agg[4 * (int64_t)(w - j)], ba, br, status);
-                    ta = powi(c_pow_chunk, j - 1) * ba;
-                    tr = powi(gamma_pow_chunk, j - 1) * br;
-                }
+        if (t.number() >= kWave) {                                  // I am some tile's 64th: a full tile, since after != 0
+            double ta = 0.0, tr = 0.0;
 #pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) {
-                    ta += __shfl_down(ta, off);
-                    tr += __shfl_down(tr, off);
-                }
-                carry_a += ta;
-                carry_r += tr;
+            for (int j = kSlots - 1; j >= 0; --j) {
+                ta = fma(p.sa.q64, ta, m.tot_a[j]);
+                tr = fma(p.sr.q64, tr, m.tot_r[j]);
             }
             if (lane == 0) {
-                s_carry[0] = carry_a;
-                s_carry[1] = carry_r;
+                publish(words + 4, p.tag, fma(p.sa.qtile, carry_a, ta));
+                publish(words + 6, p.tag, fma(p.sr.qtile, carry_r, tr));
             }
         }
-        __syncthreads();
-
-        // ---- pass 2: replay my tokens from the true value to my right and store
-        Affine va = {0.0, fma(ea.a, s_carry[0], ea.b)}, vr = {0.0, fma(er.a, s_carry[1], er.b)};
-        if (a0 == 0.0) {                                         // past a sequence's end there is nothing
-            va.b = 0.0;
-            vr.b = 0.0;
-        }
-        if (len == kChunkTokens) walk_tokens<true, true>(tk, n_mine, v_right, gamma, c, va, vr, out_a, out_r);
-        else walk_tokens<false, true>(tk, n_mine, v_right, gamma, c, va, vr, out_a, out_r);
-        // ---- results (written to my LDS run by pass 2): thread order -> token order -> global
-        __syncthreads();
+    }
+    TPPO_STAMP(4);
+    // a token's value is what pass 1 kept for it plus m^(tokens to the run's end) times the value carried into
+    // the run
+    const double pw_a[4] = {p.sa.q[0], c * c * c, c * c, c}, pw_r[4] = {p.sr.q[0], gamma * gamma * gamma, gamma * gamma, gamma};
+    float* __restrict__ adv = p.adv;
+    float* __restrict__ ret = p.ret;
 #pragma unroll
-        for (int g = 0; g < kGroups; ++g) {
-            const int k0 = g * 4 * kEgaeThreads + tid * 4;
-            const int slot = lds_slot(k0);
-            const float4 oa = *reinterpret_cast<const float4*>(s_r + slot);
-            const float4 orr = *reinterpret_cast<const float4*>(s_v + slot);
-            if (k0 + 4 <= len) {
-                float4u ua, ur;
-                ua[0] = oa.x; ua[1] = oa.y; ua[2] = oa.z; ua[3] = oa.w;
-                ur[0] = orr.x; ur[1] = orr.y; ur[2] = orr.z; ur[3] = orr.w;
-                *reinterpret_cast<float4u*>(adv + start + k0) = ua;
-                *reinterpret_cast<float4u*>(ret + start + k0) = ur;
+    for (int j = kSlots - 1; j >= 0; --j) {
+        const int k0 = 4 * (64 * j + 63 - lane);
+        if (kFull || 256 * j < len) {
+            const double xa = fma(wa.p, carry_a, dpp_move<kWaveShr1, 0xF>(m.inc_a[j]));
+            const double xr = fma(wr.p, carry_r, dpp_move<kWaveShr1, 0xF>(m.inc_r[j]));
+            const lds_float4 la = s_loc[(2 * j) * kWave + lane], lr = s_loc[(2 * j + 1) * kWave + lane];
+            float4u oa, orr;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                oa[e] = (float)fma(pw_a[e], xa, (double)la[e]);
+                orr[e] = (float)fma(pw_r[e], xr, (double)lr[e]);
+            }
+            if (kFull || k0 + 4 <= len) {
+#ifdef TPPO_EGAE_PLAIN_STORES
+                *reinterpret_cast<float4u*>(adv + start + k0) = oa;
+                *reinterpret_cast<float4u*>(ret + start + k0) = orr;
+#else
+                __builtin_nontemporal_store(oa, reinterpret_cast<float4u*>(adv + start + k0));
+                __builtin_nontemporal_store(orr, reinterpret_cast<float4u*>(ret + start + k0));
+#endif
             } else {
-                const float ea_[4] = {oa.x, oa.y, oa.z, oa.w}, er_[4] = {orr.x, orr.y, orr.z, orr.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (k0 + e < len) {
-                        adv[start + k0 + e] = ea_[e];
-                        ret[start + k0 + e] = er_[e];
+                        adv[start + k0 + e] = oa[e];
+                        ret[start + k0 + e] = orr[e];
                     }
                 }
             }
         }
-        __syncthreads();                                        // s_r / s_v are refilled by the next chunk
-        cur = nxt;
+        carry_a = fma(p.sa.q64, carry_a, m.tot_a[j]);
+        carry_r = fma(p.sr.q64, carry_r, m.tot_r[j]);
+    }
+    TPPO_STAMP(5);
+    TPPO_STAMPS_FLUSH;
+}
+
+// Schedule: one wavefront per tile, one tile per workgroup, workgroup w the tile at list position w.  The
+// hardware's dispatcher is the load balancer, and it starts workgroups in index order: the tiles a tile may have
+// to wait for stand earlier in the list, so they run or have run, and they never wait before they publish.
+// (Wavefronts that stay and walk the list with a stride were measured too -- they save the start-up of a
+// wavefront per tile, but every tile then waits for the stores of the one before it, and tiles that depend on
+// each other run side by side more often; 5 % slower on the long-CoT batches.)
+template <bool kTerminal>
+__global__ __launch_bounds__(kWave, kEgaeMinWaves) void egae_scan_kernel(EgaeParams p) {
+    __shared__ lds_float4 s_loc[2 * kSlots * kWave];
+    TPPO_STAMPS_DECL;
+    TPPO_STAMP(7);
+    const Plan pl = plan_open(p.plan);
+    const int lane = threadIdx.x;
+    const int pos = blockIdx.x;
+    const int n_tiles = load_uniform(&pl.hdr->n_tiles);
+    if (load_uniform(&pl.hdr->B) != p.B || load_uniform(&pl.hdr->n_resp) != p.n_resp || n_tiles > pl.cap ||
+        pl.cap < (int)gridDim.x) {                                  // a plan built for another batch
+        if (pos == 0 && lane == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
+        return;
+    }
+    if (pos >= n_tiles) return;                                     // the list is shorter than its capacity
+    // the descriptor as a vector load: the wavefront waits for it, and a scalar load that misses is several
+    // times slower
+    const int zero = opaque_zero();
+    const Tile t = uniform_tile(fetch_tile(pl.tiles + pos, zero));
+    if (!tile_valid(t, p.n_resp, p.B, pl.cap)) {
+        if (lane == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
+        return;
+    }
+    TileIn cur;
+    issue_tile<kTerminal>(cur, t, p, pl, pos, lane, zero);
+    TPPO_STAMP(1);
+    const LaneWeights wa = lane_weights(p.sa, lane), wr = lane_weights(p.sr, lane);    // while the loads fly
+    TileMid mid;
+    if (t.len() == kTileTokens) {
+        tile_front<kTerminal, true>(cur, mid, s_loc, p, pl, lane, wa, wr TPPO_STAMPS_PASS);
+        tile_back<true>(cur, mid, s_loc, p, pl, lane, wa, wr TPPO_STAMPS_PASS);
+    } else {
+        tile_front<kTerminal, false>(cur, mid, s_loc, p, pl, lane, wa, wr TPPO_STAMPS_PASS);
+        tile_back<false>(cur, mid, s_loc, p, pl, lane, wa, wr TPPO_STAMPS_PASS);
+    }
+}
+
+// Batches of fewer than four tokens (the streaming kernel's 16-byte accesses need four): one thread per
+// sequence walks it token by token, straight from Eq. (TD) and the two recurrences.
+template <bool kTerminal>
+__global__ __launch_bounds__(256) void egae_tiny_kernel(const float* __restrict__ rewards, const float* __restrict__ values,
+                                                        const int32_t* __restrict__ resp_off, const int32_t* __restrict__ done,
+                                                        const float* __restrict__ bootstrap, int B, int n_resp, double gamma,
+                                                        double c, float* __restrict__ adv, float* __restrict__ ret,
+                                                        int32_t* status) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < B; i += gridDim.x * blockDim.x) {
+        const int lo = resp_off[i], hi = resp_off[i + 1];
+        if (lo < 0 || hi < lo || hi > n_resp) {
+            set_status(status, TPPO_STATUS_BAD_LAYOUT);
+            continue;
+        }
+        if (hi == lo) continue;
+        const bool fin = done[i] != 0;
+        double v_next = fin ? 0.0 : (double)(bootstrap ? bootstrap[i] : values[hi - 1]);
+        double a = 0.0, r = 0.0;
+        for (int t = hi - 1; t >= lo; --t) {
+            const double rk = kTerminal ? ((t == hi - 1 && fin) ? (double)rewards[i] : 0.0) : (double)rewards[t];
+            const double vk = (double)values[t];
+            a = fma(c, a, fma(gamma, v_next, rk) - vk);
+            r = fma(gamma, r, rk);
+            adv[t] = (float)a;
+            ret[t] = (float)r;
+            v_next = vk;
+        }
     }
 }
 
@@ -406,63 +557,60 @@ __global__ __launch_bounds__(kEgaeThreads, 3) void egae_scan_kernel(
 
 extern "C" size_t tppo_egae_workspace_bytes(int64_t n_resp, int64_t B) {
     if (n_resp <= 0 || B <= 0) return 256;
-    return tppo::egae_ws_bytes(tppo::max_chunks(n_resp, B));
+    return tppo::plan_bytes_for(tppo::plan_max_tiles(n_resp, B));
 }
 
 namespace tppo {
-// Workgroups of the scan that the current device keeps resident at the same time.  The look-back waits on
-// chunks held by other workgroups, so the grid must never exceed this (else a waiting workgroup could keep
-// the one it waits for from starting); asked of the runtime once per device.
-static int egae_resident_groups() {
-    static int cached[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-    if (cached[dev] > 0) return cached[dev];
-    int per_cu = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, egae_scan_kernel<false>, kEgaeThreads, 0) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-        return 0;
-    const int n = per_cu * cus;
-    cached[dev] = n < kEgaeMaxGroups ? n : kEgaeMaxGroups;
-    return cached[dev];
-}
-}  // namespace tppo
-
-namespace tppo {
-// `rewards` is the dense [n_resp] array, or with terminal_mode the per-sequence terminal[B] array
+// `rewards` is the dense [n_resp] array, or with terminal_mode the per-sequence terminal[B] array.
+// plan != NULL: a plan of this layout, built earlier on the same stream; else one is built in `workspace`.
 static int egae_launch(const float* rewards, bool terminal_mode, const float* values, const int32_t* resp_off,
                        const int32_t* done, const float* bootstrap, int64_t B, int64_t n_resp,
                        float gamma, float lambda, float* adv, float* ret, void* workspace,
-                       size_t workspace_bytes, int32_t* status, void* stream) {
-    if (B < 0 || n_resp < 0 || n_resp > INT32_MAX - kChunkTokens || B > INT32_MAX / 4) return TPPO_ERR_SIZE;
+                       size_t workspace_bytes, void* plan, int32_t* status, void* stream) {
+    if (B < 0 || n_resp < 0 || n_resp > INT32_MAX - kTileTokens || B > INT32_MAX / 4) return TPPO_ERR_SIZE;
     if (!(gamma >= 0.f && gamma <= 1.f) || !(lambda >= 0.f && lambda <= 1.f)) return TPPO_ERR_PARAM;
     if (n_resp == 0) return TPPO_OK;
     if (B == 0) return TPPO_ERR_SIZE;
     if (!rewards || !values || !resp_off || !done || !adv || !ret) return TPPO_ERR_NULL;
-    if (!workspace || !is_aligned(workspace, 256) ||
-        workspace_bytes < tppo_egae_workspace_bytes(n_resp, B))
-        return TPPO_ERR_WORKSPACE;
+    int64_t cap64 = plan_max_tiles(n_resp, B);
+    if (cap64 > INT32_MAX / 8) return TPPO_ERR_SIZE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t cap64 = max_chunks(n_resp, B);
-    if (cap64 > INT32_MAX / 4) return TPPO_ERR_SIZE;
-    const int cap = (int)cap64;
-    const int clear_groups = (int)((cap64 * 4 + kBuildThreads * 8 - 1) / (kBuildThreads * 8));
-    const int parts = build_parts(B);
-    hipLaunchKernelGGL(egae_init_kernel, dim3(parts + (clear_groups < 1 ? 1 : clear_groups)), dim3(kBuildThreads),
-                       0, s, resp_off, (int)B, (int)n_resp, cap, parts, workspace, status);
-    if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
-    const double g = (double)gamma, c = (double)gamma * (double)lambda;
-    // weight of a whole chunk in the carry: (gamma*lambda)^2048 resp. gamma^2048
-    const double gamma_pow_chunk = pow(g, (double)kChunkTokens), c_pow_chunk = pow(c, (double)kChunkTokens);
-    const int resident = egae_resident_groups();
-    if (resident < 1) return TPPO_ERR_LAUNCH;
-    const int groups = cap < resident ? cap : resident;
-    if (terminal_mode)
-        hipLaunchKernelGGL(egae_scan_kernel<true>, dim3(groups), dim3(kEgaeThreads), 0, s, rewards, values, done,
-                           bootstrap, (int)n_resp, cap, g, c, gamma_pow_chunk, c_pow_chunk, adv, ret, workspace, status);
-    else
-        hipLaunchKernelGGL(egae_scan_kernel<false>, dim3(groups), dim3(kEgaeThreads), 0, s, rewards, values, done,
-                           bootstrap, (int)n_resp, cap, g, c, gamma_pow_chunk, c_pow_chunk, adv, ret, workspace, status);
+    if (plan) {
+        if (!is_aligned(plan, 256)) return TPPO_ERR_WORKSPACE;
+    } else if (!workspace || !is_aligned(workspace, 256) || workspace_bytes < tppo_egae_workspace_bytes(n_resp, B)) {
+        return TPPO_ERR_WORKSPACE;
+    }
+    if (n_resp < 4) {
+        const int groups = (int)((B + 255) / 256 < 1024 ? (B + 255) / 256 : 1024);
+        const double g = (double)gamma, c = (double)gamma * (double)lambda;
+        if (terminal_mode)
+            hipLaunchKernelGGL(egae_tiny_kernel<true>, dim3(groups), dim3(256), 0, s, rewards, values, resp_off, done,
+                               bootstrap, (int)B, (int)n_resp, g, c, adv, ret, status);
+        else
+            hipLaunchKernelGGL(egae_tiny_kernel<false>, dim3(groups), dim3(256), 0, s, rewards, values, resp_off, done,
+                               bootstrap, (int)B, (int)n_resp, g, c, adv, ret, status);
+        return launch_result();
+    }
+    if (!plan) {
+        if (launch_plan_build(resp_off, nullptr, done, B, n_resp, cap64, workspace, status, s) != TPPO_OK) return TPPO_ERR_LAUNCH;
+        plan = workspace;
+    }
+    EgaeParams p;
+    p.rewards = rewards; p.values = values; p.done = done; p.bootstrap = bootstrap;
+    p.adv = adv; p.ret = ret; p.plan = plan; p.status = status;
+    p.n_resp = (int)n_resp; p.B = (int)B;
+    p.tag = next_call_tag();
+    p.gamma = (double)gamma;
+    p.sa = make_consts((double)gamma * (double)lambda);
+    p.sr = make_consts((double)gamma);
+#ifdef TPPO_TUNING
+    p.prof = nullptr;
+    if (const char* e = getenv("TPPO_EGAE_PROF")) p.prof = reinterpret_cast<long long*>(strtoull(e, nullptr, 0));
+#endif
+    // one wavefront per tile; the list may be shorter than its capacity: the surplus exits at once
+    const unsigned groups = (unsigned)cap64;
+    if (terminal_mode) hipLaunchKernelGGL(egae_scan_kernel<true>, dim3(groups), dim3(kWave), 0, s, p);
+    else hipLaunchKernelGGL(egae_scan_kernel<false>, dim3(groups), dim3(kWave), 0, s, p);
     return launch_result();
 }
 }  // namespace tppo
@@ -470,15 +618,15 @@ static int egae_launch(const float* rewards, bool terminal_mode, const float* va
 extern "C" int tppo_egae(const float* rewards, const float* values, const int32_t* resp_off,
                          const int32_t* done, const float* bootstrap, int64_t B, int64_t n_resp,
                          float gamma, float lambda, float* adv, float* ret, void* workspace,
-                         size_t workspace_bytes, int32_t* status, void* stream) {
+                         size_t workspace_bytes, void* plan, int32_t* status, void* stream) {
     return tppo::egae_launch(rewards, false, values, resp_off, done, bootstrap, B, n_resp, gamma, lambda, adv,
-                             ret, workspace, workspace_bytes, status, stream);
+                             ret, workspace, workspace_bytes, plan, status, stream);
 }
 
 extern "C" int tppo_egae_terminal(const float* terminal_reward, const float* values, const int32_t* resp_off,
                                   const int32_t* done, const float* bootstrap, int64_t B, int64_t n_resp,
                                   float gamma, float lambda, float* adv, float* ret, void* workspace,
-                                  size_t workspace_bytes, int32_t* status, void* stream) {
+                                  size_t workspace_bytes, void* plan, int32_t* status, void* stream) {
     return tppo::egae_launch(terminal_reward, true, values, resp_off, done, bootstrap, B, n_resp, gamma, lambda,
-                             adv, ret, workspace, workspace_bytes, status, stream);
+                             adv, ret, workspace, workspace_bytes, plan, status, stream);
 }

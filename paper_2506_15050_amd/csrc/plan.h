@@ -4,15 +4,28 @@
 // tokens that never straddle two sequences.  A tile is described by 16 bytes,
 // so a wavefront learns everything about its tokens (which sequence, how far
 // into it, how many tiles follow) from ONE load instead of a chain of dependent
-// look-ups in the offset arrays.  Tiles are listed in token order: sequence 0
-// first and, inside a sequence, its first tile first.
+// look-ups in the offset arrays.
+//
+// Order of the list.  The scan's only dependency runs from a tile to the tiles
+// AFTER it in the same sequence, and a kernel that takes one tile per workgroup
+// starts them in list order.  So the list is sorted by `after` ("level"): first
+// every sequence's last tile, then every second-to-last one, ...  A tile's
+// dependencies then started (number of sequences at least that long) workgroups
+// earlier -- thousands on the long-CoT batches of Sec. 4 -- and have published
+// long before it looks for them; with the sequences simply laid end to end they
+// would start together with it and every tile would sit out a round trip through
+// memory.  Levels kLevels and up (sequences beyond 32 K tokens) follow the sorted
+// part, each sequence's tiles together, innermost level first.
 //
 // A plan is one block of device memory:
 //   header (256 B)   tile count, the sizes it was built for, the sizes of the
 //                    policy / value token sets of Sec. 3.2
 //   tiles[cap]       the descriptors
-//   scan_words[cap][4]   what a tile of the scan publishes for the tiles to its
-//                    left: {tag << 32 | float bits} for A hi, A lo, R hi, R lo
+//   scan_words[cap][8]   what a tile of the scan publishes for the tiles to its
+//                    left, {tag << 32 | float bits} each: A hi, A lo, R hi, R lo
+//                    of the tile alone, then the same four with everything to
+//                    its right included.  Indexed by Tile::slot(), which numbers
+//                    a sequence's tiles consecutively.
 //   finish_words[kFinishGroups][kFinishWords]   partial sums of a reduction
 //                    kernel's workgroups, in the same tagged form
 // Whoever builds the list (tppo_select, tppo_plan_build, or an entry point that
@@ -27,6 +40,8 @@ namespace tppo {
 
 constexpr int kTileTokens = 1024;
 constexpr int kTileShift = 11;                 // pos_len keeps (tokens - 1) in the low bits
+constexpr int kLevels = 32;                    // levels the list is sorted by
+constexpr int kScanWords = 8;                  // tagged words per tile
 constexpr int kBuildThreads = 1024;
 constexpr int kFinishGroups = 2048;            // most workgroups a reduction kernel may launch
 constexpr int kFinishWords = 10;               // tagged words per workgroup: five sums as hi + lo
@@ -40,6 +55,8 @@ struct Tile {
     int32_t after;     // tiles after it in the same sequence (0: it holds the sequence's last token)
     __device__ __forceinline__ int len() const { return (pos_len & ((1 << kTileShift) - 1)) + 1; }
     __device__ __forceinline__ int number() const { return pos_len >> kTileShift; }
+    // consecutive for the tiles of a sequence, unique in the batch, below plan_max_tiles(n_resp, B)
+    __device__ __forceinline__ int slot() const { return start / kTileTokens + seg; }
 };
 
 struct PlanHeader {
@@ -47,19 +64,21 @@ struct PlanHeader {
     int32_t B, n_resp;             // what the plan was built for; a consumer called with other sizes refuses it
     int32_t has_sets;              // n_policy / n_value are valid (the builder knew keep_len)
     long long n_policy, n_value;   // tokens in the policy set / the value set (Sec. 3.2)
+    int32_t cap;                   // descriptors the plan has room for (fixes where the tagged words start)
 };
 
 struct Plan {
     PlanHeader* hdr;
     Tile* tiles;
-    unsigned long long* scan_words;      // [cap][4]
+    unsigned long long* scan_words;      // [cap][kScanWords], by Tile::slot()
     unsigned long long* finish_words;    // [kFinishGroups][kFinishWords]
+    int cap;
 };
 
 static inline int64_t plan_max_tiles(int64_t n_resp, int64_t B) { return n_resp / kTileTokens + B + 1; }
 
 static inline size_t plan_bytes_for(int64_t cap) {
-    return 256 + round_up((size_t)cap * sizeof(Tile), 256) + round_up((size_t)cap * 32, 256) +
+    return 256 + round_up((size_t)cap * sizeof(Tile), 256) + round_up((size_t)cap * kScanWords * 8, 256) +
            (size_t)kFinishGroups * kFinishWords * sizeof(unsigned long long);
 }
 
@@ -71,14 +90,55 @@ __host__ __device__ __forceinline__ Plan plan_view(void* raw, int64_t cap) {
     pl.tiles = reinterpret_cast<Tile*>(p);
     p += ((size_t)cap * sizeof(Tile) + 255) / 256 * 256;
     pl.scan_words = reinterpret_cast<unsigned long long*>(p);
-    p += ((size_t)cap * 32 + 255) / 256 * 256;
+    p += ((size_t)cap * kScanWords * 8 + 255) / 256 * 256;
     pl.finish_words = reinterpret_cast<unsigned long long*>(p);
+    pl.cap = (int)cap;
     return pl;
 }
 
+// a consumer's view: the capacity the builder used is in the header
+__device__ __forceinline__ Plan plan_open(void* raw) {
+    return plan_view(raw, load_uniform(&static_cast<const PlanHeader*>(raw)->cap));
+}
+
+// a wave-uniform descriptor, through the scalar data cache
+__device__ __forceinline__ Tile load_tile(const Tile* p) {
+    typedef int int4v __attribute__((ext_vector_type(4)));
+    const int4v x = *(const int4v __attribute__((address_space(4)))*)(p);
+    return Tile{x[0], x[1], x[2], x[3]};
+}
+
+// A zero the compiler cannot see through.  Added to a wave-uniform address it keeps the load a VECTOR load: with
+// thousands of wavefronts each fetching a line of its own, loads through the scalar data cache were measured
+// at 4000-6000 cycles, against about 1200 for vector loads issued at the same moment.
+__device__ __forceinline__ int opaque_zero() {
+    int z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+}
+
+// a descriptor as a vector load (every lane the same 16 bytes) ...
+typedef int tile_bits __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ tile_bits fetch_tile(const Tile* p, int zero) {
+    return *reinterpret_cast<const tile_bits*>(reinterpret_cast<const char*>(p) + zero);
+}
+// ... and back in scalar registers, where lengths and branches on it cost nothing
+__device__ __forceinline__ Tile uniform_tile(tile_bits x) {
+    return Tile{__builtin_amdgcn_readfirstlane(x[0]), __builtin_amdgcn_readfirstlane(x[1]),
+                __builtin_amdgcn_readfirstlane(x[2]), __builtin_amdgcn_readfirstlane(x[3])};
+}
+
+// A consumer trusts no descriptor it has not checked: a plan is caller-held memory, and a descriptor decides
+// which addresses are touched.  True when every token, side load and tagged word the tile names exists.
+__device__ __forceinline__ bool tile_valid(const Tile& t, int n_resp, int B, int cap) {
+    const int len = t.len();
+    return t.start >= 0 && t.start <= n_resp - len && t.seg >= 0 && t.seg < B && t.after >= 0 && t.number() >= 0 &&
+           t.after < cap - t.slot() && (t.after == 0 || (len == kTileTokens && t.start + len < n_resp));
+}
+
 // number of 8-byte tagged words of a plan (scan words, then finish words: contiguous but for padding)
-static inline int64_t plan_words(int64_t cap) {
-    return (int64_t)(((size_t)cap * 32 + 255) / 256 * 256) / 8 + (int64_t)kFinishGroups * kFinishWords;
+__host__ __device__ static inline int64_t plan_words(int64_t cap) {
+    return (int64_t)(((size_t)cap * kScanWords * 8 + 255) / 256 * 256) / 8 + (int64_t)kFinishGroups * kFinishWords;
 }
 
 // One workgroup per 1024 sequences builds the list (measured on 8704 sequences: the descriptor stores, one
@@ -128,8 +188,9 @@ __device__ __forceinline__ bool poll(const unsigned long long* p, uint32_t tag, 
 uint32_t next_call_tag();
 
 // Enqueue the kernel that builds a plan for (resp_off, done[, keep_len]) in `plan_raw` (plan_bytes_for(cap)
-// bytes, cap = plan_max_tiles(n_resp, B)) and zeroes its tagged words.  keep_len may be NULL (no set sizes).
+// bytes) and zeroes its tagged words.  keep_len may be NULL (no set sizes).  n_resp < 0: the kernel takes
+// resp_off[B] for it (a caller whose offsets are still being computed on the stream).
 int launch_plan_build(const int32_t* resp_off, const int32_t* keep_len, const int32_t* done, int64_t B,
-                      int64_t n_resp, void* plan_raw, int32_t* status, hipStream_t s);
+                      int64_t n_resp, int64_t cap, void* plan_raw, int32_t* status, hipStream_t s);
 
 }  // namespace tppo

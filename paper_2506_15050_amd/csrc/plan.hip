@@ -1,0 +1,247 @@
+// tppo_plan_build: the work plan of a batch layout (plan.h), built once and
+// handed to tppo_egae*, tppo_ppo_losses and tppo_ppo_losses_backward so that
+// none of them has to cut the batch into tiles again.  tppo_select builds the
+// same plan as a by-product of the token filter (Sec. 3.2).
+#include <atomic>
+
+#include "plan.h"
+
+namespace tppo {
+
+uint32_t next_call_tag() {
+    static std::atomic<uint32_t> counter{0};
+    uint32_t t = counter.fetch_add(1, std::memory_order_relaxed) + 1;
+    if (t == 0) t = counter.fetch_add(1, std::memory_order_relaxed) + 1;   // 0 means "never written"
+    return t;
+}
+
+__device__ __forceinline__ int window_of(const int32_t* __restrict__ resp_off, int i, int n_resp, int& lo,
+                                         int32_t* status) {
+    lo = resp_off[i];
+    const int hi = resp_off[i + 1];
+    if (lo < 0 || hi < lo || hi > n_resp) {
+        if (status) set_status(status, TPPO_STATUS_BAD_LAYOUT);
+        return 0;
+    }
+    return hi - lo;
+}
+
+// n[l], l < kLevels: sequences with more than l tiles, i.e. tiles of level l; n[kLevels]: tiles of deeper levels
+struct LevelCounts { int n[kLevels + 1]; };
+
+__device__ __forceinline__ void count_sequence(LevelCounts& c, int tiles) {
+#pragma unroll
+    for (int l = 0; l < kLevels; ++l) c.n[l] += tiles > l ? 1 : 0;
+    c.n[kLevels] += max(tiles - kLevels, 0);
+}
+
+__device__ __forceinline__ Tile make_tile(int seg, int lo, int len, int tiles, int after) {
+    const int c = tiles - 1 - after;
+    Tile d;
+    d.start = lo + c * kTileTokens;
+    d.pos_len = (c << kTileShift) | (min(kTileTokens, len - c * kTileTokens) - 1);
+    d.seg = seg;
+    d.after = after;
+    return d;
+}
+
+// Workgroups 0 .. parts-1 build the list: workgroup `part` owns a contiguous range of the sequences and,
+// inside it, thread t a contiguous block.  The tile of sequence i at level l goes to
+//   (tiles of lower levels, whole batch) + (level-l tiles of sequences before i).
+// Every builder counts the first term and the second term's share of the sequences before its range by
+// itself, from offsets that sit in the cache -- cheaper than a second launch; the share inside the range is
+// one workgroup-wide prefix sum per level over the threads' blocks.  Then each thread walks its block once
+// per level it has tiles at and writes the descriptors.  Workgroup `parts` counts the two token sets
+// meanwhile; the remaining workgroups zero the tagged words.
+__global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t* __restrict__ resp_off,
+                                                                   const int32_t* __restrict__ keep_len,
+                                                                   const int32_t* __restrict__ done, int B,
+                                                                   int n_resp_arg, int cap, int parts, void* plan_raw,
+                                                                   int32_t* status) {
+    constexpr int kWaves = kBuildThreads / kWave;
+    __shared__ long long s_cnt[2][kWaves];
+    __shared__ int s_red[2][kWaves][kLevels + 1];
+    __shared__ int s_sum[2][kLevels + 1];
+    __shared__ int s_first[kLevels + 1];                   // list position of the range's first tile of a level
+    __shared__ int s_total;
+    __shared__ int s_top[kWaves];
+    const Plan pl = plan_view(plan_raw, cap);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int block = blockIdx.x;
+    if (block > parts) {                                   // zero the tagged words
+        const int64_t words = plan_words(cap);
+        for (int64_t i = (int64_t)(block - parts - 1) * kBuildThreads + tid; i < words;
+             i += (int64_t)(gridDim.x - parts - 1) * kBuildThreads)
+            pl.scan_words[i] = 0ull;
+        return;
+    }
+    if (block == parts) {                                  // sizes of the two token sets, from the metadata alone
+        long long np = 0, nv = 0;
+        if (keep_len) {
+            for (int i = tid; i < B; i += kBuildThreads) {
+                const int win = max(resp_off[i + 1] - resp_off[i], 0);
+                np += min(max(keep_len[i], 0), win);
+                nv += done[i] != 0 ? win : 0;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            np += __shfl_down(np, off);
+            nv += __shfl_down(nv, off);
+        }
+        if (lane == 0) {
+            s_cnt[0][wave] = np;
+            s_cnt[1][wave] = nv;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            np = nv = 0;
+            for (int w = 0; w < kWaves; ++w) {
+                np += s_cnt[0][w];
+                nv += s_cnt[1][w];
+            }
+            pl.hdr->n_policy = np;
+            pl.hdr->n_value = nv;
+            pl.hdr->has_sets = keep_len ? 1 : 0;
+        }
+        return;
+    }
+    const int part = block;
+    const int n_resp = n_resp_arg >= 0 ? n_resp_arg : resp_off[B];
+    if (part == 0 && tid == 0 && (resp_off[0] != 0 || resp_off[B] != n_resp)) set_status(status, TPPO_STATUS_BAD_LAYOUT);
+    const int range = (B + parts - 1) / parts;
+    const int p_begin = min(part * range, B), p_end = min(p_begin + range, B);
+    const int per = (p_end - p_begin + kBuildThreads - 1) / kBuildThreads;
+    const int i_begin = min(p_begin + tid * per, p_end), i_end = min(i_begin + per, p_end);
+    int lo;
+    // levels the batch has (all the per-level work below is skipped beyond them)
+    int top = 0;
+    for (int i = tid; i < B; i += kBuildThreads) top = max(top, tiles_of(window_of(resp_off, i, n_resp, lo, nullptr)));
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) top = max(top, __shfl_xor(top, off));
+    if (lane == 0) s_top[wave] = top;
+    __syncthreads();
+    for (int w = 0; w < kWaves; ++w) top = max(top, s_top[w]);
+    const int levels = min(top, kLevels);                  // wave-uniform, the same in every workgroup
+    const bool deep = top > kLevels;
+    {   // per level: tiles in the whole batch, and those of the sequences before my range
+        LevelCounts all = {}, ahead = {};
+        for (int i = tid; i < B; i += kBuildThreads) {
+            const int tiles = tiles_of(window_of(resp_off, i, n_resp, lo, nullptr));
+            count_sequence(all, tiles);
+            count_sequence(ahead, i < p_begin ? tiles : 0);
+        }
+#pragma unroll
+        for (int l = 0; l <= kLevels; ++l) {
+            if (l < kLevels ? l < levels : deep) {
+#pragma unroll
+                for (int off = 1; off < kWave; off <<= 1) {
+                    all.n[l] += __shfl_xor(all.n[l], off);
+                    ahead.n[l] += __shfl_xor(ahead.n[l], off);
+                }
+            }
+            if (lane == 0) {
+                s_red[0][wave][l] = all.n[l];              // (zero where skipped: nothing was counted there)
+                s_red[1][wave][l] = ahead.n[l];
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < 2 * (kLevels + 1)) {
+        const int which = tid / (kLevels + 1), l = tid % (kLevels + 1);
+        int sum = 0;
+        for (int w = 0; w < kWaves; ++w) sum += s_red[which][w][l];
+        s_sum[which][l] = sum;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int base = 0;
+        for (int l = 0; l <= kLevels; ++l) {
+            s_first[l] = base + s_sum[1][l];
+            base += s_sum[0][l];
+        }
+        s_total = base;
+    }
+    // my block's tiles per level, and an exclusive prefix sum of them over the workgroup
+    LevelCounts mine = {}, before;
+    for (int i = i_begin; i < i_end; ++i) count_sequence(mine, tiles_of(window_of(resp_off, i, n_resp, lo, status)));
+#pragma unroll
+    for (int l = 0; l <= kLevels; ++l) {
+        int inc = mine.n[l];
+        if (l < kLevels ? l < levels : deep) {
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                const int y = __shfl_up(inc, off);
+                if (lane >= off) inc += y;
+            }
+        }
+        before.n[l] = inc - mine.n[l];
+        if (lane == kWave - 1) s_red[0][wave][l] = inc;     // (the sums above were consumed before the last barrier)
+    }
+    __syncthreads();
+    if (tid <= kLevels) {
+        int run = 0;
+        for (int w = 0; w < kWaves; ++w) {
+            const int x = s_red[0][w][tid];
+            s_red[0][w][tid] = run;
+            run += x;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int l = 0; l < kLevels; ++l) {
+        if (mine.n[l] == 0) continue;
+        int at = s_first[l] + s_red[0][wave][l] + before.n[l];
+        for (int i = i_begin; i < i_end; ++i) {
+            const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = tiles_of(len);
+            if (tiles <= l) continue;
+            if (at < cap) pl.tiles[at] = make_tile(i, lo, len, tiles, l);     // (invalid offsets cannot overflow the list)
+            ++at;
+        }
+    }
+    if (mine.n[kLevels] != 0) {
+        int at = s_first[kLevels] + s_red[0][wave][kLevels] + before.n[kLevels];
+        for (int i = i_begin; i < i_end; ++i) {
+            const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = tiles_of(len);
+            for (int l = kLevels; l < tiles; ++l, ++at)
+                if (at < cap) pl.tiles[at] = make_tile(i, lo, len, tiles, l);
+        }
+    }
+    if (part == parts - 1 && tid == 0) {
+        const int total = s_total;
+        if (total > cap) set_status(status, TPPO_STATUS_BAD_LAYOUT);
+        pl.hdr->n_tiles = min(total, cap);
+        pl.hdr->B = B;
+        pl.hdr->n_resp = n_resp;
+        pl.hdr->cap = cap;
+    }
+}
+
+int launch_plan_build(const int32_t* resp_off, const int32_t* keep_len, const int32_t* done, int64_t B,
+                      int64_t n_resp, int64_t cap, void* plan_raw, int32_t* status, hipStream_t s) {
+    const int parts = build_parts(B);
+    int64_t zero_groups = (plan_words(cap) + kBuildThreads * 8 - 1) / (kBuildThreads * 8);
+    zero_groups = zero_groups < 1 ? 1 : zero_groups > 4096 ? 4096 : zero_groups;
+    hipLaunchKernelGGL(plan_build_kernel, dim3(parts + 1 + (int)zero_groups), dim3(kBuildThreads), 0, s, resp_off,
+                       keep_len, done, (int)B, (int)(n_resp < 0 ? -1 : n_resp), (int)cap, parts, plan_raw, status);
+    return launch_result();
+}
+
+}  // namespace tppo
+
+extern "C" size_t tppo_plan_bytes(int64_t n_resp, int64_t B) {
+    if (n_resp < 0 || B < 0) return 256;
+    return tppo::plan_bytes_for(tppo::plan_max_tiles(n_resp, B));
+}
+
+extern "C" int tppo_plan_build(const int32_t* resp_off, const int32_t* keep_len, const int32_t* done, int64_t B,
+                               int64_t n_resp, void* plan, size_t plan_bytes, int32_t* status, void* stream) {
+    using namespace tppo;
+    if (B < 0 || n_resp < 0 || n_resp > INT32_MAX - kTileTokens || B > INT32_MAX / 4) return TPPO_ERR_SIZE;
+    if (n_resp > 0 && B == 0) return TPPO_ERR_SIZE;
+    if (!resp_off || (B > 0 && !done)) return TPPO_ERR_NULL;
+    if (plan_max_tiles(n_resp, B) > INT32_MAX / 8) return TPPO_ERR_SIZE;
+    if (!plan || !is_aligned(plan, 256) || plan_bytes < tppo_plan_bytes(n_resp, B)) return TPPO_ERR_WORKSPACE;
+    return launch_plan_build(resp_off, keep_len, done, B, n_resp, plan_max_tiles(n_resp, B), plan, status,
+                             static_cast<hipStream_t>(stream));
+}

@@ -1076,12 +1076,12 @@ def test_whole_step_captured_in_a_graph_replays_like_eager(tp):
     logp_old = dev((-np.abs(rng.normal(size=n_resp)) - 6.0).astype(np.float32))
 
     def step():
-        sel = tp.tppo_select(cu, ctx, done, ids, b["tail_drop"])
+        sel = tp.tppo_select(cu, ctx, done, ids, b["tail_drop"], want_plan=True)
         logp, _ = tp.tppo_token_logprobs(hidden, w, sel["sel_rows"], sel["sel_targets"], M=n_tok,
                                          m_actual=sel["counts"], out_index=sel["sel_resp_idx"], out_size=n_resp)
-        adv, ret = tp.tppo_egae(rewards, values, sel["resp_off"], done, b["gamma"], b["lam"])
+        adv, ret = tp.tppo_egae(rewards, values, sel["resp_off"], done, b["gamma"], b["lam"], plan=sel["plan"])
         res = tp.tppo_ppo_losses(logp, logp_old, adv, v_new, values, ret, sel["resp_off"], sel["keep_len"], done,
-                                 b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"])
+                                 b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"], plan=sel["plan"])
         return sel, logp, adv, ret, res
 
     step()                                                    # first calls (occupancy queries, attributes) outside
@@ -1116,6 +1116,78 @@ def test_whole_step_captured_in_a_graph_replays_like_eager(tp):
     olp, _ = ofast.token_logprobs(host(hidden.view(torch.int16)).view(np.uint16), b["w_head"], osel["sel_rows"],
                                   osel["sel_targets"])
     assert np.max(np.abs(got[2][osel["sel_resp_idx"]] - olp)) <= LOGP_ATOL
+
+
+# ------------------------------------------------------------------ one plan per batch
+@pytest.mark.parametrize("name", ["small", "longcot"])
+def test_plan_from_select_feeds_every_consumer(tp, name):
+    """tppo_select hands out the work plan of the batch; EGAE (dense and terminal rewards), the losses and
+    their derivatives take it instead of building their own, any number of times, with results bit-identical
+    to the calls that build their own -- and correct against the oracle."""
+    import torch
+    b = synth.make_batch(name, with_head=False)
+    st = tp.new_status("cuda")
+    ids = dev(b["input_ids"]) if "input_ids" in b else None
+    sel = tp.tppo_select(dev(b["cu_seqlens"]), dev(b["ctx_len"]), dev(b["done"]), ids, b["tail_drop"],
+                         n_tok=b["n_tok"], status=st, want_plan=True)
+    plan, off, keep, done = sel["plan"], sel["resp_off"], sel["keep_len"], dev(b["done"])
+    a, keep_ref = loss_inputs(b)
+    assert np.array_equal(host(keep), keep_ref)
+    d = {k: dev(v) for k, v in a.items()}
+    rewards, values = dev(b["rewards"]), dev(b["values"])
+    eps = (b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"])
+    order = ("logp_new", "logp_old", "adv", "v_new", "v_old", "ret")
+    for trial, (gamma, lam) in enumerate(((1.0, 0.95), (0.999, 1.0), (1.0, 0.95))):      # the same plan again and again
+        adv_p, ret_p = tp.tppo_egae(rewards, values, off, done, gamma, lam, status=st, plan=plan)
+        adv_s, ret_s = tp.tppo_egae(rewards, values, off, done, gamma, lam, status=st)
+        assert torch.equal(adv_p, adv_s) and torch.equal(ret_p, ret_s), trial
+        ref_a, ref_r = ofast.egae(b["rewards"], b["values"], b["resp_off"], b["done"], float(np.float32(gamma)),
+                                  float(np.float32(lam)))
+        assert_egae_close(host(adv_p), ref_a, "adv")
+        assert_egae_close(host(ret_p), ref_r, "ret")
+        res_p = tp.read_loss_out(tp.tppo_ppo_losses(*(d[k] for k in order), off, keep, done, *eps, status=st, plan=plan))
+        res_s = tp.read_loss_out(tp.tppo_ppo_losses(*(d[k] for k in order), off, keep, done, *eps, status=st))
+        assert res_p == res_s
+        g_p = tp.tppo_ppo_losses_backward(*(d[k] for k in order), off, keep, done, *eps, status=st, plan=plan)
+        g_s = tp.tppo_ppo_losses_backward(*(d[k] for k in order), off, keep, done, *eps, status=st)
+        assert torch.equal(g_p[0], g_s[0]) and torch.equal(g_p[1], g_s[1])
+        assert tp.read_loss_out(g_p[2]) == res_p and tp.read_loss_stats(g_p[3]) == tp.read_loss_stats(g_s[3])
+    ref = ofast.ppo_losses(*(a[k] for k in order), b["resp_off"], keep_ref, b["done"], *eps)
+    assert_loss_close(res_p, ref)
+    term = dev(np.ones(b["B"], np.float32))
+    t_p = tp.tppo_egae_terminal(term, values, off, done, 1.0, 0.95, status=st, plan=plan)
+    t_s = tp.tppo_egae_terminal(term, values, off, done, 1.0, 0.95, status=st)
+    assert torch.equal(t_p[0], t_s[0]) and torch.equal(t_p[1], t_s[1])
+    assert int(host(st)[0]) == 0
+
+
+def test_plan_build_and_a_plan_of_another_batch(tp):
+    import torch
+    b = synth.make_batch("small", with_head=False)
+    a, keep = loss_inputs(b)
+    off, done, keepd = dev(b["resp_off"]), dev(b["done"]), dev(keep)
+    rewards, values = dev(b["rewards"]), dev(b["values"])
+    plan = tp.tppo_plan_build(off, keepd, done, b["n_resp"])
+    adv, ret = tp.tppo_egae(rewards, values, off, done, 1.0, 0.95, plan=plan)
+    adv_s, ret_s = tp.tppo_egae(rewards, values, off, done, 1.0, 0.95)
+    assert torch.equal(adv, adv_s) and torch.equal(ret, ret_s)
+    # a plan without keep_len serves the scan, not the losses
+    scan_only = tp.tppo_plan_build(off, None, done, b["n_resp"])
+    adv2, _ = tp.tppo_egae(rewards, values, off, done, 1.0, 0.95, plan=scan_only)
+    assert torch.equal(adv2, adv)
+    d = {k: dev(v) for k, v in a.items()}
+    order = ("logp_new", "logp_old", "adv", "v_new", "v_old", "ret")
+    st = tp.new_status("cuda")
+    res = tp.read_loss_out(tp.tppo_ppo_losses(*(d[k] for k in order), off, keepd, done, 0.2, 0.28, 0.5, 0.6,
+                                              status=st, plan=scan_only))
+    assert int(host(st)[0]) == tp.STATUS_BAD_LAYOUT and np.isnan(res["policy_loss"])
+    # a plan built for other sizes is refused: status bit, outputs untouched
+    b2 = synth.make_batch("small", with_head=False, B=5)
+    st = tp.new_status("cuda")
+    out = (torch.full((b2["n_resp"],), 7.0, device="cuda"), torch.full((b2["n_resp"],), 7.0, device="cuda"))
+    tp.tppo_egae(dev(b2["rewards"]), dev(b2["values"]), dev(b2["resp_off"]), dev(b2["done"]), 1.0, 0.95,
+                 status=st, plan=plan, out=out)
+    assert int(host(st)[0]) == tp.STATUS_BAD_LAYOUT and bool((out[0] == 7.0).all())
 
 
 # ------------------------------------------------------------------ randomised batches
