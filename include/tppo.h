@@ -206,6 +206,30 @@ int tppo_egae(const float* rewards, const float* values, const int32_t* resp_off
               float* adv, float* ret, void* workspace, size_t workspace_bytes,
               void* plan, int32_t* status, void* stream);
 
+/* tppo_egae_static -- tppo_egae for callers that cannot allocate device memory
+ * or may not call anything that does: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs,
+ * results and errors as tppo_egae with plan = NULL, but there is no workspace
+ * argument: the call builds its plan in a fixed array of just under 4 MiB that
+ * is part of the library's image on every GPU the library runs on (it stays
+ * there until the process ends).  It calls no hipMalloc / hipFree and no
+ * library routine that allocates; the first call on a device asks the runtime
+ * for the array's address there and keeps it.
+ * Limit: n_resp / 1024 + B + 1 <= tppo_egae_static_max_tiles() (49152: e.g.
+ * 40 M tokens in 8704 sequences); larger batches -> TPPO_ERR_SIZE, nothing is
+ * launched.
+ * All calls on one GPU share the array: two calls may not overlap in time on
+ * the same GPU (calls on one stream never do; calls on different streams, or
+ * from different threads on different streams, race).  Nothing has to be
+ * cleared between calls: each call rebuilds the list and zeroes the words it
+ * is going to use.
+ */
+int64_t tppo_egae_static_max_tiles(void);
+int tppo_egae_static(const float* rewards, const float* values, const int32_t* resp_off,
+                     const int32_t* done, const float* bootstrap,
+                     int64_t B, int64_t n_resp, float gamma, float lambda,
+                     float* adv, float* ret, int32_t* status, void* stream);
+
 /* tppo_egae_terminal -- the same with the sparse reward of Sec. 2.1 (one
  * rule-based reward at the end of a finished response, nothing else): instead
  * of a dense array, terminal_reward[B] gives r of the last window token of

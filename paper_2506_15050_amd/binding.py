@@ -35,6 +35,9 @@ _SIGNATURES = {
                                                 _c_ptr, _c_size, _c_ptr, _c_ptr, _c_ptr]),
     "tppo_egae_terminal": (ctypes.c_int, [_c_ptr] * 5 + [_c_i64, _c_i64, _c_f32, _c_f32, _c_ptr, _c_ptr,
                                                          _c_ptr, _c_size, _c_ptr, _c_ptr, _c_ptr]),
+    "tppo_egae_static_max_tiles": (_c_i64, []),
+    "tppo_egae_static": (ctypes.c_int, [_c_ptr] * 5 + [_c_i64, _c_i64, _c_f32, _c_f32, _c_ptr, _c_ptr,
+                                                       _c_ptr, _c_ptr]),
     "tppo_ppo_losses_workspace_bytes": (_c_size, [_c_i64, _c_i64]),
     "tppo_ppo_losses": (ctypes.c_int, [_c_ptr] * 9 + [_c_i64, _c_i64] + [_c_f32] * 4 +
                         [_c_ptr, _c_ptr, _c_size, _c_ptr, _c_ptr, _c_ptr]),
@@ -200,6 +203,19 @@ def tppo_egae(rewards, values, resp_off, done, gamma, lam, bootstrap=None, statu
                        _ptr(adv), _ptr(ret), _ptr(ws), 0 if ws is None else ws.numel(), _ptr(plan),
                        _ptr(status), _stream())
     _check(rc, "tppo_egae")
+    return adv, ret
+
+
+def tppo_egae_static(rewards, values, resp_off, done, gamma, lam, bootstrap=None, status=None, out=None):
+    """``tppo_egae`` without a workspace: the library's own fixed array holds the plan.  The binding
+    still allocates the outputs unless ``out=(adv, ret)`` is given.  Returns (adv, ret)."""
+    lib = load()
+    n_resp, B = rewards.numel(), done.numel()
+    adv, ret = out if out is not None else (torch.empty_like(rewards), torch.empty_like(rewards))
+    rc = lib.tppo_egae_static(_ptr(_dev_f32(rewards)), _ptr(_dev_f32(values)), _ptr(_dev_i32(resp_off)),
+                              _ptr(_dev_i32(done)), _ptr(bootstrap), B, n_resp, float(gamma), float(lam),
+                              _ptr(adv), _ptr(ret), _ptr(status), _stream())
+    _check(rc, "tppo_egae_static")
     return adv, ret
 
 

@@ -15,7 +15,7 @@ static inline bool is_aligned(const void* p, size_t a) {
     return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;
 }
 
-static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static constexpr size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 static inline int launch_result() {
     return hipGetLastError() == hipSuccess ? TPPO_OK : TPPO_ERR_LAUNCH;

@@ -41,6 +41,8 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "plan.h"
 
 namespace tppo {
@@ -621,6 +623,46 @@ extern "C" int tppo_egae(const float* rewards, const float* values, const int32_
                          size_t workspace_bytes, void* plan, int32_t* status, void* stream) {
     return tppo::egae_launch(rewards, false, values, resp_off, done, bootstrap, B, n_resp, gamma, lambda, adv,
                              ret, workspace, workspace_bytes, plan, status, stream);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// tppo_egae_static: tppo_egae for callers that may not allocate.  The plan is built in a fixed array that is
+// part of the library's image on every GPU it runs on.
+namespace tppo {
+constexpr int64_t kStaticTiles = 49152;                            // plan capacity of the array, in tiles
+constexpr size_t kStaticBytes = plan_bytes_for(kStaticTiles);      // just under 4 MiB
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+// The array's address on the current device.  In host code `scratch` is only a handle: the address has to be
+// asked for, once per device and with that device current (every GPU holds its own copy at its own address).
+static void* static_plan_memory() {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> known[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* ptr = known[dev].load(std::memory_order_acquire);
+    if (ptr) return ptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    known[dev].store(ptr, std::memory_order_release);            // (two threads racing here store the same value)
+    return ptr;
+}
+}  // namespace tppo
+
+extern "C" int64_t tppo_egae_static_max_tiles(void) { return tppo::kStaticTiles; }
+
+extern "C" int tppo_egae_static(const float* rewards, const float* values, const int32_t* resp_off,
+                                const int32_t* done, const float* bootstrap, int64_t B, int64_t n_resp,
+                                float gamma, float lambda, float* adv, float* ret, int32_t* status, void* stream) {
+    using namespace tppo;
+    if (B < 0 || n_resp < 0) return TPPO_ERR_SIZE;
+    if (n_resp / kTileTokens + B + 1 > kStaticTiles) return TPPO_ERR_SIZE;        // more tiles than the array holds
+    void* mem = static_plan_memory();
+    if (!mem) return TPPO_ERR_LAUNCH;
+    return egae_launch(rewards, false, values, resp_off, done, bootstrap, B, n_resp, gamma, lambda, adv, ret, mem,
+                       kStaticBytes, nullptr, status, stream);
 }
 
 extern "C" int tppo_egae_terminal(const float* terminal_reward, const float* values, const int32_t* resp_off,

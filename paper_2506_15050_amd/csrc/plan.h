@@ -75,9 +75,9 @@ struct Plan {
     int cap;
 };
 
-static inline int64_t plan_max_tiles(int64_t n_resp, int64_t B) { return n_resp / kTileTokens + B + 1; }
+static constexpr int64_t plan_max_tiles(int64_t n_resp, int64_t B) { return n_resp / kTileTokens + B + 1; }
 
-static inline size_t plan_bytes_for(int64_t cap) {
+static constexpr size_t plan_bytes_for(int64_t cap) {
     return 256 + round_up((size_t)cap * sizeof(Tile), 256) + round_up((size_t)cap * kScanWords * 8, 256) +
            (size_t)kFinishGroups * kFinishWords * sizeof(unsigned long long);
 }
