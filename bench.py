@@ -9,8 +9,12 @@ bf16, token ids sampled from the policy).
 
 Prints ONE JSON line with the whole-path throughput, the roofline position of
 the dominant kernel (the fused LM-head MFMA kernel, timed with HIP events on
-the launch stream inside the timed region) and the CPU oracle timed on a
-bounded sample of the same batch on this machine's host cores.
+the launch stream inside the timed region), the roofline positions of the
+HBM-bound kernels (EGAE scan, losses, loss derivatives) on long-CoT-sized
+arrays that no cache holds, and the CPU oracle timed on a bounded sample of
+the same batch on this machine's host cores.  The oracle's sample doubles as a
+check: its log-probs are compared with those of the last timed step, and the
+run fails if they differ by more than 2e-3.
 """
 import argparse
 import json
@@ -26,6 +30,8 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
+PARITY_TOLERANCE = 2e-3            # |log-prob (timed run) - log-prob (oracle)| on the oracle's sample
+STREAMING_WORKLOAD = "longcot20x"  # 40 M response tokens in 8704 sequences: 160 MB per array
 
 
 def measured_traffic(workload, kernel):
@@ -53,6 +59,8 @@ def parse():
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--metric-only", action="store_true",
                     help="skip everything outside the metric's four steps (measured ceilings, backward passes)")
+    ap.add_argument("--no-streaming-rooflines", action="store_true",
+                    help="skip the HBM-bound kernels' roofline entries on long-CoT-sized arrays")
     ap.add_argument("--no-reference-rates", action="store_true",
                     help="skip the two measuring sticks printed beside the datasheet peak")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
@@ -119,20 +127,20 @@ def main():
     H, V = b["H"], b["V"]
     ws_head = tp._workspace(lib.tppo_token_logprobs_workspace_bytes(M, H, V, tp.TPPO_BF16), "cuda") if has_head else None
     ws_egae = tp._workspace(lib.tppo_egae_workspace_bytes(n_resp, b["B"]), "cuda")
-    ws_loss = tp._workspace(lib.tppo_ppo_losses_workspace_bytes(n_resp, b["B"]), "cuda")
     adv_ret = (torch.empty(n_resp, device="cuda"), torch.empty(n_resp, device="cuda"))
     loss_out = torch.empty(32, dtype=torch.uint8, device="cuda")
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     stage_names = ("select", "logprobs", "egae", "losses")
     marks = []
+    last = {}
 
     def step(record):
         e = [ev() for _ in range(5)] if record else None
         if record:
             e[0].record()
         s = tp.tppo_select(d["cu_seqlens"], d["ctx_len"], d["done"], ids, b["tail_drop"], n_tok=n_tok,
-                           status=status)
+                           status=status, want_plan=True)       # the work plan is built once, here
         if record:
             e[1].record()
         if has_head:
@@ -144,15 +152,16 @@ def main():
         if record:
             e[2].record()
         adv, ret = tp.tppo_egae(d["rewards"], d["values"], s["resp_off"], d["done"], b["gamma"], b["lam"],
-                                status=status, workspace=ws_egae, out=adv_ret)
+                                status=status, plan=s["plan"], out=adv_ret)
         if record:
             e[3].record()
         tp.tppo_ppo_losses(logp, logp_old, adv, d["v_new"], d["values"], ret, s["resp_off"],
                            s["keep_len"], d["done"], b["eps_low"], b["eps_high"], b["xi_low"],
-                           b["xi_high"], status=status, workspace=ws_loss, out=loss_out)
+                           b["xi_high"], status=status, plan=s["plan"], out=loss_out)
         if record:
             e[4].record()
             marks.append(e)
+        last["logp"], last["sel"] = logp, s
 
     for _ in range(args.warmup):
         step(False)
@@ -293,9 +302,16 @@ def main():
                                                 "TFLOP/s": 6.0 * M * V * H / (hb_ms * 1e-3) / 1e12}
             del ws_hb, grad_w
 
-    cpu = None
+    streaming = None
+    if not (args.metric_only or args.no_streaming_rooflines):
+        streaming = streaming_rooflines(tp, synth, args.steps)
+
+    cpu, parity_ok = None, True
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(b, M, args.cpu_sample_rows, has_head)
+        gpu_logp = last["logp"].float().cpu().numpy() if has_head else None
+        gpu_idx = last["sel"]["sel_resp_idx"][:M].cpu().numpy() if has_head else None
+        cpu = cpu_baseline(b, M, args.cpu_sample_rows, has_head, gpu_logp, gpu_idx)
+        parity_ok = cpu.get("parity_max_abs_err") is None or cpu["parity_max_abs_err"] <= PARITY_TOLERANCE
 
     out = {
         "metric": "selected tokens/sec (logprob+EGAE+loss) at 1 MI355X",
@@ -307,9 +323,14 @@ def main():
                    "gamma": b["gamma"], "lambda": b["lam"]},
         "stages_ms": stage_ms,
         "losses": {k: losses[k] for k in ("policy_loss", "value_loss", "n_policy", "n_value")},
-        "roofline": roofline, "cpu_baseline": cpu, "beyond_the_metric": extra,
+        "roofline": roofline, "roofline_streaming": streaming, "cpu_baseline": cpu,
+        "beyond_the_metric": extra,
     }
     print(json.dumps(out))
+    if not parity_ok:
+        print(f"bench.py: the timed run's log-probs differ from the oracle's by {cpu['parity_max_abs_err']:.3g} "
+              f"(> {PARITY_TOLERANCE}) on the oracle's sample", file=sys.stderr)
+        sys.exit(1)
 
 
 def reference_rates(tp, hidden, w_head, s_rows):
@@ -342,10 +363,105 @@ def reference_rates(tp, hidden, w_head, s_rows):
     return {"mfma_loop_in_registers_tflops": mfma_only, "library_gemm_logits_to_hbm_tflops": gemm}
 
 
-def cpu_baseline(b, M, sample_rows, has_head):
+def streaming_rooflines(tp, synth, steps):
+    """Roofline entries of the HBM-bound kernels: tppo_egae, tppo_ppo_losses and
+    tppo_ppo_losses_backward on arrays of the long-CoT batch (40 M response
+    tokens, 160 MB per array), each launch on another of three array sets so that
+    nothing is served from the 256 MB cache, with the plan built once (as in the
+    whole path, where tppo_select builds it).  Every launch is timed with its own
+    pair of HIP events on the launch stream."""
+    import torch
+    name = STREAMING_WORKLOAD
+    cfg = dict(synth.CONFIGS[name])
+    meta = synth._rng(cfg["seed"], "meta")
+    done = (meta.random(cfg["B"]) < cfg["p_done"]).astype(np.int32)
+    win = synth._draw_lengths(meta, cfg, done)
+    off = np.concatenate([[0], np.cumsum(win)]).astype(np.int32)
+    n, B = int(off[-1]), cfg["B"]
+    keep = np.where(done != 0, win, np.maximum(win - cfg["tail_drop"], 0)).astype(np.int32)
+    n_pol, n_val = int(np.minimum(keep, win).sum()), int(win[done != 0].sum())
+    d_off, d_done, d_keep = (torch.from_numpy(x).cuda() for x in (off, done, keep))
+    sets = []
+    for k in range(3):
+        g = torch.Generator(device="cuda").manual_seed(1000 + k)
+        mk = lambda: torch.rand(n, device="cuda", generator=g) * 2 - 1
+        a = dict(r=mk() * 0.1, v=mk(), adv=torch.empty(n, device="cuda"), ret=torch.empty(n, device="cuda"),
+                 ln=-mk().abs() - 0.01, vn=mk(), glp=torch.empty(n, device="cuda"), gv=torch.empty(n, device="cuda"))
+        a["lo"] = a["ln"] + 0.1 * mk()
+        sets.append(a)
+    plan = tp.tppo_plan_build(d_off, d_keep, d_done, n)
+    st = tp.new_status("cuda")
+    out = torch.empty(32, dtype=torch.uint8, device="cuda")
+    stats = torch.empty(32, dtype=torch.uint8, device="cuda")
+    eps = (cfg["eps"][0], cfg["eps"][1], synth.XI[0], synth.XI[1])
+
+    def egae(a):
+        tp.tppo_egae(a["r"], a["v"], d_off, d_done, synth.GAMMA, synth.LAMBDA, status=st, plan=plan,
+                     out=(a["adv"], a["ret"]))
+
+    def losses(a):
+        tp.tppo_ppo_losses(a["ln"], a["lo"], a["adv"], a["vn"], a["v"], a["ret"], d_off, d_keep, d_done, *eps,
+                           status=st, plan=plan, out=out)
+
+    def grads(a):
+        tp.tppo_ppo_losses_backward(a["ln"], a["lo"], a["adv"], a["vn"], a["v"], a["ret"], d_off, d_keep, d_done,
+                                    *eps, status=st, plan=plan, out=out, stats=stats, grads=(a["glp"], a["gv"]))
+
+    for a in sets:
+        egae(a)
+    torch.cuda.synchronize()
+    per_stream = (4 * n + 15) // 16 * 16
+    pool_r = torch.zeros(3 * 6 * per_stream // 4 + 64, device="cuda")
+    pool_w = torch.empty(3 * 2 * per_stream // 4 + 64, device="cuda")
+
+    def timed(fn, reps):
+        for a in sets:
+            fn(a)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for i, (e0, e1) in enumerate(evs):
+            e0.record()
+            fn(sets[i % 3])
+            e1.record()
+        torch.cuda.synchronize()
+        return float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs])) * 1e-3
+
+    def ceiling(n_read, n_write):
+        run = lambda k: tp.tppo_diag_streams(pool_r[k * 6 * per_stream // 4:], pool_w[k * 2 * per_stream // 4:],
+                                             per_stream, per_stream, n_read, n_write)
+        for k in range(3):
+            run(k)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        total = sum(run(i % 3) for i in range(9))
+        e1.record()
+        torch.cuda.synchronize()
+        return total / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    reps = max(6, 2 * steps)
+    entries = []
+    for kernel, fn, nbytes, mix in (
+            ("egae_scan_kernel", egae, 16.0 * n, (2, 2)),
+            ("loss_kernel", losses, 12.0 * (n_pol + n_val), (6, 0)),
+            ("loss_grad_kernel", grads, 16.0 * (n_pol + n_val) + 4.0 * (2 * n - n_pol - n_val), (6, 2))):
+        sec = timed(fn, reps)
+        top = ceiling(*mix)
+        achieved = nbytes / sec / 1e9
+        entries.append(dict(bound="hbm", kernel=kernel, workload=name, achieved=achieved, peak=HBM_PEAK_GBS,
+                            unit="GB/s", frac=achieved / HBM_PEAK_GBS, traffic=measured_traffic(name, kernel),
+                            bytes_per_launch=nbytes, avg_us=sec * 1e6, launches=reps, cold=True,
+                            elementwise_pass_same_streams_GBps=top, frac_of_elementwise_pass=achieved / top))
+    assert int(st.item()) == 0, f"device status {int(st.item())} in the streaming kernels"
+    return entries
+
+
+def cpu_baseline(b, M, sample_rows, has_head, gpu_logp=None, gpu_resp_idx=None):
     """The CPU oracle, as it stands, on a bounded sample of the same batch:
     the LM head on `sample_rows` seeded kept rows, the other stages on the full
-    batch; per-token costs are added."""
+    batch; per-token costs are added.  With the timed run's log-probs
+    (response-packed) and the kept tokens' response-packed indices, the sample
+    is also a check: the largest difference is reported."""
     from oracle import fast as ofast
     t = time.perf_counter()
     ids = b["input_ids"] if has_head else np.zeros(b["n_tok"], np.int32)
@@ -369,8 +485,12 @@ def cpu_baseline(b, M, sample_rows, has_head):
                      b["xi_low"], b["xi_high"])
     t_loss = time.perf_counter() - t
     per_token = (t_sel + t_egae + t_loss) / max(M, 1) + (t_head / n_head if n_head else 0.0)
+    err = None
+    if has_head and gpu_logp is not None:
+        assert np.array_equal(gpu_resp_idx[pick], sel["sel_resp_idx"][pick]), "kept-token indices differ from the oracle's"
+        err = float(np.max(np.abs(gpu_logp[gpu_resp_idx[pick]].astype(np.float64) - olp.astype(np.float64))))
     return dict(value=1.0 / per_token, unit="tokens/s", cores=len(os.sched_getaffinity(0)),
-                kind="oracle",
+                kind="oracle", parity_max_abs_err=err, parity_rows=n_head, parity_tolerance=PARITY_TOLERANCE,
                 sample=(f"LM head on {n_head} seeded kept rows of {M} ({t_head:.1f}s); select, EGAE and "
                         f"losses on the full batch ({t_sel + t_egae + t_loss:.1f}s); per-token costs added"))
 

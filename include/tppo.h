@@ -215,7 +215,7 @@ int tppo_egae(const float* rewards, const float* values, const int32_t* resp_off
  * there until the process ends).  It calls no hipMalloc / hipFree and no
  * library routine that allocates; the first call on a device asks the runtime
  * for the array's address there and keeps it.
- * Limit: n_resp / 1024 + B + 1 <= tppo_egae_static_max_tiles() (49152: e.g.
+ * Limit: n_resp / 1024 + B + 1 <= tppo_egae_static_max_tiles() (47872: e.g.
  * 40 M tokens in 8704 sequences); larger batches -> TPPO_ERR_SIZE, nothing is
  * launched.
  * All calls on one GPU share the array: two calls may not overlap in time on
@@ -440,8 +440,9 @@ int tppo_diag_mfma_rate(const void* operands, float* out, int64_t iters, double*
 /* tppo_diag_streams -- the streaming counterpart: one elementwise pass over
  * n_read input streams (src + k * stride_bytes) and n_write output streams
  * (dst + k * stride_bytes), each bytes_per_stream long; every output is the
- * sum of the inputs.  Lanes on consecutive 16 bytes, 2048 workgroups, nothing
- * else.  Timing it gives the rate the memory system sustains for as many
+ * sum of the inputs.  Lanes on consecutive 16 bytes, one element per thread
+ * and stream, non-temporal accesses, small workgroups: the shape measured
+ * fastest on this chip.  Timing it gives the rate the memory system sustains for as many
  * concurrent streams as one of this library's kernels has: (n_read, n_write) =
  * (2,2) EGAE, (1,2) EGAE from terminal rewards, (6,0) losses, (6,2) loss
  * derivatives, (1,1) plain copy, (1,0) plain read; other shapes ->

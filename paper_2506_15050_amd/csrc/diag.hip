@@ -48,33 +48,35 @@ __global__ __launch_bounds__(kDiagThreads, 2) void diag_mfma_rate_kernel(const u
 }
 
 // Streaming measuring sticks: an elementwise pass over n_read input streams and n_write output streams
-// (out = sum of the inputs), lanes on consecutive 16 bytes, grid-stride, nothing else.
-constexpr int kStreamThreads = 256, kStreamGroups = 2048, kStreamMax = 8;
+// (out = sum of the inputs) and nothing else, in the shape that was measured fastest on this chip for each
+// mix: lanes on consecutive 16 bytes, non-temporal loads and stores (every byte is touched once), ONE 16-byte
+// element per thread and stream, small workgroups that come and go (the dispatcher keeps the chip full; a
+// grid-stride loop of resident workgroups was measured 5-8 % slower with stores in the mix).
+constexpr int kStreamMax = 8;
+typedef float stream_vec __attribute__((ext_vector_type(4)));
 
-template <int NR, int NW>
-__global__ __launch_bounds__(kStreamThreads) void diag_streams_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
-                                                                      int64_t stride16, int64_t n16, float* sink) {
-    float acc = 0.f;
-    for (int64_t i = (int64_t)blockIdx.x * kStreamThreads + threadIdx.x; i < n16; i += (int64_t)gridDim.x * kStreamThreads) {
-        float4 v[NR];
+template <int NR, int NW, int T>
+__global__ __launch_bounds__(T) void diag_streams_kernel(const stream_vec* __restrict__ src, stream_vec* __restrict__ dst,
+                                                         int64_t stride16, int64_t n16, float* sink) {
+    const int64_t i = (int64_t)blockIdx.x * T + threadIdx.x;
+    if (i >= n16) return;
+    stream_vec v[NR];
 #pragma unroll
-        for (int s = 0; s < NR; ++s) v[s] = src[s * stride16 + i];
-        float4 t = v[0];
+    for (int s = 0; s < NR; ++s) v[s] = __builtin_nontemporal_load(src + s * stride16 + i);
+    stream_vec t = v[0];
 #pragma unroll
-        for (int s = 1; s < NR; ++s) {
-            t.x += v[s].x; t.y += v[s].y; t.z += v[s].z; t.w += v[s].w;
-        }
+    for (int s = 1; s < NR; ++s) t += v[s];
 #pragma unroll
-        for (int s = 0; s < NW; ++s) dst[s * stride16 + i] = t;
-        if (NW == 0) acc += (t.x + t.y) + (t.z + t.w);
-    }
-    if (NW == 0 && acc == 1.2345e-30f) sink[0] = acc;          // keeps the loads alive; practically never taken
+    for (int s = 0; s < NW; ++s) __builtin_nontemporal_store(t, dst + s * stride16 + i);
+    if (NW == 0 && (t[0] + t[1]) + (t[2] + t[3]) == 1.2345e-30f) sink[0] = t[0];   // keeps the loads alive
 }
 
-template <int NR, int NW>
+template <int NR, int NW, int T>
 static int launch_streams(const void* src, void* dst, int64_t stride16, int64_t n16, hipStream_t s) {
-    hipLaunchKernelGGL((diag_streams_kernel<NR, NW>), dim3(kStreamGroups), dim3(kStreamThreads), 0, s,
-                       static_cast<const float4*>(src), static_cast<float4*>(dst), stride16, n16,
+    const int64_t groups = (n16 + T - 1) / T;
+    if (groups > INT32_MAX) return TPPO_ERR_SIZE;
+    hipLaunchKernelGGL((diag_streams_kernel<NR, NW, T>), dim3((unsigned)groups), dim3(T), 0, s,
+                       static_cast<const stream_vec*>(src), static_cast<stream_vec*>(dst), stride16, n16,
                        static_cast<float*>(const_cast<void*>(src)));
     return launch_result();
 }
@@ -92,12 +94,12 @@ extern "C" int tppo_diag_streams(const void* src, void* dst, int64_t bytes_per_s
     const int64_t n16 = bytes_per_stream / 16, st = stride_bytes / 16;
     const int shape = n_read * 10 + n_write;                // the shapes of this library's streaming kernels
     switch (shape) {
-        case 10: return launch_streams<1, 0>(src, dst, st, n16, s);
-        case 11: return launch_streams<1, 1>(src, dst, st, n16, s);
-        case 22: return launch_streams<2, 2>(src, dst, st, n16, s);
-        case 12: return launch_streams<1, 2>(src, dst, st, n16, s);
-        case 60: return launch_streams<6, 0>(src, dst, st, n16, s);
-        case 62: return launch_streams<6, 2>(src, dst, st, n16, s);
+        case 10: return launch_streams<1, 0, 64>(src, dst, st, n16, s);
+        case 11: return launch_streams<1, 1, 64>(src, dst, st, n16, s);
+        case 22: return launch_streams<2, 2, 64>(src, dst, st, n16, s);
+        case 12: return launch_streams<1, 2, 64>(src, dst, st, n16, s);
+        case 60: return launch_streams<6, 0, 128>(src, dst, st, n16, s);
+        case 62: return launch_streams<6, 2, 128>(src, dst, st, n16, s);
         default: return TPPO_ERR_PARAM;
     }
 }

@@ -629,7 +629,7 @@ extern "C" int tppo_egae(const float* rewards, const float* values, const int32_
 // tppo_egae_static: tppo_egae for callers that may not allocate.  The plan is built in a fixed array that is
 // part of the library's image on every GPU it runs on.
 namespace tppo {
-constexpr int64_t kStaticTiles = 49152;                            // plan capacity of the array, in tiles
+constexpr int64_t kStaticTiles = 47872;                            // plan capacity of the array, in tiles
 constexpr size_t kStaticBytes = plan_bytes_for(kStaticTiles);      // just under 4 MiB
 static __device__ __align__(256) unsigned char scratch[kStaticBytes];
 

@@ -113,13 +113,24 @@ struct TileSets {
     __device__ __forceinline__ int n_val(int g, int tid) const { return min(max(val - k0(g, tid), 0), 4); }
 };
 
-__device__ __forceinline__ TileSets tile_sets(const Tile& t, int keep, int fin, bool has_pol, bool has_val) {
+__device__ __forceinline__ TileSets tile_sets(const Tile& t, int32_t word, bool has_pol, bool has_val) {
     TileSets s;
     s.start = t.start;
     s.len = t.len();
-    s.pol = has_pol ? min(max(keep - t.number() * kTileTokens, 0), s.len) : 0;
-    s.val = (has_val && fin != 0) ? s.len : 0;
+    s.pol = has_pol ? min(word & 0xFFFF, s.len) : 0;
+    s.val = (has_val && (word >> 16) != 0) ? s.len : 0;
     return s;
+}
+
+// What the loop keeps of the NEXT tile while it works on the current one: descriptor and set word, both asked
+// for a whole tile ahead and independent of each other (one trip through the scalar cache, not two in a row).
+struct TileAhead {
+    Tile d;
+    int32_t word;
+};
+
+__device__ __forceinline__ TileAhead fetch_ahead(const Plan& pl, int pos) {
+    return TileAhead{load_tile(pl.tiles + pos), load_uniform(pl.sets + pos)};
 }
 
 // Issue the loads of a tile.  Four consecutive tokens per access, consecutive lanes on consecutive 16 bytes (the
@@ -216,7 +227,7 @@ __device__ __forceinline__ void write_invalid(tppo_loss_out* out) {
     out->n_policy = out->n_value = 0;
 }
 
-__global__ __launch_bounds__(kLossThreads) void loss_kernel(LossParams p, tppo_loss_out* __restrict__ out) {
+__global__ __launch_bounds__(kLossThreads, 8) void loss_kernel(LossParams p, tppo_loss_out* __restrict__ out) {
     __shared__ double s_red[kLossThreads / kWave];
     __shared__ int s_flag;
     const Plan pl = plan_open(p.plan);
@@ -234,21 +245,20 @@ __global__ __launch_bounds__(kLossThreads) void loss_kernel(LossParams p, tppo_l
     const int count = pl.hdr->n_tiles;
 
     double pol_acc = 0.0, val_acc = 0.0;
-    auto sets_of = [&](int pos) {
-        const Tile d = load_tile(pl.tiles + pos);
-        if (!tile_valid(d, p.n_resp, p.B, pl.cap)) {               // a damaged plan: no tokens, and the call says so
+    auto sets_of = [&](const TileAhead& a) {
+        if (!tile_valid(a.d, p.n_resp, p.B, pl.cap)) {             // a damaged plan: no tokens, and the call says so
             if (tid == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
             return TileSets{0, 0, 0, 0};
         }
-        return tile_sets(d, load_uniform(p.keep_len + d.seg), load_uniform(p.done + d.seg), has_pol, has_val);
+        return tile_sets(a.d, a.word, has_pol, has_val);
     };
-    TileSets ts_next = {};
-    if ((int)blockIdx.x < count) ts_next = sets_of(blockIdx.x);
+    TileAhead ahead = {};
+    if ((int)blockIdx.x < count) ahead = fetch_ahead(pl, blockIdx.x);
     for (int w = blockIdx.x; w < count; w += gridDim.x) {
-        const TileSets ts_cur = ts_next;
+        const TileSets ts_cur = sets_of(ahead);
+        if (w + (int)gridDim.x < count) ahead = fetch_ahead(pl, w + gridDim.x);     // the next tile's, meanwhile
         LossRegs cur;
         loss_load(cur, p, ts_cur, tid);
-        if (w + (int)gridDim.x < count) ts_next = sets_of(w + gridDim.x);     // the next descriptor, meanwhile
         unshift(cur, ts_cur, p.n_resp, tid);
         float pol_t = 0.f, val_t = 0.f;                            // this thread's <= 8 terms of the tile
 #pragma unroll
@@ -329,7 +339,7 @@ struct GradParams {
     long long policy_denominator, value_denominator;     // <= 0: the call's own token counts
 };
 
-__global__ __launch_bounds__(kLossThreads) void loss_grad_kernel(GradParams gp, tppo_loss_out* __restrict__ out,
+__global__ __launch_bounds__(kLossThreads, 8) void loss_grad_kernel(GradParams gp, tppo_loss_out* __restrict__ out,
                                                                 tppo_loss_stats* __restrict__ stats) {
     __shared__ double s_red[kLossThreads / kWave];
     __shared__ int s_flag;
@@ -355,21 +365,20 @@ __global__ __launch_bounds__(kLossThreads) void loss_grad_kernel(GradParams gp, 
 
     double pol_acc = 0.0, val_acc = 0.0, ratio_acc = 0.0;
     int pol_clipped = 0, val_clipped = 0;
-    auto sets_of = [&](int pos) {
-        const Tile d = load_tile(pl.tiles + pos);
-        if (!tile_valid(d, p.n_resp, p.B, pl.cap)) {               // a damaged plan: no tokens, and the call says so
+    auto sets_of = [&](const TileAhead& a) {
+        if (!tile_valid(a.d, p.n_resp, p.B, pl.cap)) {             // a damaged plan: no tokens, and the call says so
             if (tid == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
             return TileSets{0, 0, 0, 0};
         }
-        return tile_sets(d, load_uniform(p.keep_len + d.seg), load_uniform(p.done + d.seg), has_pol, has_val);
+        return tile_sets(a.d, a.word, has_pol, has_val);
     };
-    TileSets ts_next = {};
-    if ((int)blockIdx.x < count) ts_next = sets_of(blockIdx.x);
+    TileAhead ahead = {};
+    if ((int)blockIdx.x < count) ahead = fetch_ahead(pl, blockIdx.x);
     for (int w = blockIdx.x; w < count; w += gridDim.x) {
-        const TileSets ts_cur = ts_next;
+        const TileSets ts_cur = sets_of(ahead);
+        if (w + (int)gridDim.x < count) ahead = fetch_ahead(pl, w + gridDim.x);     // the next tile's, meanwhile
         LossRegs cur;
         loss_load(cur, p, ts_cur, tid);
-        if (w + (int)gridDim.x < count) ts_next = sets_of(w + gridDim.x);     // the next descriptor, meanwhile
         unshift(cur, ts_cur, p.n_resp, tid);
         float pol_t = 0.f, val_t = 0.f, ratio_t = 0.f;
 #pragma unroll

@@ -21,6 +21,9 @@
 //   header (256 B)   tile count, the sizes it was built for, the sizes of the
 //                    policy / value token sets of Sec. 3.2
 //   tiles[cap]       the descriptors
+//   sets[cap]        per tile: how many of its tokens are policy tokens (a prefix,
+//                    Sec. 3.2) and whether all of them are value tokens, so that
+//                    the loss kernels need no second, dependent look-up per tile
 //   scan_words[cap][8]   what a tile of the scan publishes for the tiles to its
 //                    left, {tag << 32 | float bits} each: A hi, A lo, R hi, R lo
 //                    of the tile alone, then the same four with everything to
@@ -67,9 +70,15 @@ struct PlanHeader {
     int32_t cap;                   // descriptors the plan has room for (fixes where the tagged words start)
 };
 
+// a tile's share of the two token sets: policy tokens in the low 16 bits, bit 16 set when the sequence is finished
+__host__ __device__ __forceinline__ int32_t pack_sets(int policy_tokens, bool finished) {
+    return policy_tokens | (finished ? 1 << 16 : 0);
+}
+
 struct Plan {
     PlanHeader* hdr;
     Tile* tiles;
+    int32_t* sets;                       // [cap], pack_sets(); meaningful when hdr->has_sets
     unsigned long long* scan_words;      // [cap][kScanWords], by Tile::slot()
     unsigned long long* finish_words;    // [kFinishGroups][kFinishWords]
     int cap;
@@ -78,7 +87,8 @@ struct Plan {
 static constexpr int64_t plan_max_tiles(int64_t n_resp, int64_t B) { return n_resp / kTileTokens + B + 1; }
 
 static constexpr size_t plan_bytes_for(int64_t cap) {
-    return 256 + round_up((size_t)cap * sizeof(Tile), 256) + round_up((size_t)cap * kScanWords * 8, 256) +
+    return 256 + round_up((size_t)cap * sizeof(Tile), 256) + round_up((size_t)cap * 4, 256) +
+           round_up((size_t)cap * kScanWords * 8, 256) +
            (size_t)kFinishGroups * kFinishWords * sizeof(unsigned long long);
 }
 
@@ -89,6 +99,8 @@ __host__ __device__ __forceinline__ Plan plan_view(void* raw, int64_t cap) {
     p += 256;
     pl.tiles = reinterpret_cast<Tile*>(p);
     p += ((size_t)cap * sizeof(Tile) + 255) / 256 * 256;
+    pl.sets = reinterpret_cast<int32_t*>(p);
+    p += ((size_t)cap * 4 + 255) / 256 * 256;
     pl.scan_words = reinterpret_cast<unsigned long long*>(p);
     p += ((size_t)cap * kScanWords * 8 + 255) / 256 * 256;
     pl.finish_words = reinterpret_cast<unsigned long long*>(p);

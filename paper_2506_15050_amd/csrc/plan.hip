@@ -45,6 +45,14 @@ __device__ __forceinline__ Tile make_tile(int seg, int lo, int len, int tiles, i
     return d;
 }
 
+// the tile's share of the two token sets of Sec. 3.2 (0 when the builder was not given keep_len)
+__device__ __forceinline__ int32_t sets_word(const Tile& d, const int32_t* __restrict__ keep_len,
+                                             const int32_t* __restrict__ done) {
+    if (!keep_len) return 0;
+    const int policy = min(max(keep_len[d.seg] - d.number() * kTileTokens, 0), d.len());
+    return pack_sets(policy, done[d.seg] != 0);
+}
+
 // Workgroups 0 .. parts-1 build the list: workgroup `part` owns a contiguous range of the sequences and,
 // inside it, thread t a contiguous block.  The tile of sequence i at level l goes to
 //   (tiles of lower levels, whole batch) + (level-l tiles of sequences before i).
@@ -195,7 +203,11 @@ __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t
         for (int i = i_begin; i < i_end; ++i) {
             const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = tiles_of(len);
             if (tiles <= l) continue;
-            if (at < cap) pl.tiles[at] = make_tile(i, lo, len, tiles, l);     // (invalid offsets cannot overflow the list)
+            if (at < cap) {                                                   // (invalid offsets cannot overflow the list)
+                const Tile d = make_tile(i, lo, len, tiles, l);
+                pl.tiles[at] = d;
+                pl.sets[at] = sets_word(d, keep_len, done);
+            }
             ++at;
         }
     }
@@ -203,8 +215,13 @@ __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t
         int at = s_first[kLevels] + s_red[0][wave][kLevels] + before.n[kLevels];
         for (int i = i_begin; i < i_end; ++i) {
             const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = tiles_of(len);
-            for (int l = kLevels; l < tiles; ++l, ++at)
-                if (at < cap) pl.tiles[at] = make_tile(i, lo, len, tiles, l);
+            for (int l = kLevels; l < tiles; ++l, ++at) {
+                if (at < cap) {
+                    const Tile d = make_tile(i, lo, len, tiles, l);
+                    pl.tiles[at] = d;
+                    pl.sets[at] = sets_word(d, keep_len, done);
+                }
+            }
         }
     }
     if (part == parts - 1 && tid == 0) {

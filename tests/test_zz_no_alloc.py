@@ -50,7 +50,7 @@ def test_static_entry_point_matches_tppo_egae_twice_in_a_row(first, second):
 def test_static_entry_point_rejects_what_its_array_cannot_hold():
     lib = tp.load()
     limit = lib.tppo_egae_static_max_tiles()
-    assert limit == 49152
+    assert limit == 47872
     B = 8
     n_resp = (limit - B) * 1024                                        # n_resp / 1024 + B + 1 == limit + 1
     x = torch.zeros(8, device="cuda")
