@@ -15,11 +15,19 @@
  * Conventions common to every entry point
  *   - Every array pointer is DEVICE memory owned by the caller, valid until the
  *     work enqueued by the call has finished.  The library allocates nothing and
- *     frees nothing.  The only state it keeps is a process-wide call counter
- *     (each launch that lets workgroups exchange partial results tags them with
- *     its call number, which is why scratch memory needs no clearing between
- *     calls) and, for tppo_token_logprobs*, a one-time per-process kernel
- *     attribute.  No environment variable is read.
+ *     frees nothing.  The state it keeps: a process-wide call counter (each
+ *     launch that lets workgroups exchange partial results tags them with its
+ *     call number, which is why scratch memory needs no clearing between
+ *     calls), and what it learns or sets once per device on first use -- the
+ *     number of compute units, the large-LDS attribute of the
+ *     tppo_token_logprobs* kernels, the address of tppo_egae_static's array.
+ *     All of it is kept in atomics; calls from several threads are safe.  No
+ *     environment variable is read.
+ *   - The matrix-core kernels of tppo_token_logprobs* are scheduled for the
+ *     whole MI355X (256 compute units in 8 XCDs).  On a device that reports
+ *     another number of compute units (a partition of the chip) the bf16 path
+ *     returns TPPO_ERR_LAUNCH instead of running with its workgroups taking
+ *     turns.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     All work is enqueued asynchronously on it; no call synchronises with the
  *     host, which is why scalar results are written to device memory.
@@ -59,7 +67,7 @@ typedef enum {
     TPPO_ERR_PARAM = -3,     /* scalar out of range (gamma, lambda outside [0,1]; negative eps, xi, tail_drop) */
     TPPO_ERR_DTYPE = -4,     /* unknown tppo_dtype */
     TPPO_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small */
-    TPPO_ERR_LAUNCH = -6     /* the HIP runtime refused a launch */
+    TPPO_ERR_LAUNCH = -6     /* the HIP runtime refused a launch, or the device is not one the kernel is scheduled for */
 } tppo_error;
 
 /* bits of the device status word */

@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256) void head_combine_kernel(
     if (lse) lse[o] = l;
 }
 
-// Kernel variants (TPPO_HEAD_VARIANT selects one; 0 is the default).
+// Kernel variants (0 is what the library runs; a tuning build can select another through TPPO_HEAD_VARIANT).
 using Cfg0 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 32, 16, 8>;   // v_mfma_f32_16x16x32_bf16, one W block per MFMA step
 using Cfg1 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 16, 32>;      // v_mfma_f32_32x32x16_bf16
 using Cfg2 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 0, 32>;       // the same, transfers issued back to back
@@ -275,9 +275,11 @@ static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 static const HeadVariant& pick_variant() {
-    const char* e = getenv("TPPO_HEAD_VARIANT");
-    int id = e ? atoi(e) : 0;
+    int id = 0;
+#ifdef TPPO_TUNING
+    if (const char* e = getenv("TPPO_HEAD_VARIANT")) id = atoi(e);       // tuning builds only
     if (id < 0 || id >= kNumVariants) id = 0;
+#endif
     return kVariants[id];
 }
 

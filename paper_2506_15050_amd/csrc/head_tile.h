@@ -6,6 +6,8 @@
 #pragma once
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "common.h"
 
 namespace tppo {
@@ -391,10 +393,12 @@ static int choose_splits(const HeadVariant& hv, int64_t M, int64_t V) {
     const int64_t row_tiles = (M + hv.tile_t - 1) / hv.tile_t, vocab_tiles = (V + hv.tile_v - 1) / hv.tile_v;
     const int64_t unit_rows = (row_tiles + 7) / 8;
     const int max_s = (int)(vocab_tiles < kMaxSplits ? vocab_tiles : kMaxSplits);
-    if (const char* e = getenv("TPPO_HEAD_SPLITS")) {       // tuning override
+#ifdef TPPO_TUNING
+    if (const char* e = getenv("TPPO_HEAD_SPLITS")) {       // tuning builds only
         const int forced = atoi(e);
         if (forced >= 1 && (forced < 4 || forced % 4 == 0)) return forced < max_s ? forced : max_s < 4 ? max_s : max_s / 4 * 4;
     }
+#endif
     int best = 1;
     double best_cost = 1e300;
     for (int s = 1; s <= max_s; ++s) {
@@ -427,19 +431,46 @@ static void plan_sweep(HeadParams& p, const HeadVariant& hv, int64_t M, int64_t 
     p.unit_cols = p.splits / p.unit_splits;
     p.unit_rows = (p.row_tiles + 7) / 8;
     p.n_units = p.unit_rows * p.unit_cols;
-    const char* e = getenv("TPPO_HEAD_ORDER");
-    p.col_major = e ? atoi(e) : 1;                        // tuning override: 0 = units in row-major order
+    p.col_major = 1;
+#ifdef TPPO_TUNING
+    if (const char* e = getenv("TPPO_HEAD_ORDER")) p.col_major = atoi(e);     // tuning builds only: 0 = row-major units
+#endif
     p.unit_arrivals = static_cast<int32_t*>(arrivals);
 }
 
-// Clear the arrival counters and launch one sweep (persistent: one workgroup per CU).
+// The schedule above is laid out for the whole MI355X: 256 compute units, hardware workgroup id b on XCD b % 8.
+constexpr int kSweepGroups = 256;
+
+// A kernel that wants more than 64 KiB of LDS has to be told so once per device.
+static bool allow_lds(const HeadVariant& hv) {
+    constexpr int kMaxDevices = 64, kMaxKernels = 8;
+    static std::atomic<const void*> done[kMaxDevices][kMaxKernels];
+    const void* fn = reinterpret_cast<const void*>(hv.kernel);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return false;
+    std::atomic<const void*>* row = dev < kMaxDevices ? done[dev] : nullptr;
+    int free_slot = -1;
+    if (row) {
+        for (int i = 0; i < kMaxKernels; ++i) {
+            const void* seen = row[i].load(std::memory_order_acquire);
+            if (seen == fn) return true;
+            if (!seen && free_slot < 0) free_slot = i;
+        }
+    }
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, hv.lds_bytes) != hipSuccess) return false;
+    if (row && free_slot >= 0) row[free_slot].store(fn, std::memory_order_release);   // (a lost race only repeats the call)
+    return true;
+}
+
+// Clear the arrival counters and launch one sweep (persistent: one workgroup per CU).  A device that does not
+// report 256 compute units (a partition of the chip, another chip) is refused: the sweep would still be
+// correct there, but its workgroups would take turns instead of running side by side.
 static int launch_sweep(const HeadVariant& hv, const HeadParams& p, hipStream_t s) {
+    if (device_compute_units() != kSweepGroups) return TPPO_ERR_LAUNCH;
+    if (!allow_lds(hv)) return TPPO_ERR_LAUNCH;
     hipLaunchKernelGGL(head_clear_kernel, dim3((p.n_units + 255) / 256), dim3(256), 0, s, p.unit_arrivals, p.n_units);
     if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(hv.kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            hv.lds_bytes) != hipSuccess)
-        return TPPO_ERR_LAUNCH;
-    hipLaunchKernelGGL(hv.kernel, dim3(256), dim3(hv.threads), hv.lds_bytes, s, p);
+    hipLaunchKernelGGL(hv.kernel, dim3(kSweepGroups), dim3(hv.threads), hv.lds_bytes, s, p);
     return launch_result();
 }
 

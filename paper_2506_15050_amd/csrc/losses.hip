@@ -23,7 +23,10 @@
 
 namespace tppo {
 
-constexpr int kLossThreads = 256;
+#ifndef TPPO_LOSS_THREADS
+#define TPPO_LOSS_THREADS 256
+#endif
+constexpr int kLossThreads = TPPO_LOSS_THREADS;
 constexpr int kLossSlots = kTileTokens / (4 * kLossThreads);      // 16-byte groups per thread and array: 1
 constexpr int kLossGroups = 2048;                                  // workgroups of the persistent grid: 8 per CU
 constexpr int kFinishSpin = 1 << 20;

@@ -15,6 +15,21 @@ uint32_t next_call_tag() {
     return t;
 }
 
+int device_compute_units() {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> known[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return 0;
+    if (dev < kMaxDevices) {
+        const int v = known[dev].load(std::memory_order_relaxed);
+        if (v > 0) return v;
+    }
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (dev < kMaxDevices && cus > 0) known[dev].store(cus, std::memory_order_relaxed);
+    return cus;
+}
+
 __device__ __forceinline__ int window_of(const int32_t* __restrict__ resp_off, int i, int n_resp, int& lo,
                                          int32_t* status) {
     lo = resp_off[i];
