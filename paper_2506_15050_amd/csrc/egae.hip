@@ -224,10 +224,11 @@ struct TileMid {
 };
 typedef float lds_float4 __attribute__((ext_vector_type(4)));
 
-// Issue the loads of tile `t` (list position `pos`).  Slot j, lane l holds tokens k0 .. k0 + 3,
-// k0 = 4 (64 j + 63 - l).  Every lane with a token issues ONE 16-byte load per array: a group that straddles
-// the tile's end reads on into the next sequence (the surplus is zeroed later), and the one group that would
-// read past the END OF THE ARRAY reads the array's last 16 bytes instead (moved into place later).  No branch
+// Issue the loads of tile `t` (list position `pos`).  The tile is tokens begin .. end - 1 of an aligned block of
+// 1024 tokens of the arrays (plan.h); slot j, lane l holds the block's tokens k0 .. k0 + 3, k0 = 4 (64 j + 63 - l).
+// Every lane with a token issues ONE 16-byte load per array: a group that straddles an end of the tile reads
+// on into the neighbouring sequence (the surplus is zeroed later), and the one group that would read past the
+// END OF THE ARRAY reads the array's last 16 bytes instead (moved into place later).  No branch
 // and no wait separates the loads, so all of them are in flight together.  kTerminal: there is no reward array;
 // the only reward is terminal[seq] on the last token of a finished sequence (Sec. 2.1: the rule-based reward
 // arrives with the end of the response).
@@ -239,12 +240,13 @@ __device__ __forceinline__ void issue_tile(TileIn& x, const Tile& t, const EgaeP
     x.pos = pos;
     x.t = t;
     const int start = x.t.start, len = x.t.len(), seg = x.t.seg;
+    const int base = x.t.base(), begin = x.t.begin(), end = begin + len;
 #pragma unroll
     for (int j = 0; j < kSlots; ++j) {
         const int k0 = 4 * (64 * j + 63 - lane);
         float4u vv = {0.f, 0.f, 0.f, 0.f}, rr = {0.f, 0.f, 0.f, 0.f};
-        if (k0 < len) {
-            const int at = min(start + k0, p.n_resp - 4);
+        if (k0 + 4 > begin && k0 < end) {
+            const int at = min(base + k0, p.n_resp - 4);
             vv = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(values + at));
             if (!kTerminal) rr = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(rewards + at));
         }
@@ -284,18 +286,18 @@ __device__ __forceinline__ void tile_front(TileIn& x, TileMid& m, lds_float4* s_
                                            const LaneWeights& wr TPPO_STAMPS_ARG) {
     const double gamma = p.gamma, c = p.sa.m;
     const int n_resp = p.n_resp, pos = x.pos;
-    const int start = x.t.start, len = kFull ? kTileTokens : x.t.len();
+    const int base = x.t.base(), begin = kFull ? 0 : x.t.begin(), end = kFull ? kTileTokens : begin + x.t.len();
     // V(s_{t+1}) of the tile's last token: the next tile's first value, or the value of the state after the
     // sequence -- 0 for a finished one, else the bootstrap value, by default V(s_{l-1}) (Sec. 3.1)
     const bool fin = x.side_done != 0;
     const float v_end = x.t.after != 0 ? x.side_next : fin ? 0.f : p.bootstrap ? x.side_boot : x.side_last;
     const float terminal = (kTerminal && x.t.after == 0 && fin) ? x.side_term : 0.f;
     if (!kFull) {
-        if (__builtin_expect(start + len > n_resp - 4, 0)) {        // wave-uniform: the array's last tile
+        if (__builtin_expect(base + end > n_resp - 4, 0)) {         // wave-uniform: the array's last tile
 #pragma unroll
             for (int j = 0; j < kSlots; ++j) {
                 const int k0 = 4 * (64 * j + 63 - lane);
-                const int sh = k0 < len ? start + k0 - min(start + k0, n_resp - 4) : 0;
+                const int sh = (k0 + 4 > begin && k0 < end) ? base + k0 - min(base + k0, n_resp - 4) : 0;
                 float tv[4], tr[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -309,16 +311,19 @@ __device__ __forceinline__ void tile_front(TileIn& x, TileMid& m, lds_float4* s_
                 }
             }
         }
-        // Tokens past the tile's end become r = 0, V = 0, except that the slot after the last token takes the
-        // value that follows the tile: then Eq. (TD) needs no special case for the last token, and the
-        // residuals of the padding are zeroed where they are computed.
+        // The block's tokens outside the tile become r = 0, V = 0, except that the place after the last token
+        // takes the value that follows the tile: then Eq. (TD) needs no special case for the last token, and the
+        // residuals of the padding are zeroed where they are computed.  (Padding to the RIGHT of the tile, only
+        // in a sequence's last tile, sees no carry; padding to the left, only in a sequence's first tile, comes
+        // after the tile in scan order and feeds nothing: the recurrences pass through the padding unharmed.)
 #pragma unroll
         for (int j = 0; j < kSlots; ++j) {
             const int k0 = 4 * (64 * j + 63 - lane);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                x.r[j][e] = keep_if(x.r[j][e], k0 + e < len);
-                x.v[j][e] = k0 + e == len ? v_end : keep_if(x.v[j][e], k0 + e < len);
+                const bool in = k0 + e >= begin && k0 + e < end;
+                x.r[j][e] = keep_if(x.r[j][e], in);
+                x.v[j][e] = k0 + e == end ? v_end : keep_if(x.v[j][e], in);
             }
         }
     }
@@ -327,7 +332,7 @@ __device__ __forceinline__ void tile_front(TileIn& x, TileMid& m, lds_float4* s_
         for (int j = 0; j < kSlots; ++j) {
             const int k0 = 4 * (64 * j + 63 - lane);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) x.r[j][e] = keep_if(terminal, k0 + e == len - 1);
+            for (int e = 0; e < 4; ++e) x.r[j][e] = keep_if(terminal, k0 + e == end - 1);
         }
     }
     TPPO_STAMP(2);
@@ -347,7 +352,7 @@ __device__ __forceinline__ void tile_front(TileIn& x, TileMid& m, lds_float4* s_
 #pragma unroll
     for (int j = 0; j < kSlots; ++j) {
         double ba = 0.0, br = 0.0;
-        if (kFull || 256 * j < len) {                               // wave-uniform: an empty slot stays zero
+        if (kFull || (256 * j < end && 256 * (j + 1) > begin)) {    // wave-uniform: an empty slot stays zero
             const int k0 = 4 * (64 * j + 63 - lane);
             double vn = (double)v_next_run[j];
             lds_float4 la, lr;
@@ -355,7 +360,7 @@ __device__ __forceinline__ void tile_front(TileIn& x, TileMid& m, lds_float4* s_
             for (int e = 3; e >= 0; --e) {
                 const double vk = (double)x.v[j][e], rk = (double)x.r[j][e];
                 double delta = fma(gamma, vn, rk) - vk;             // Eq. (TD)
-                if (!kFull) delta = k0 + e < len ? delta : 0.0;
+                if (!kFull) delta = (k0 + e >= begin && k0 + e < end) ? delta : 0.0;
                 ba = fma(c, ba, delta);
                 br = fma(gamma, br, rk);
                 la[e] = (float)ba;
@@ -403,7 +408,7 @@ __device__ __forceinline__ void tile_back(const TileIn& x, const TileMid& m, con
     const int pos = x.pos;
     (void)pos;
     const double gamma = p.gamma, c = p.sa.m;
-    const int start = t.start, len = kFull ? kTileTokens : t.len(), after = t.after;
+    const int base = t.base(), begin = kFull ? 0 : t.begin(), end = kFull ? kTileTokens : begin + t.len(), after = t.after;
     double carry_a = 0.0, carry_r = 0.0;
     unsigned long long* words = &pl.scan_words[(int64_t)kScanWords * t.slot()];
     if (after != 0) {                                               // wave-uniform
@@ -447,7 +452,7 @@ __device__ __forceinline__ void tile_back(const TileIn& x, const TileMid& m, con
 #pragma unroll
     for (int j = kSlots - 1; j >= 0; --j) {
         const int k0 = 4 * (64 * j + 63 - lane);
-        if (kFull || 256 * j < len) {
+        if (kFull || (256 * j < end && 256 * (j + 1) > begin)) {
             const double xa = fma(wa.p, carry_a, dpp_move<kWaveShr1, 0xF>(m.inc_a[j]));
             const double xr = fma(wr.p, carry_r, dpp_move<kWaveShr1, 0xF>(m.inc_r[j]));
             const lds_float4 la = s_loc[(2 * j) * kWave + lane], lr = s_loc[(2 * j + 1) * kWave + lane];
@@ -457,20 +462,15 @@ __device__ __forceinline__ void tile_back(const TileIn& x, const TileMid& m, con
                 oa[e] = (float)fma(pw_a[e], xa, (double)la[e]);
                 orr[e] = (float)fma(pw_r[e], xr, (double)lr[e]);
             }
-            if (kFull || k0 + 4 <= len) {
-#ifdef TPPO_EGAE_PLAIN_STORES
-                *reinterpret_cast<float4u*>(adv + start + k0) = oa;
-                *reinterpret_cast<float4u*>(ret + start + k0) = orr;
-#else
-                __builtin_nontemporal_store(oa, reinterpret_cast<float4u*>(adv + start + k0));
-                __builtin_nontemporal_store(orr, reinterpret_cast<float4u*>(ret + start + k0));
-#endif
+            if (kFull || (k0 >= begin && k0 + 4 <= end)) {
+                __builtin_nontemporal_store(oa, reinterpret_cast<float4u*>(adv + base + k0));
+                __builtin_nontemporal_store(orr, reinterpret_cast<float4u*>(ret + base + k0));
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    if (k0 + e < len) {
-                        adv[start + k0 + e] = oa[e];
-                        ret[start + k0 + e] = orr[e];
+                    if (k0 + e >= begin && k0 + e < end) {
+                        adv[base + k0 + e] = oa[e];
+                        ret[base + k0 + e] = orr[e];
                     }
                 }
             }

@@ -1,7 +1,9 @@
 // Work plan shared by the EGAE scan and the loss kernels.
 //
 // The response-packed token array is cut into tiles of at most kTileTokens
-// tokens that never straddle two sequences.  A tile is described by 16 bytes,
+// tokens that never straddle two sequences, at multiples of kTileTokens of the
+// packed index: a sequence is a short first tile up to the next multiple, full
+// tiles that are aligned blocks of the arrays, and a short last tile.  A tile is described by 16 bytes,
 // so a wavefront learns everything about its tokens (which sequence, how far
 // into it, how many tiles follow) from ONE load instead of a chain of dependent
 // look-ups in the offset arrays.
@@ -58,6 +60,10 @@ struct Tile {
     int32_t after;     // tiles after it in the same sequence (0: it holds the sequence's last token)
     __device__ __forceinline__ int len() const { return (pos_len & ((1 << kTileShift) - 1)) + 1; }
     __device__ __forceinline__ int number() const { return pos_len >> kTileShift; }
+    // a tile lies inside one aligned block of kTileTokens tokens of the arrays: the block's first token, and
+    // where in the block the tile begins (0 for every tile but a sequence's first)
+    __device__ __forceinline__ int base() const { return start & ~(kTileTokens - 1); }
+    __device__ __forceinline__ int begin() const { return start & (kTileTokens - 1); }
     // consecutive for the tiles of a sequence, unique in the batch, below plan_max_tiles(n_resp, B)
     __device__ __forceinline__ int slot() const { return start / kTileTokens + seg; }
 };
@@ -84,6 +90,7 @@ struct Plan {
     int cap;
 };
 
+// most tiles a batch can have: a sequence has one more tile than multiples of kTileTokens inside it
 static constexpr int64_t plan_max_tiles(int64_t n_resp, int64_t B) { return n_resp / kTileTokens + B + 1; }
 
 static constexpr size_t plan_bytes_for(int64_t cap) {
@@ -145,7 +152,8 @@ __device__ __forceinline__ Tile uniform_tile(tile_bits x) {
 __device__ __forceinline__ bool tile_valid(const Tile& t, int n_resp, int B, int cap) {
     const int len = t.len();
     return t.start >= 0 && t.start <= n_resp - len && t.seg >= 0 && t.seg < B && t.after >= 0 && t.number() >= 0 &&
-           t.after < cap - t.slot() && (t.after == 0 || (len == kTileTokens && t.start + len < n_resp));
+           t.after < cap - t.slot() && t.begin() + len <= kTileTokens &&
+           (t.after == 0 || (t.begin() + len == kTileTokens && t.start + len < n_resp));
 }
 
 // number of 8-byte tagged words of a plan (scan words, then finish words: contiguous but for padding)

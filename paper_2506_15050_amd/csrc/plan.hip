@@ -50,21 +50,32 @@ __device__ __forceinline__ void count_sequence(LevelCounts& c, int tiles) {
     c.n[kLevels] += max(tiles - kLevels, 0);
 }
 
+// Tiles are cut at multiples of kTileTokens of the response-packed INDEX, not of the position inside the
+// sequence: every tile but a sequence's first and last is then a 4 KiB-aligned block of each array (given
+// aligned arrays), which is worth 10-15 % to a streaming kernel on this chip -- a wavefront's 1 KiB access
+// that straddles 128-byte lines costs an extra line each time.  The price is up to one more (short) tile per
+// sequence.
+__device__ __forceinline__ int window_tiles(int lo, int len) {
+    return len > 0 ? ((lo + len - 1) / kTileTokens) - (lo / kTileTokens) + 1 : 0;
+}
+
 __device__ __forceinline__ Tile make_tile(int seg, int lo, int len, int tiles, int after) {
     const int c = tiles - 1 - after;
+    const int block = lo / kTileTokens + c;                             // which aligned block of the arrays
+    const int first = max(lo, block * kTileTokens), last = min(lo + len, (block + 1) * kTileTokens);
     Tile d;
-    d.start = lo + c * kTileTokens;
-    d.pos_len = (c << kTileShift) | (min(kTileTokens, len - c * kTileTokens) - 1);
+    d.start = first;
+    d.pos_len = (c << kTileShift) | (last - first - 1);
     d.seg = seg;
     d.after = after;
     return d;
 }
 
 // the tile's share of the two token sets of Sec. 3.2 (0 when the builder was not given keep_len)
-__device__ __forceinline__ int32_t sets_word(const Tile& d, const int32_t* __restrict__ keep_len,
+__device__ __forceinline__ int32_t sets_word(const Tile& d, int lo, const int32_t* __restrict__ keep_len,
                                              const int32_t* __restrict__ done) {
     if (!keep_len) return 0;
-    const int policy = min(max(keep_len[d.seg] - d.number() * kTileTokens, 0), d.len());
+    const int policy = min(max(keep_len[d.seg] - (d.start - lo), 0), d.len());
     return pack_sets(policy, done[d.seg] != 0);
 }
 
@@ -139,7 +150,10 @@ __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t
     int lo;
     // levels the batch has (all the per-level work below is skipped beyond them)
     int top = 0;
-    for (int i = tid; i < B; i += kBuildThreads) top = max(top, tiles_of(window_of(resp_off, i, n_resp, lo, nullptr)));
+    for (int i = tid; i < B; i += kBuildThreads) {
+        const int len = window_of(resp_off, i, n_resp, lo, nullptr);
+        top = max(top, window_tiles(lo, len));
+    }
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) top = max(top, __shfl_xor(top, off));
     if (lane == 0) s_top[wave] = top;
@@ -150,7 +164,7 @@ __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t
     {   // per level: tiles in the whole batch, and those of the sequences before my range
         LevelCounts all = {}, ahead = {};
         for (int i = tid; i < B; i += kBuildThreads) {
-            const int tiles = tiles_of(window_of(resp_off, i, n_resp, lo, nullptr));
+            const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = window_tiles(lo, len);
             count_sequence(all, tiles);
             count_sequence(ahead, i < p_begin ? tiles : 0);
         }
@@ -187,7 +201,10 @@ __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t
     }
     // my block's tiles per level, and an exclusive prefix sum of them over the workgroup
     LevelCounts mine = {}, before;
-    for (int i = i_begin; i < i_end; ++i) count_sequence(mine, tiles_of(window_of(resp_off, i, n_resp, lo, status)));
+    for (int i = i_begin; i < i_end; ++i) {
+        const int len = window_of(resp_off, i, n_resp, lo, status);
+        count_sequence(mine, window_tiles(lo, len));
+    }
 #pragma unroll
     for (int l = 0; l <= kLevels; ++l) {
         int inc = mine.n[l];
@@ -216,12 +233,12 @@ __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t
         if (mine.n[l] == 0) continue;
         int at = s_first[l] + s_red[0][wave][l] + before.n[l];
         for (int i = i_begin; i < i_end; ++i) {
-            const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = tiles_of(len);
+            const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = window_tiles(lo, len);
             if (tiles <= l) continue;
             if (at < cap) {                                                   // (invalid offsets cannot overflow the list)
                 const Tile d = make_tile(i, lo, len, tiles, l);
                 pl.tiles[at] = d;
-                pl.sets[at] = sets_word(d, keep_len, done);
+                pl.sets[at] = sets_word(d, lo, keep_len, done);
             }
             ++at;
         }
@@ -229,12 +246,12 @@ __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t
     if (mine.n[kLevels] != 0) {
         int at = s_first[kLevels] + s_red[0][wave][kLevels] + before.n[kLevels];
         for (int i = i_begin; i < i_end; ++i) {
-            const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = tiles_of(len);
+            const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = window_tiles(lo, len);
             for (int l = kLevels; l < tiles; ++l, ++at) {
                 if (at < cap) {
                     const Tile d = make_tile(i, lo, len, tiles, l);
                     pl.tiles[at] = d;
-                    pl.sets[at] = sets_word(d, keep_len, done);
+                    pl.sets[at] = sets_word(d, lo, keep_len, done);
                 }
             }
         }

@@ -1262,9 +1262,11 @@ def all_stages_against_oracle(tp, rng, win, seed):
 @pytest.mark.timeout(600)
 def test_all_stages_at_the_largest_batch_the_abi_takes(tp):
     """~2^31 window tokens (the ABI's 32-bit token indices end there): a sub-batch of 40 sequences -- two
-    of them hundreds of chunks long -- repeated 1800-odd times.  Every copy must reproduce the first one
-    bit for bit (indices shifted by the copy's offset), the first and last copy are compared with the
-    oracle element by element, and the loss sums with the oracle's sums for the sub-batch times the copies."""
+    of them hundreds of tiles long -- repeated 1800-odd times.  Every copy must reproduce the first one:
+    bit for bit where the result is elementwise or an index (shifted by the copy's offset); to the EGAE
+    tolerance for advantages and returns, whose tiles are cut at multiples of 1024 of the packed index,
+    i.e. at different places in different copies.  The first and last copy are compared with the oracle
+    element by element, and the loss sums with the oracle's sums for the sub-batch times the copies."""
     import torch
     rng = np.random.default_rng(4242)
     win = np.concatenate([[700001, 0, 300007], np.exp(rng.uniform(np.log(256), np.log(20480), size=37)).astype(np.int64)])
@@ -1298,6 +1300,17 @@ def test_all_stages_at_the_largest_batch_the_abi_takes(tp):
                 return False
         return True
 
+    def close_in_every_copy(t, width, rtol):
+        """|t[c*width + k] - t[k]| <= rtol * max(|t[k]|, 1) for every copy c, checked on the device in slices"""
+        first = t[:width]
+        tol = rtol * first.abs().clamp(min=1.0)
+        for c0 in range(0, copies, 64):
+            c1 = min(c0 + 64, copies)
+            block = t[c0 * width:c1 * width].view(c1 - c0, width)
+            if not bool(((block - first) .abs() <= tol).all()):
+                return False
+        return True
+
     # ---- select
     ids_s = rng.integers(0, 50000, size=n_tok_sub).astype(np.int32)
     st = tp.new_status("cuda")
@@ -1324,7 +1337,7 @@ def test_all_stages_at_the_largest_batch_the_abi_takes(tp):
     for c in (0, copies - 1):
         assert_egae_close(host(adv[c * n_sub:(c + 1) * n_sub]), ref_a, "adv")
         assert_egae_close(host(ret[c * n_sub:(c + 1) * n_sub]), ref_r, "ret")
-    assert same_in_every_copy(adv, n_sub) and same_in_every_copy(ret, n_sub)
+    assert close_in_every_copy(adv, n_sub, 2 * EGAE_RTOL) and close_in_every_copy(ret, n_sub, 2 * EGAE_RTOL)
     del adv, ret
     torch.cuda.empty_cache()
 
