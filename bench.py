@@ -198,12 +198,14 @@ def main():
     if not has_head and not (args.no_reference_rates or args.metric_only):
         # what the memory system sustains for as many concurrent streams as each kernel has, on arrays of the
         # same length, cold (each launch walks its own part of a 2 GB pool: nothing comes from the 256 MB cache)
-        per_stream = (4 * n_resp + 15) // 16 * 16
-        pool_r = torch.zeros(6 * 2 * per_stream // 4 + 64, device="cuda")
-        pool_w = torch.empty(2 * 2 * per_stream // 4 + 64, device="cuda")
+        per_stream = (4 * n_resp + 4095) // 4096 * 4096
+        pool_r = torch.zeros(6 * 2 * per_stream // 4 + 1024, device="cuda")
+        pool_w = torch.empty(2 * 2 * per_stream // 4 + 1024, device="cuda")
+        skip_r, skip_w = (-pool_r.data_ptr()) % 4096 // 4, (-pool_w.data_ptr()) % 4096 // 4
 
         def rate(n_read, n_write):
-            run = lambda half: tp.tppo_diag_streams(pool_r[half * 6 * per_stream // 4:], pool_w[half * 2 * per_stream // 4:],
+            run = lambda half: tp.tppo_diag_streams(pool_r[skip_r + half * 6 * per_stream // 4:],
+                                                    pool_w[skip_w + half * 2 * per_stream // 4:],
                                                     per_stream, per_stream, n_read, n_write)
             run(0); run(1)
             torch.cuda.synchronize()
@@ -410,9 +412,12 @@ def streaming_rooflines(tp, synth, steps):
     for a in sets:
         egae(a)
     torch.cuda.synchronize()
-    per_stream = (4 * n + 15) // 16 * 16
-    pool_r = torch.zeros(3 * 6 * per_stream // 4 + 64, device="cuda")
-    pool_w = torch.empty(3 * 2 * per_stream // 4 + 64, device="cuda")
+    # the elementwise pass beside each kernel: same number of streams, same bytes per stream, streams 4 KiB-aligned
+    # (as the kernels' full tiles are; misaligned streams cost such a pass ~15 %)
+    per_stream = (4 * n + 4095) // 4096 * 4096
+    pool_r = torch.zeros(3 * 6 * per_stream // 4 + 1024, device="cuda")
+    pool_w = torch.empty(3 * 2 * per_stream // 4 + 1024, device="cuda")
+    skip_r, skip_w = (-pool_r.data_ptr()) % 4096 // 4, (-pool_w.data_ptr()) % 4096 // 4
 
     def timed(fn, reps):
         for a in sets:
@@ -427,7 +432,8 @@ def streaming_rooflines(tp, synth, steps):
         return float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs])) * 1e-3
 
     def ceiling(n_read, n_write):
-        run = lambda k: tp.tppo_diag_streams(pool_r[k * 6 * per_stream // 4:], pool_w[k * 2 * per_stream // 4:],
+        run = lambda k: tp.tppo_diag_streams(pool_r[skip_r + k * 6 * per_stream // 4:],
+                                             pool_w[skip_w + k * 2 * per_stream // 4:],
                                              per_stream, per_stream, n_read, n_write)
         for k in range(3):
             run(k)

@@ -493,9 +493,15 @@ __global__ __launch_bounds__(kWave, kEgaeMinWaves) void egae_scan_kernel(EgaePar
     __shared__ lds_float4 s_loc[2 * kSlots * kWave];
     TPPO_STAMPS_DECL;
     TPPO_STAMP(7);
-    const Plan pl = plan_open(p.plan);
     const int lane = threadIdx.x;
     const int pos = blockIdx.x;
+    // The descriptor is asked for before anything is known about the plan -- its place depends on the plan's
+    // address alone, and the caller guarantees a buffer that holds gridDim.x descriptors -- so that it travels
+    // together with the header instead of after it.  As a vector load: the wavefront waits for it, and a scalar
+    // load that misses is several times slower.
+    const int zero = opaque_zero();
+    const tile_bits raw = fetch_tile(reinterpret_cast<const Tile*>(static_cast<const char*>(p.plan) + 256) + pos, zero);
+    const Plan pl = plan_open(p.plan);
     const int n_tiles = load_uniform(&pl.hdr->n_tiles);
     if (load_uniform(&pl.hdr->B) != p.B || load_uniform(&pl.hdr->n_resp) != p.n_resp || n_tiles > pl.cap ||
         pl.cap < (int)gridDim.x) {                                  // a plan built for another batch
@@ -503,10 +509,7 @@ __global__ __launch_bounds__(kWave, kEgaeMinWaves) void egae_scan_kernel(EgaePar
         return;
     }
     if (pos >= n_tiles) return;                                     // the list is shorter than its capacity
-    // the descriptor as a vector load: the wavefront waits for it, and a scalar load that misses is several
-    // times slower
-    const int zero = opaque_zero();
-    const Tile t = uniform_tile(fetch_tile(pl.tiles + pos, zero));
+    const Tile t = uniform_tile(raw);
     if (!tile_valid(t, p.n_resp, p.B, pl.cap)) {
         if (lane == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
         return;
