@@ -41,15 +41,6 @@ __device__ __forceinline__ int window_of(const int32_t* __restrict__ resp_off, i
     return hi - lo;
 }
 
-// n[l], l < kLevels: sequences with more than l tiles, i.e. tiles of level l; n[kLevels]: tiles of deeper levels
-struct LevelCounts { int n[kLevels + 1]; };
-
-__device__ __forceinline__ void count_sequence(LevelCounts& c, int tiles) {
-#pragma unroll
-    for (int l = 0; l < kLevels; ++l) c.n[l] += tiles > l ? 1 : 0;
-    c.n[kLevels] += max(tiles - kLevels, 0);
-}
-
 // Tiles are cut at multiples of kTileTokens of the response-packed INDEX, not of the position inside the
 // sequence: every tile but a sequence's first and last is then a 4 KiB-aligned block of each array (given
 // aligned arrays), which is worth 10-15 % to a streaming kernel on this chip -- a wavefront's 1 KiB access
@@ -57,6 +48,12 @@ __device__ __forceinline__ void count_sequence(LevelCounts& c, int tiles) {
 // sequence.
 __device__ __forceinline__ int window_tiles(int lo, int len) {
     return len > 0 ? ((lo + len - 1) / kTileTokens) - (lo / kTileTokens) + 1 : 0;
+}
+
+__device__ __forceinline__ int wave_max(int x) {
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) x = max(x, __shfl_xor(x, off));
+    return __builtin_amdgcn_readfirstlane(x);
 }
 
 __device__ __forceinline__ Tile make_tile(int seg, int lo, int len, int tiles, int after) {
@@ -71,22 +68,17 @@ __device__ __forceinline__ Tile make_tile(int seg, int lo, int len, int tiles, i
     return d;
 }
 
-// the tile's share of the two token sets of Sec. 3.2 (0 when the builder was not given keep_len)
-__device__ __forceinline__ int32_t sets_word(const Tile& d, int lo, const int32_t* __restrict__ keep_len,
-                                             const int32_t* __restrict__ done) {
-    if (!keep_len) return 0;
-    const int policy = min(max(keep_len[d.seg] - (d.start - lo), 0), d.len());
-    return pack_sets(policy, done[d.seg] != 0);
-}
-
 // Workgroups 0 .. parts-1 build the list: workgroup `part` owns a contiguous range of the sequences and,
-// inside it, thread t a contiguous block.  The tile of sequence i at level l goes to
-//   (tiles of lower levels, whole batch) + (level-l tiles of sequences before i).
-// Every builder counts the first term and the second term's share of the sequences before its range by
-// itself, from offsets that sit in the cache -- cheaper than a second launch; the share inside the range is
-// one workgroup-wide prefix sum per level over the threads' blocks.  Then each thread walks its block once
-// per level it has tiles at and writes the descriptors.  Workgroup `parts` counts the two token sets
-// meanwhile; the remaining workgroups zero the tagged words.
+// inside it, thread t a contiguous block.  A tile of level l goes to
+//   (tiles of lower levels, whole batch) + (level-l tiles of the sequences before the range)
+//   + (level-l tiles of the range's wavefronts before mine) + (its rank inside the wavefront).
+// Every builder counts the first two terms by itself, from offsets that sit in the cache -- cheaper than a
+// second launch.  All counting is by ballot, level by level, in loops that run as deep as the longest
+// sequence the wavefront is looking at: the code stays small (a kernel that runs once per batch pays for
+// every instruction-cache line it touches; the fully unrolled form of this one took 20 us on 32 sequences)
+// and short batches cost little.  Inside a level the order is whatever the ballots give; only the level order
+// matters.  Workgroup `parts` counts the two token sets meanwhile; the remaining workgroups zero the tagged
+// words.
 __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t* __restrict__ resp_off,
                                                                    const int32_t* __restrict__ keep_len,
                                                                    const int32_t* __restrict__ done, int B,
@@ -94,11 +86,12 @@ __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t
                                                                    int32_t* status) {
     constexpr int kWaves = kBuildThreads / kWave;
     __shared__ long long s_cnt[2][kWaves];
-    __shared__ int s_red[2][kWaves][kLevels + 1];
+    // per wavefront and level: tiles of the whole batch [0], of the sequences before my range [1], of my range [2]
+    // ([.][.][kLevels]: tiles beyond the sorted levels)
+    __shared__ int s_cnt3[3][kWaves][kLevels + 1];
     __shared__ int s_sum[2][kLevels + 1];
     __shared__ int s_first[kLevels + 1];                   // list position of the range's first tile of a level
     __shared__ int s_total;
-    __shared__ int s_top[kWaves];
     const Plan pl = plan_view(plan_raw, cap);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int block = blockIdx.x;
@@ -148,112 +141,110 @@ __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t
     const int per = (p_end - p_begin + kBuildThreads - 1) / kBuildThreads;
     const int i_begin = min(p_begin + tid * per, p_end), i_end = min(i_begin + per, p_end);
     int lo;
-    // levels the batch has (all the per-level work below is skipped beyond them)
-    int top = 0;
-    for (int i = tid; i < B; i += kBuildThreads) {
-        const int len = window_of(resp_off, i, n_resp, lo, nullptr);
-        top = max(top, window_tiles(lo, len));
-    }
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) top = max(top, __shfl_xor(top, off));
-    if (lane == 0) s_top[wave] = top;
+    for (int k = tid; k < 3 * kWaves * (kLevels + 1); k += kBuildThreads) (&s_cnt3[0][0][0])[k] = 0;
     __syncthreads();
-    for (int w = 0; w < kWaves; ++w) top = max(top, s_top[w]);
-    const int levels = min(top, kLevels);                  // wave-uniform, the same in every workgroup
-    const bool deep = top > kLevels;
-    {   // per level: tiles in the whole batch, and those of the sequences before my range
-        LevelCounts all = {}, ahead = {};
-        for (int i = tid; i < B; i += kBuildThreads) {
-            const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = window_tiles(lo, len);
-            count_sequence(all, tiles);
-            count_sequence(ahead, i < p_begin ? tiles : 0);
+    const unsigned long long below = (1ull << lane) - 1;          // lanes before mine
+    // wave-wide: add, per level, the lanes whose sequence has a tile there to row `row` of the counters
+    auto count_levels = [&](int which, int tiles) {
+        const int deepest = wave_max(tiles);
+        for (int l = 0; l < min(deepest, kLevels); ++l) {
+            const int c = __popcll(__ballot(tiles > l));
+            if (lane == 0) s_cnt3[which][wave][l] += c;
         }
+        if (deepest > kLevels) {                                    // tiles beyond the sorted levels
+            int extra = max(tiles - kLevels, 0);
 #pragma unroll
-        for (int l = 0; l <= kLevels; ++l) {
-            if (l < kLevels ? l < levels : deep) {
-#pragma unroll
-                for (int off = 1; off < kWave; off <<= 1) {
-                    all.n[l] += __shfl_xor(all.n[l], off);
-                    ahead.n[l] += __shfl_xor(ahead.n[l], off);
-                }
-            }
-            if (lane == 0) {
-                s_red[0][wave][l] = all.n[l];              // (zero where skipped: nothing was counted there)
-                s_red[1][wave][l] = ahead.n[l];
-            }
+            for (int off = 1; off < kWave; off <<= 1) extra += __shfl_xor(extra, off);
+            if (lane == 0) s_cnt3[which][wave][kLevels] += extra;
         }
+    };
+    // whole batch (0) and the sequences before my range (1): every wavefront its share, strided
+    for (int i0 = wave * kWave; i0 < B; i0 += kBuildThreads) {
+        const int i = i0 + lane;
+        int tiles = 0;
+        if (i < B) {
+            const int len = window_of(resp_off, i, n_resp, lo, nullptr);
+            tiles = window_tiles(lo, len);
+        }
+        count_levels(0, tiles);
+        if (i0 < p_begin) count_levels(1, i < p_begin ? tiles : 0);
+    }
+    // my range (2): thread t owns sequences i_begin .. i_end - 1; the wavefront handles one of each at a time
+    for (int k = 0; k < per; ++k) {
+        const int i = i_begin + k;
+        int tiles = 0;
+        if (i < i_end) {
+            const int len = window_of(resp_off, i, n_resp, lo, status);
+            tiles = window_tiles(lo, len);
+        }
+        count_levels(2, tiles);
     }
     __syncthreads();
-    if (tid < 2 * (kLevels + 1)) {
+    if (tid < 2 * (kLevels + 1)) {                                  // totals over the wavefronts
         const int which = tid / (kLevels + 1), l = tid % (kLevels + 1);
         int sum = 0;
-        for (int w = 0; w < kWaves; ++w) sum += s_red[which][w][l];
+        for (int w = 0; w < kWaves; ++w) sum += s_cnt3[which][w][l];
         s_sum[which][l] = sum;
+    } else if (tid >= 128 && tid <= 128 + kLevels) {                // another wavefront: my range's counts into offsets
+        const int l = tid - 128;
+        int run = 0;
+        for (int w = 0; w < kWaves; ++w) {
+            const int x = s_cnt3[2][w][l];
+            s_cnt3[2][w][l] = run;
+            run += x;
+        }
     }
     __syncthreads();
-    if (tid == 0) {
+    if (tid <= kLevels) {                                           // where each level starts for this range
         int base = 0;
-        for (int l = 0; l <= kLevels; ++l) {
-            s_first[l] = base + s_sum[1][l];
-            base += s_sum[0][l];
+        for (int l = 0; l < tid; ++l) base += s_sum[0][l];
+        s_first[tid] = base + s_sum[1][tid];
+        if (tid == kLevels) s_total = base + s_sum[0][kLevels];
+    }
+    __syncthreads();
+    // Emission, in the same order as the count of my range.  s_cnt3[2][wave][l] is the wavefront's running
+    // offset inside level l (wave-private from here on).
+    for (int k = 0; k < per; ++k) {
+        const int i = i_begin + k;
+        int tiles = 0, len = 0, keep = 0;
+        bool fin = false;
+        if (i < i_end) {
+            len = window_of(resp_off, i, n_resp, lo, nullptr);
+            tiles = window_tiles(lo, len);
+            if (keep_len && tiles > 0) {
+                keep = keep_len[i];
+                fin = done[i] != 0;
+            }
         }
-        s_total = base;
-    }
-    // my block's tiles per level, and an exclusive prefix sum of them over the workgroup
-    LevelCounts mine = {}, before;
-    for (int i = i_begin; i < i_end; ++i) {
-        const int len = window_of(resp_off, i, n_resp, lo, status);
-        count_sequence(mine, window_tiles(lo, len));
-    }
-#pragma unroll
-    for (int l = 0; l <= kLevels; ++l) {
-        int inc = mine.n[l];
-        if (l < kLevels ? l < levels : deep) {
+        const int deepest = wave_max(tiles);
+        for (int l = 0; l < min(deepest, kLevels); ++l) {
+            const unsigned long long has = __ballot(tiles > l);
+            const int at = s_first[l] + s_cnt3[2][wave][l] + __popcll(has & below);
+            if (tiles > l && at < cap) {                            // (invalid offsets cannot overflow the list)
+                const Tile d = make_tile(i, lo, len, tiles, l);
+                pl.tiles[at] = d;
+                pl.sets[at] = keep_len ? pack_sets(min(max(keep - (d.start - lo), 0), d.len()), fin) : 0;
+            }
+            if (lane == 0) s_cnt3[2][wave][l] += __popcll(has);
+        }
+        if (deepest > kLevels) {                                    // a sequence's deeper tiles stay together
+            const int extra = max(tiles - kLevels, 0);
+            int inc = extra;
 #pragma unroll
             for (int off = 1; off < kWave; off <<= 1) {
                 const int y = __shfl_up(inc, off);
                 if (lane >= off) inc += y;
             }
-        }
-        before.n[l] = inc - mine.n[l];
-        if (lane == kWave - 1) s_red[0][wave][l] = inc;     // (the sums above were consumed before the last barrier)
-    }
-    __syncthreads();
-    if (tid <= kLevels) {
-        int run = 0;
-        for (int w = 0; w < kWaves; ++w) {
-            const int x = s_red[0][w][tid];
-            s_red[0][w][tid] = run;
-            run += x;
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int l = 0; l < kLevels; ++l) {
-        if (mine.n[l] == 0) continue;
-        int at = s_first[l] + s_red[0][wave][l] + before.n[l];
-        for (int i = i_begin; i < i_end; ++i) {
-            const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = window_tiles(lo, len);
-            if (tiles <= l) continue;
-            if (at < cap) {                                                   // (invalid offsets cannot overflow the list)
-                const Tile d = make_tile(i, lo, len, tiles, l);
-                pl.tiles[at] = d;
-                pl.sets[at] = sets_word(d, lo, keep_len, done);
-            }
-            ++at;
-        }
-    }
-    if (mine.n[kLevels] != 0) {
-        int at = s_first[kLevels] + s_red[0][wave][kLevels] + before.n[kLevels];
-        for (int i = i_begin; i < i_end; ++i) {
-            const int len = window_of(resp_off, i, n_resp, lo, nullptr), tiles = window_tiles(lo, len);
+            int at = s_first[kLevels] + s_cnt3[2][wave][kLevels] + inc - extra;
             for (int l = kLevels; l < tiles; ++l, ++at) {
                 if (at < cap) {
                     const Tile d = make_tile(i, lo, len, tiles, l);
                     pl.tiles[at] = d;
-                    pl.sets[at] = sets_word(d, lo, keep_len, done);
+                    pl.sets[at] = keep_len ? pack_sets(min(max(keep - (d.start - lo), 0), d.len()), fin) : 0;
                 }
             }
+            const int total = __shfl(inc, kWave - 1);
+            if (lane == 0) s_cnt3[2][wave][kLevels] += total;
         }
     }
     if (part == parts - 1 && tid == 0) {

@@ -1190,6 +1190,82 @@ def test_plan_build_and_a_plan_of_another_batch(tp):
     assert int(host(st)[0]) == tp.STATUS_BAD_LAYOUT and bool((out[0] == 7.0).all())
 
 
+def expected_tiles(off, keep, done):
+    """The plan's tiles as the header documents them, worked out on the host: a sequence is cut at multiples of
+    1024 of the response-packed index; per tile (first token, tokens, sequence, tile number in the sequence,
+    tiles after it, policy tokens, finished)."""
+    out = {}
+    for i in range(len(done)):
+        lo, hi = int(off[i]), int(off[i + 1])
+        if hi == lo:
+            continue
+        cuts = [lo] + list(range((lo // 1024 + 1) * 1024, hi, 1024)) + [hi]
+        for c in range(len(cuts) - 1):
+            first, n = cuts[c], cuts[c + 1] - cuts[c]
+            pol = min(max(int(keep[i]) - (first - lo), 0), n) if keep is not None else 0
+            out[(i, c)] = (first, n, len(cuts) - 2 - c, pol, bool(done[i]) if keep is not None else False)
+    return out
+
+
+@pytest.mark.parametrize("case", ["small", "longcot", "many", "deep", "select"])
+def test_plan_lists_every_tile_once_in_level_order(tp, case):
+    """The work plan read back from the device: every tile of every sequence exactly once, with the fields the
+    consumers rely on, sorted by the number of tiles after it in its sequence (beyond 32, sequence by sequence);
+    all tagged words zero after the build."""
+    import torch
+    rng = np.random.default_rng(77)
+    if case in ("small", "longcot", "select"):
+        b = synth.make_batch("longcot" if case == "longcot" else "small", with_head=False)
+        win, done = np.diff(b["resp_off"]), b["done"]
+    elif case == "many":                                     # several builder workgroups, several sequences per thread
+        win = rng.integers(0, 3000, size=20011)
+        win[rng.random(win.size) < 0.1] = 0
+        done = (rng.random(win.size) < 0.5).astype(np.int32)
+    else:                                                    # sequences beyond the 32 sorted levels, one of them very long
+        win = np.concatenate([[70001, 5, 0, 40000], rng.integers(1, 9000, size=70), [33 * 1024 + 1]])
+        done = (rng.random(win.size) < 0.5).astype(np.int32)
+    off = np.concatenate([[0], np.cumsum(win)]).astype(np.int32)
+    keep = np.where(done != 0, win, np.maximum(win - 128, 0)).astype(np.int32)
+    n, B = int(off[-1]), len(done)
+    if case == "select":                                     # the plan tppo_select writes: capacity sized for n_tok
+        sel, st = run_select(tp, b)
+        sel = tp.tppo_select(dev(b["cu_seqlens"]), dev(b["ctx_len"]), dev(b["done"]), None, b["tail_drop"],
+                             n_tok=b["n_tok"], want_plan=True)
+        plan, keep = sel["plan"], host(sel["keep_len"])
+    else:
+        plan = tp.tppo_plan_build(dev(off), dev(keep), dev(done.astype(np.int32)), n)
+    torch.cuda.synchronize()
+    raw = plan.cpu().numpy()
+    hdr = raw[:256].view(np.int32)
+    n_tiles, cap = int(hdr[0]), int(hdr[8])
+    assert (int(hdr[1]), int(hdr[2])) == (B, n) and cap >= n // 1024 + B + 1
+    want = expected_tiles(off, keep, done)
+    assert n_tiles == len(want)
+    tiles = raw[256:256 + 16 * cap].view(np.int32).reshape(cap, 4)[:n_tiles]
+    at = 256 + (16 * cap + 255) // 256 * 256
+    sets = raw[at:at + 4 * cap].view(np.int32)[:n_tiles]
+    at += (4 * cap + 255) // 256 * 256
+    assert not raw[at:].any(), "tagged words must be zero after the build"
+    seen = set()
+    afters = []
+    for (start, pos_len, seg, after), word in zip(tiles.tolist(), sets.tolist()):
+        key = (seg, pos_len >> 11)
+        assert key in want and key not in seen, key
+        seen.add(key)
+        first, ntok, aft, pol, fin = want[key]
+        assert (start, (pos_len & 2047) + 1, after) == (first, ntok, aft), key
+        assert (word & 0xFFFF, bool(word >> 16)) == (pol, fin), key
+        afters.append(after)
+    afters = np.array(afters)
+    sorted_part = afters[afters < 32]
+    assert np.all(np.diff(sorted_part) >= 0) and np.all(afters[:sorted_part.size] < 32)
+    deep_seg, deep_after = tiles[sorted_part.size:, 2], afters[sorted_part.size:]
+    for s_ in np.unique(deep_seg):                           # a sequence's deeper tiles: together, innermost first
+        idx = np.nonzero(deep_seg == s_)[0]
+        assert np.array_equal(idx, np.arange(idx[0], idx[0] + idx.size))
+        assert np.array_equal(deep_after[idx], np.arange(32, 32 + idx.size))
+
+
 # ------------------------------------------------------------------ randomised batches
 SPECIAL_WINDOWS = np.array([0, 1, 2, 2047, 2048, 2049, 4096, 4097])
 
