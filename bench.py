@@ -126,7 +126,6 @@ def main():
     lib = tp.load()
     H, V = b["H"], b["V"]
     ws_head = tp._workspace(lib.tppo_token_logprobs_workspace_bytes(M, H, V, tp.TPPO_BF16), "cuda") if has_head else None
-    ws_egae = tp._workspace(lib.tppo_egae_workspace_bytes(n_resp, b["B"]), "cuda")
     adv_ret = (torch.empty(n_resp, device="cuda"), torch.empty(n_resp, device="cuda"))
     loss_out = torch.empty(32, dtype=torch.uint8, device="cuda")
 
@@ -226,10 +225,10 @@ def main():
     extra = None
     if not args.metric_only:
         # --- beyond the metric's four steps: the loss derivatives (one more streaming pass), timed on their own
-        ws_bwd = tp._workspace(lib.tppo_ppo_losses_backward_workspace_bytes(n_resp, b["B"]), "cuda")
         grads = (torch.empty(n_resp, device="cuda"), torch.empty(n_resp, device="cuda"))
         stats_out = torch.empty(32, dtype=torch.uint8, device="cuda")
-        s_last = tp.tppo_select(d["cu_seqlens"], d["ctx_len"], d["done"], ids, b["tail_drop"], n_tok=n_tok)
+        s_last = tp.tppo_select(d["cu_seqlens"], d["ctx_len"], d["done"], ids, b["tail_drop"], n_tok=n_tok,
+                                want_plan=True)
         logp_last = logp0
         adv_last, ret_last = adv_ret
 
@@ -237,7 +236,7 @@ def main():
             tp.tppo_ppo_losses_backward(logp_last, logp_old, adv_last, d["v_new"], d["values"], ret_last,
                                         s_last["resp_off"], s_last["keep_len"], d["done"], b["eps_low"],
                                         b["eps_high"], b["xi_low"], b["xi_high"], status=status,
-                                        workspace=ws_bwd, out=loss_out, stats=stats_out, grads=grads)
+                                        plan=s_last["plan"], out=loss_out, stats=stats_out, grads=grads)
 
         backward_pass()
         torch.cuda.synchronize()
@@ -256,7 +255,7 @@ def main():
         # Extended GAE from one terminal reward per sequence (12 instead of 16 bytes per token)
         terminal = torch.ones(b["B"], dtype=torch.float32, device="cuda")
         run_t = lambda: tp.tppo_egae_terminal(terminal, d["values"], s_last["resp_off"], d["done"], b["gamma"],
-                                              b["lam"], status=status, workspace=ws_egae, out=adv_ret)
+                                              b["lam"], status=status, plan=s_last["plan"], out=adv_ret)
         run_t()
         torch.cuda.synchronize()
         e0.record()
