@@ -163,7 +163,8 @@ int tppo_plan_build(const int32_t* resp_off, const int32_t* keep_len, const int3
  *      both of type `dt` (TPPO_BF16: bf16 inputs, fp32 accumulation on the
  *      matrix cores when H % 64 == 0 and both leading dimensions are multiples
  *      of 8 and the base pointers 16-byte aligned, otherwise a slower generic
- *      kernel; TPPO_F32: fp32 FMA kernel);
+ *      kernel; TPPO_F32: fp32 FMA kernel; the generic and the fp32 kernel keep
+ *      one hidden row in LDS and take H <= 16320, beyond that TPPO_ERR_SIZE);
  *      sel_rows[M], sel_targets[M] int32;
  *      m_actual: optional device int64 (e.g. counts+0 of tppo_select): only the
  *      first min(M, *m_actual) tokens are computed, so M can be a host-side

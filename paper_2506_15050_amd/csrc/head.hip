@@ -26,7 +26,7 @@ namespace tppo {
 // One workgroup per kept token, one wavefront per vocabulary row at a time.
 // fp32 FMA; serves TPPO_F32 and bf16 shapes the MFMA path does not take.
 constexpr int kGenThreads = 256;
-constexpr int kGenMaxH = 16384;
+constexpr int kGenMaxH = 16320;               // the hidden row (fp32) and 48 bytes of partial results share 64 KiB of LDS
 
 __device__ __forceinline__ float load_as_float(const float* p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float load_as_float(const uint16_t* p, int64_t i) {
