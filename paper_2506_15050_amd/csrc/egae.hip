@@ -166,26 +166,7 @@ struct EgaeParams {
     uint32_t tag;
     double gamma;
     ScanConsts sa, sr;             // multipliers gamma*lambda (advantages) and gamma (returns)
-#ifdef TPPO_TUNING
-    long long* prof;               // per-tile phase timestamps (tuning builds only)
-#endif
 };
-
-#ifdef TPPO_TUNING
-// timestamps stay in scalar registers until the tile is done: a store in mid-tile would sit in the same in-order
-// memory counter as the loads being timed
-#define TPPO_STAMP(k) do { g_stamp_local[k] = __builtin_amdgcn_s_memtime(); } while (0)
-#define TPPO_STAMPS_DECL unsigned long long g_stamp_local[8] = {0, 0, 0, 0, 0, 0, 0, 0}
-#define TPPO_STAMPS_ARG , unsigned long long (&g_stamp_local)[8]
-#define TPPO_STAMPS_PASS , g_stamp_local
-#define TPPO_STAMPS_FLUSH do { if (p.prof && lane == 0) { for (int k_ = 0; k_ < 8; ++k_) p.prof[(int64_t)pos * 8 + k_] = (long long)g_stamp_local[k_]; } } while (0)
-#else
-#define TPPO_STAMP(k) do { } while (0)
-#define TPPO_STAMPS_DECL do { } while (0)
-#define TPPO_STAMPS_ARG
-#define TPPO_STAMPS_PASS
-#define TPPO_STAMPS_FLUSH do { } while (0)
-#endif
 
 // bits of x where keep, else zero: a select the compiler cannot turn into a branch, and one that never lets a
 // NaN of a neighbouring sequence through (no multiplication by a mask)
@@ -278,12 +259,26 @@ __device__ __forceinline__ void issue_tile(TileIn& x, const Tile& t, const EgaeP
     for (int q = 0; q < 4; ++q) x.early[q] = __hip_atomic_load(look + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
+// Everything issue_tile asked for has arrived and is in its final form: the look-back's words are unpacked and
+// every loaded register is pinned here, BEFORE any tile of the wavefront stores anything.  The memory counter
+// of a wavefront retires in order, stores included: a wait for a load placed after a store -- the publication
+// below, a tile's results -- also waits for that store, a full trip to memory.
+__device__ __forceinline__ void settle_tile(TileIn& x, const EgaeParams& p) {
+    x.look_ok = unpack_words(x.early, p.tag, x.look_a, x.look_r);
+    asm volatile("" : "+v"(x.look_a), "+v"(x.look_r) : : "memory");
+#pragma unroll
+    for (int j = 0; j < kSlots; ++j)
+        asm volatile("" : "+v"(x.v[j][0]), "+v"(x.v[j][1]), "+v"(x.v[j][2]), "+v"(x.v[j][3]), "+v"(x.r[j][0]),
+                          "+v"(x.r[j][1]), "+v"(x.r[j][2]), "+v"(x.r[j][3]));
+    asm volatile("" : "+v"(x.side_next), "+v"(x.side_last), "+v"(x.side_boot), "+v"(x.side_term), "+v"(x.side_done));
+}
+
 // Pass 1 of a tile, and the publication of its aggregate.  kFull: all 1024 tokens exist (every tile but a
 // sequence's last): no masks -- straight-line code.
 template <bool kTerminal, bool kFull>
 __device__ __forceinline__ void tile_front(TileIn& x, TileMid& m, lds_float4* s_loc, const EgaeParams& p,
                                            const Plan& pl, int lane, const LaneWeights& wa,
-                                           const LaneWeights& wr TPPO_STAMPS_ARG) {
+                                           const LaneWeights& wr) {
     const double gamma = p.gamma, c = p.sa.m;
     const int n_resp = p.n_resp, pos = x.pos;
     const int base = x.t.base(), begin = kFull ? 0 : x.t.begin(), end = kFull ? kTileTokens : begin + x.t.len();
@@ -335,7 +330,6 @@ __device__ __forceinline__ void tile_front(TileIn& x, TileMid& m, lds_float4* s_
             for (int e = 0; e < 4; ++e) x.r[j][e] = keep_if(terminal, k0 + e == end - 1);
         }
     }
-    TPPO_STAMP(2);
     // V of the token after each of my runs: my left neighbour's first value; for lane 0 the next slot's first
     // value (held by lane 63) or, after the last slot, the value after the tile
     float v_next_run[kSlots];
@@ -377,13 +371,9 @@ __device__ __forceinline__ void tile_front(TileIn& x, TileMid& m, lds_float4* s_
         m.tot_a[j] = read_lane63(ba);
         m.tot_r[j] = read_lane63(br);
     }
-    TPPO_STAMP(3);
     // Take the look-back's words out of flight BEFORE anything is stored: the memory counter of a wavefront
     // retires in order, so a wait for these loads placed after the publication below would also wait for its
     // write-through stores, a full trip to memory.
-    x.look_ok = unpack_words(x.early, p.tag, x.look_a, x.look_r);
-    asm volatile("" : "+v"(x.look_a), "+v"(x.look_r) : : "memory");
-    TPPO_STAMP(6);
     if (x.t.number() > 0) {                                         // somebody to my left will ask for the tile's value
         double ta = 0.0, tr = 0.0;
 #pragma unroll
@@ -403,10 +393,8 @@ __device__ __forceinline__ void tile_front(TileIn& x, TileMid& m, lds_float4* s_
 template <bool kFull>
 __device__ __forceinline__ void tile_back(const TileIn& x, const TileMid& m, const lds_float4* s_loc,
                                           const EgaeParams& p, const Plan& pl, int lane, const LaneWeights& wa,
-                                          const LaneWeights& wr TPPO_STAMPS_ARG) {
+                                          const LaneWeights& wr) {
     const Tile& t = x.t;
-    const int pos = x.pos;
-    (void)pos;
     const double gamma = p.gamma, c = p.sa.m;
     const int base = t.base(), begin = kFull ? 0 : t.begin(), end = kFull ? kTileTokens : begin + t.len(), after = t.after;
     double carry_a = 0.0, carry_r = 0.0;
@@ -419,12 +407,6 @@ __device__ __forceinline__ void tile_back(const TileIn& x, const TileMid& m, con
             carry_a = powi(p.sa.qtile, lane) * ba;
             carry_r = powi(p.sr.qtile, lane) * br;
         }
-#ifdef TPPO_TUNING
-        {
-            const unsigned long long late = __ballot(lane < after && !x.look_ok);
-            g_stamp_local[0] = __popcll(late);
-        }
-#endif
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
             carry_a += __shfl_xor(carry_a, off);
@@ -443,7 +425,6 @@ __device__ __forceinline__ void tile_back(const TileIn& x, const TileMid& m, con
             }
         }
     }
-    TPPO_STAMP(4);
     // a token's value is what pass 1 kept for it plus m^(tokens to the run's end) times the value carried into
     // the run
     const double pw_a[4] = {p.sa.q[0], c * c * c, c * c, c}, pw_r[4] = {p.sr.q[0], gamma * gamma * gamma, gamma * gamma, gamma};
@@ -478,54 +459,77 @@ __device__ __forceinline__ void tile_back(const TileIn& x, const TileMid& m, con
         carry_a = fma(p.sa.q64, carry_a, m.tot_a[j]);
         carry_r = fma(p.sr.q64, carry_r, m.tot_r[j]);
     }
-    TPPO_STAMP(5);
-    TPPO_STAMPS_FLUSH;
 }
 
-// Schedule: one wavefront per tile, one tile per workgroup, workgroup w the tile at list position w.  The
-// hardware's dispatcher is the load balancer, and it starts workgroups in index order: the tiles a tile may have
-// to wait for stand earlier in the list, so they run or have run, and they never wait before they publish.
-// (Wavefronts that stay and walk the list with a stride were measured too -- they save the start-up of a
-// wavefront per tile, but every tile then waits for the stores of the one before it, and tiles that depend on
-// each other run side by side more often; 5 % slower on the long-CoT batches.)
+// Schedule: one wavefront per workgroup, kTilesPerWave consecutive list positions per wavefront; the hardware's
+// dispatcher is the load balancer, and it starts workgroups in index order: the tiles a tile may have to wait
+// for stand earlier in the list, so they run or have run (or are this wavefront's own earlier tile), and they
+// never wait before they publish.  All loads of all the wavefront's tiles go out first, then the tiles are
+// worked through one after the other: the start of a wavefront, the trip to memory and the drain of the
+// stores are paid once per kTilesPerWave tiles, and no load ever waits behind a store.
+// Measured on the 40 M-token long-CoT batch: 1 tile per wavefront 135 us (4 wavefronts per SIMD), 2 tiles 149 us
+// (3 per SIMD), 3 tiles 173 us (2 per SIMD) -- what a second tile saves in start-up and drain it loses in
+// wavefronts per SIMD, and a tile that is worked on later publishes later.  Wavefronts that stay and walk the
+// list in a loop: every tile then waits for the stores of the one before it; 150 us.
+#ifndef TPPO_EGAE_TILES
+#define TPPO_EGAE_TILES 1
+#endif
+constexpr int kTilesPerWave = TPPO_EGAE_TILES;
+
+template <bool kTerminal>
+__device__ __forceinline__ void run_tile(TileIn& x, lds_float4* s_loc, const EgaeParams& p, const Plan& pl, int lane,
+                                         const LaneWeights& wa, const LaneWeights& wr) {
+    TileMid mid;
+    if (x.t.len() == kTileTokens) {
+        tile_front<kTerminal, true>(x, mid, s_loc, p, pl, lane, wa, wr);
+        tile_back<true>(x, mid, s_loc, p, pl, lane, wa, wr);
+    } else {
+        tile_front<kTerminal, false>(x, mid, s_loc, p, pl, lane, wa, wr);
+        tile_back<false>(x, mid, s_loc, p, pl, lane, wa, wr);
+    }
+}
+
 template <bool kTerminal>
 __global__ __launch_bounds__(kWave, kEgaeMinWaves) void egae_scan_kernel(EgaeParams p) {
     __shared__ lds_float4 s_loc[2 * kSlots * kWave];
-    TPPO_STAMPS_DECL;
-    TPPO_STAMP(7);
     const int lane = threadIdx.x;
-    const int pos = blockIdx.x;
-    // The descriptor is asked for before anything is known about the plan -- its place depends on the plan's
-    // address alone, and the caller guarantees a buffer that holds gridDim.x descriptors -- so that it travels
-    // together with the header instead of after it.  As a vector load: the wavefront waits for it, and a scalar
-    // load that misses is several times slower.
+    const int pos0 = blockIdx.x * kTilesPerWave;
+    // The descriptors are asked for before anything is known about the plan -- their place depends on the
+    // plan's address alone, and the caller guarantees a buffer that holds them -- so that they travel together
+    // with the header instead of after it.  As vector loads: the wavefront waits for them, and a scalar load
+    // that misses is several times slower.
     const int zero = opaque_zero();
-    const tile_bits raw = fetch_tile(reinterpret_cast<const Tile*>(static_cast<const char*>(p.plan) + 256) + pos, zero);
+    const Tile* list = reinterpret_cast<const Tile*>(static_cast<const char*>(p.plan) + 256);
+    tile_bits raw[kTilesPerWave];
+#pragma unroll
+    for (int h = 0; h < kTilesPerWave; ++h) raw[h] = fetch_tile(list + pos0 + h, zero);
     const Plan pl = plan_open(p.plan);
     const int n_tiles = load_uniform(&pl.hdr->n_tiles);
     if (load_uniform(&pl.hdr->B) != p.B || load_uniform(&pl.hdr->n_resp) != p.n_resp || n_tiles > pl.cap ||
-        pl.cap < (int)gridDim.x) {                                  // a plan built for another batch
-        if (pos == 0 && lane == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
+        pl.cap < p.n_resp / kTileTokens + p.B + 1) {                // a plan built for another batch
+        if (pos0 == 0 && lane == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
         return;
     }
-    if (pos >= n_tiles) return;                                     // the list is shorter than its capacity
-    const Tile t = uniform_tile(raw);
-    if (!tile_valid(t, p.n_resp, p.B, pl.cap)) {
-        if (lane == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
-        return;
+    if (pos0 >= n_tiles) return;                                    // the list is shorter than its capacity
+    TileIn x[kTilesPerWave];
+    bool live[kTilesPerWave];
+#pragma unroll
+    for (int h = 0; h < kTilesPerWave; ++h) {
+        const Tile t = uniform_tile(raw[h]);
+        live[h] = pos0 + h < n_tiles;
+        if (live[h] && !tile_valid(t, p.n_resp, p.B, pl.cap)) {
+            if (lane == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
+            live[h] = false;
+        }
+        if (live[h]) issue_tile<kTerminal>(x[h], t, p, pl, pos0 + h, lane, zero);
     }
-    TileIn cur;
-    issue_tile<kTerminal>(cur, t, p, pl, pos, lane, zero);
-    TPPO_STAMP(1);
     const LaneWeights wa = lane_weights(p.sa, lane), wr = lane_weights(p.sr, lane);    // while the loads fly
-    TileMid mid;
-    if (t.len() == kTileTokens) {
-        tile_front<kTerminal, true>(cur, mid, s_loc, p, pl, lane, wa, wr TPPO_STAMPS_PASS);
-        tile_back<true>(cur, mid, s_loc, p, pl, lane, wa, wr TPPO_STAMPS_PASS);
-    } else {
-        tile_front<kTerminal, false>(cur, mid, s_loc, p, pl, lane, wa, wr TPPO_STAMPS_PASS);
-        tile_back<false>(cur, mid, s_loc, p, pl, lane, wa, wr TPPO_STAMPS_PASS);
-    }
+#pragma unroll
+    for (int h = 0; h < kTilesPerWave; ++h)
+        if (live[h]) settle_tile(x[h], p);
+#pragma unroll
+    for (int h = 0; h < kTilesPerWave; ++h)
+        if (live[h]) run_tile<kTerminal>(x[h], s_loc, p, pl, lane, wa, wr);
 }
 
 // Batches of fewer than four tokens (the streaming kernel's 16-byte accesses need four): one thread per
@@ -608,12 +612,8 @@ static int egae_launch(const float* rewards, bool terminal_mode, const float* va
     p.gamma = (double)gamma;
     p.sa = make_consts((double)gamma * (double)lambda);
     p.sr = make_consts((double)gamma);
-#ifdef TPPO_TUNING
-    p.prof = nullptr;
-    if (const char* e = getenv("TPPO_EGAE_PROF")) p.prof = reinterpret_cast<long long*>(strtoull(e, nullptr, 0));
-#endif
-    // one wavefront per tile; the list may be shorter than its capacity: the surplus exits at once
-    const unsigned groups = (unsigned)cap64;
+    // one wavefront per kTilesPerWave tiles; the list may be shorter than its capacity: the surplus exits at once
+    const unsigned groups = (unsigned)((cap64 + kTilesPerWave - 1) / kTilesPerWave);
     if (terminal_mode) hipLaunchKernelGGL(egae_scan_kernel<true>, dim3(groups), dim3(kWave), 0, s, p);
     else hipLaunchKernelGGL(egae_scan_kernel<false>, dim3(groups), dim3(kWave), 0, s, p);
     return launch_result();
