@@ -266,12 +266,23 @@ __global__ __launch_bounds__(256) void head_combine_kernel(
 using Cfg0 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 32, 16, 8>;   // v_mfma_f32_16x16x32_bf16, one W block per MFMA step
 using Cfg1 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 16, 32>;      // v_mfma_f32_32x32x16_bf16
 using Cfg2 = HeadCfg<256, 256, 2, 4, 64, 2, 1, 0, 32>;       // the same, transfers issued back to back
+#ifdef TPPO_TUNING
+// Two workgroups of 4 wavefronts per CU, 256 x 128 tiles, half-size stages: the two drift apart, so one's
+// log-softmax fold and stage hand-overs fall into the other's MFMAs.  Measured: correct, and a third slower
+// than variant 0 on every shape (0.34 / 0.38 / 0.38 of peak against 0.43 / 0.53 / 0.54 at H = 1024 / 3584 /
+// 5120): half cache lines per transfer and 1.5x the L2 -> LDS bytes per flop cost more than the overlap gains.
+using Cfg3 = HeadCfg<256, 128, 2, 2, 32, 2, 2, 24, 16, 8>;
+#endif
 
 template <class C>
 constexpr HeadVariant make_variant() {
     return {head_mfma_kernel<C, LaneSoftmax>, C::kTileV, C::kTileT, C::kThreads, C::kLdsBytes, C::kWgsPerCu};
 }
-static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>(), make_variant<Cfg2>()};
+#ifdef TPPO_TUNING
+static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>(), make_variant<Cfg2>(), make_variant<Cfg3>()};
+#else
+static const HeadVariant kVariants[] = {make_variant<Cfg0>()};
+#endif
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 static const HeadVariant& pick_variant() {

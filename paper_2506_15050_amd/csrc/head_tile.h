@@ -7,6 +7,7 @@
 #include <stdlib.h>
 
 #include <atomic>
+#include <type_traits>
 
 #include "common.h"
 
@@ -253,7 +254,13 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
     //             4*(step/kSubdiv) + group; the token fragments once per K step of 32 (with part 0).
     constexpr int kSubVB = C::kSubVB;
     bf16x8 fa[2][kSubVB], fb[2][kTB];
-    auto load_frags = [&](int stage, int step) {
+    // `par`: parity of the K iteration the fragments belong to.  With 32-deep stages a stage holds ONE K step of
+    // 32, so the token fragments of consecutive iterations must alternate between the two buffers (the next
+    // stage's first fragments are fetched before this stage's last MFMAs); with 64-deep stages the two K steps
+    // of a stage alternate by themselves.
+    auto fb_slot = [](int k32, int par) { return C::kBK == 32 ? ((k32 + par) & 1) : (k32 & 1); };
+    auto load_frags = [&](int stage, int step, auto par_c) {
+        constexpr int par = decltype(par_c)::value;
         const unsigned char* st = smem + stage * C::kStageBytes;
         const unsigned char* a_base = st + (wv * kWaveV) * C::kRowBytes;
         const unsigned char* b_base = st + (kTileV + wt * kWaveT) * C::kRowBytes;
@@ -273,23 +280,24 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
             if (part == 0) {
 #pragma unroll
                 for (int tb = 0; tb < kTB; ++tb)
-                    fb[k32 & 1][tb] = *reinterpret_cast<const bf16x8*>(b_base + C::chunk_off(tb * 16 + frag_row, c));
+                    fb[fb_slot(k32, par)][tb] = *reinterpret_cast<const bf16x8*>(b_base + C::chunk_off(tb * 16 + frag_row, c));
             }
         }
     };
-    auto mfma_one = [&](int step, int j, int tb) {
+    auto mfma_one = [&](int step, int j, int tb, auto par_c) {
+        constexpr int par = decltype(par_c)::value;
         if constexpr (C::kMI == 32) {
             acc[j][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[step & 1][j], fb[step & 1][tb], acc[j][tb], 0, 0, 0);
         } else {
             const int vb = (step % C::kSubdiv) * kSubVB + j;
-            acc[vb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[step & 1][j], fb[(step / C::kSubdiv) & 1][tb], acc[vb][tb], 0, 0, 0);
+            acc[vb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[step & 1][j], fb[fb_slot(step / C::kSubdiv, par)][tb], acc[vb][tb], 0, 0, 0);
         }
     };
-    auto mfma_step = [&](int step) {
+    auto mfma_step = [&](int step, auto par_c) {
 #pragma unroll
         for (int j = 0; j < kSubVB; ++j)
 #pragma unroll
-            for (int tb = 0; tb < kTB; ++tb) mfma_one(step, j, tb);
+            for (int tb = 0; tb < kTB; ++tb) mfma_one(step, j, tb, par_c);
     };
     // The same K step with this wave's transfers first .. first + n - 1 of the
     // stage being refilled issued between the MFMAs (`on` is workgroup-uniform).
@@ -297,13 +305,13 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
     // floor(j * kSpread / kDmaPerWave), counted from the barrier that freed it.
     constexpr int kMfmaPerStep = C::kMfmaPerStep;
     constexpr int kSpreadSteps = (C::kSpread + kMfmaPerStep - 1) / kMfmaPerStep;   // MFMA steps the issue touches
-    auto mfma_step_issuing = [&](int step, int part, bool on) {
+    auto mfma_step_issuing = [&](int step, int part, bool on, auto par_c) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int vb = 0; vb < kSubVB; ++vb)
 #pragma unroll
             for (int tb = 0; tb < kTB; ++tb) {
-                mfma_one(step, vb, tb);
+                mfma_one(step, vb, tb, par_c);
                 const int g = part * kMfmaPerStep + vb * kTB + tb;
                 if (on) {
 #pragma unroll
@@ -324,19 +332,24 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
     if (kStages - 1 < total_iters) issue();
-    load_frags(0, 0);
+    typedef std::integral_constant<int, 0> Even;
+    typedef std::integral_constant<int, 1> Odd;
+    load_frags(0, 0, Even());
 
     int kt = 0, vt = vt_begin, stage = 0;
     bool refill = false;                // spread issue: transfers of the stage freed at the last barrier are pending
-    for (int it = 0; it < total_iters; ++it) {
+    // one K iteration (one stage); par_c = the iteration's parity where it matters (32-deep stages), else Even
+    auto iteration = [&](int it, auto par_c) {
+        constexpr int par = decltype(par_c)::value;
+        typedef std::integral_constant<int, (C::kBK == 32 ? par ^ 1 : 0)> Next;
 #pragma unroll
         for (int ks = 0; ks + 1 < kKSteps; ++ks) {
-            load_frags(stage, ks + 1);
+            load_frags(stage, ks + 1, par_c);
             if (C::kSpread && ks + 1 < kSpreadSteps) {
-                mfma_step_issuing(ks, ks + 1, refill);
+                mfma_step_issuing(ks, ks + 1, refill, par_c);
                 if (ks + 2 == kSpreadSteps && refill) issue_advance();
             } else {
-                mfma_step(ks);
+                mfma_step(ks, par_c);
             }
         }
         // The stage's last fragments are in registers.  Hand the stage back,
@@ -354,14 +367,14 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
                 if (C::kSpread) refill = true;
                 else issue();
             }
-            load_frags(next_stage, 0);
+            load_frags(next_stage, 0, Next());
         }
         if (C::kSpread) {
-            mfma_step_issuing(kKSteps - 1, 0, refill);
+            mfma_step_issuing(kKSteps - 1, 0, refill, par_c);
             if (kSpreadSteps == 1 && refill) issue_advance();
         } else {
             __builtin_amdgcn_sched_barrier(0);
-            mfma_step(kKSteps - 1);
+            mfma_step(kKSteps - 1, par_c);
         }
         stage = next_stage;
         if (++kt == k_tiles) {          // a vocabulary tile is complete
@@ -369,6 +382,14 @@ __global__ __launch_bounds__(C::kThreads, C::kWgsPerCu* C::kWaves / 4) void head
             kt = 0;
             ++vt;
         }
+    };
+    if constexpr (C::kBK == 32) {
+        for (int it = 0; it < total_iters; it += 2) {
+            iteration(it, Even());
+            if (it + 1 < total_iters) iteration(it + 1, Odd());
+        }
+    } else {
+        for (int it = 0; it < total_iters; ++it) iteration(it, Even());
     }
     __syncthreads();                    // every fragment read is done before the stages are reused
     epi.finish(p, reinterpret_cast<float*>(smem), tok0, m_eff, sp, wv, wt, lane, tid);
@@ -385,28 +406,29 @@ struct HeadVariant {
     void (*kernel)(HeadParams);
     int tile_v, tile_t, threads, lds_bytes, wgs_per_cu;
 };
-// Number of vocabulary splits.  A unit is 8 token tiles x min(splits, 4) splits
+// Number of vocabulary splits.  A unit is 8 token tiles x min(splits, 4 per CU slot) splits
 // and every XCD works through ceil(units / 8) units of ceil(vocab_tiles /
 // splits) vocabulary tiles each; pick the count (1, 2, 3 or a multiple of 4)
-// that minimises that product, with a small per-unit overhead.
+// that minimises that product, with a small per-unit overhead (1 .. us - 1, or a multiple of us).
 static int choose_splits(const HeadVariant& hv, int64_t M, int64_t V) {
     const int64_t row_tiles = (M + hv.tile_t - 1) / hv.tile_t, vocab_tiles = (V + hv.tile_v - 1) / hv.tile_v;
     const int64_t unit_rows = (row_tiles + 7) / 8;
     const int max_s = (int)(vocab_tiles < kMaxSplits ? vocab_tiles : kMaxSplits);
+    const int us = 4 * hv.wgs_per_cu;                       // splits a unit holds: 32 workgroups per XCD and per CU slot
 #ifdef TPPO_TUNING
     if (const char* e = getenv("TPPO_HEAD_SPLITS")) {       // tuning builds only
         const int forced = atoi(e);
-        if (forced >= 1 && (forced < 4 || forced % 4 == 0)) return forced < max_s ? forced : max_s < 4 ? max_s : max_s / 4 * 4;
+        if (forced >= 1 && (forced < us || forced % us == 0)) return forced < max_s ? forced : max_s < us ? max_s : max_s / us * us;
     }
 #endif
     int best = 1;
     double best_cost = 1e300;
     for (int s = 1; s <= max_s; ++s) {
-        if (s > 4 && s % 4 != 0) continue;
-        const int64_t units = unit_rows * (s <= 4 ? 1 : s / 4);
+        if (s > us && s % us != 0) continue;
+        const int64_t units = unit_rows * (s <= us ? 1 : s / us);
         const double rounds = (double)((units + 7) / 8);
         const double per = (double)((vocab_tiles + s - 1) / s) + 0.25;
-        // fewer than 4 splits leave CUs idle: 8*s of the 32 workgroups of an XCD work
+        // fewer than `us` splits leave CUs idle: 8*s of the 8*us workgroups of an XCD work
         const double cost = rounds * per;
         if (cost < best_cost - 1e-9) {
             best_cost = cost;
@@ -417,7 +439,7 @@ static int choose_splits(const HeadVariant& hv, int64_t M, int64_t V) {
 }
 
 // arrival counters of the persistent schedule: one per unit, at the end of the workspace
-static size_t arrivals_bytes(int64_t M) { return round_up((size_t)((M / 256 / 8 + 2) * (kMaxSplits / 4)) * 4, 256); }
+static size_t arrivals_bytes(int64_t M) { return round_up((size_t)((M / 128 / 8 + 2) * (kMaxSplits / 4)) * 4, 256); }   // (token tiles of >= 128)
 
 
 // Fill in the schedule fields of `p` for M token-role rows and V W-role rows.
@@ -427,7 +449,8 @@ static void plan_sweep(HeadParams& p, const HeadVariant& hv, int64_t M, int64_t 
     p.row_tiles = (int)((M + hv.tile_t - 1) / hv.tile_t);
     p.vocab_tiles = (int)((V + hv.tile_v - 1) / hv.tile_v);
     p.splits = choose_splits(hv, M, V);
-    p.unit_splits = p.splits < 4 ? p.splits : 4;
+    const int us = 4 * hv.wgs_per_cu;
+    p.unit_splits = p.splits < us ? p.splits : us;
     p.unit_cols = p.splits / p.unit_splits;
     p.unit_rows = (p.row_tiles + 7) / 8;
     p.n_units = p.unit_rows * p.unit_cols;
@@ -470,7 +493,7 @@ static int launch_sweep(const HeadVariant& hv, const HeadParams& p, hipStream_t 
     if (!allow_lds(hv)) return TPPO_ERR_LAUNCH;
     hipLaunchKernelGGL(head_clear_kernel, dim3((p.n_units + 255) / 256), dim3(256), 0, s, p.unit_arrivals, p.n_units);
     if (launch_result() != TPPO_OK) return TPPO_ERR_LAUNCH;
-    hipLaunchKernelGGL(hv.kernel, dim3(kSweepGroups), dim3(hv.threads), hv.lds_bytes, s, p);
+    hipLaunchKernelGGL(hv.kernel, dim3(kSweepGroups * hv.wgs_per_cu), dim3(hv.threads), hv.lds_bytes, s, p);
     return launch_result();
 }
 
