@@ -363,8 +363,14 @@ int tppo_ppo_losses_backward(const float* logp_new, const float* logp_old, const
  *                         accumulate_w != 0.  Either may be NULL to skip it.
  * status is not written by this call (bad rows and targets were reported by
  * the forward pass; rows are clamped, a bad target matches no column).
- * workspace: at least tppo_token_logprobs_backward_workspace_bytes; a larger
- *      one lets more tokens (up to 32768) go through per chunk.
+ * workspace: tppo_token_logprobs_backward_workspace_bytes(M, ...) holds dZ in
+ *      both layouts for min(M, 98304) tokens at once (about 4 V bytes per
+ *      token plus W^T: 46 GB for the 77 000 kept tokens of the 32B-shaped
+ *      head) and is the fastest.  The call works with any workspace that
+ *      holds 256 tokens (the size the same function returns for M = 256): it
+ *      then goes through chunks of as many tokens, a multiple of 256, as the
+ *      workspace holds, more slowly (fewer tiles per sweep, grad_w re-read and
+ *      re-written per chunk); smaller than that -> TPPO_ERR_WORKSPACE.
  */
 size_t tppo_token_logprobs_backward_workspace_bytes(int64_t M, int64_t H, int64_t V, tppo_dtype dt);
 int tppo_token_logprobs_backward(const void* hidden, int64_t n_rows, int64_t H, int64_t ld_hidden,

@@ -184,10 +184,14 @@ static int launch_transpose(const uint16_t* src, int64_t rows, int64_t cols, int
 using BwdCfg = HeadCfg<256, 256, 2, 4, 64, 2, 1, 32, 16, 8>;
 static const HeadVariant kDzVariant = {head_mfma_kernel<BwdCfg, DzEpilogue>, BwdCfg::kTileV, BwdCfg::kTileT,
                                        BwdCfg::kThreads, BwdCfg::kLdsBytes, BwdCfg::kWgsPerCu};
+// The products' tiles are deep (K = the vocabulary, or a chunk of tokens) and their splits need no merge, so a
+// unit costs next to nothing besides its tiles: the schedule may cut the W-role rows into as many splits as
+// there are tiles, which rounds the work to whole tiles per workgroup instead of to five at a time.  Units in
+// row-major order, so that the XCDs share the long token-role rows (the operand that does not fit a cache).
 static const HeadVariant kGemmVariant = {head_mfma_kernel<BwdCfg, StoreEpilogue>, BwdCfg::kTileV, BwdCfg::kTileT,
-                                         BwdCfg::kThreads, BwdCfg::kLdsBytes, BwdCfg::kWgsPerCu};
+                                         BwdCfg::kThreads, BwdCfg::kLdsBytes, BwdCfg::kWgsPerCu, 0.02, 0};
 
-constexpr int64_t kBwdChunkDefault = 16384, kBwdChunkMax = 32768;
+constexpr int64_t kBwdChunkDefault = 98304, kBwdChunkMax = 98304;
 
 struct BwdLayout {
     int64_t v_pad, chunk;              // vocabulary padded to 64; tokens per chunk (multiple of 256)
@@ -276,7 +280,7 @@ extern "C" int tppo_token_logprobs_backward(const void* hidden, int64_t n_rows, 
             q.hidden = dz; q.n_rows = mc; q.ld_h = L.v_pad;
             q.w = wt; q.ld_w = L.v_pad; q.H = (int)L.v_pad;
             q.out = grad_hidden + m0 * H; q.ld_out = H; q.out_cols = H;
-            plan_sweep(q, kGemmVariant, mc, H, arrivals);
+            plan_sweep(q, kGemmVariant, mc, H, arrivals, "TPPO_GH_SPLITS", "TPPO_GH_ORDER");
             if (launch_sweep(kGemmVariant, q, s) != TPPO_OK) return TPPO_ERR_LAUNCH;
         }
         // 3. grad_w[v, :] (+)= dZ^T[v, :] . Hid   (token role: rows of dZ^T; W role: rows of Hid^T; K = m_pad)
@@ -289,7 +293,7 @@ extern "C" int tppo_token_logprobs_backward(const void* hidden, int64_t n_rows, 
             q.w = hidt; q.ld_w = m_pad; q.H = (int)m_pad;
             q.out = grad_w; q.ld_out = H; q.out_cols = H;
             q.accumulate = (m0 > 0 || accumulate_w) ? 1 : 0;
-            plan_sweep(q, kGemmVariant, V, H, arrivals);
+            plan_sweep(q, kGemmVariant, V, H, arrivals, "TPPO_GW_SPLITS", "TPPO_GW_ORDER");
             if (launch_sweep(kGemmVariant, q, s) != TPPO_OK) return TPPO_ERR_LAUNCH;
         }
     }

@@ -405,6 +405,10 @@ static __global__ __launch_bounds__(256) void head_clear_kernel(int32_t* p, int 
 struct HeadVariant {
     void (*kernel)(HeadParams);
     int tile_v, tile_t, threads, lds_bytes, wgs_per_cu;
+    // what a unit costs besides its tiles, in tile times (pipeline fill, the wait at the unit boundary, and for
+    // the log-softmax the merge of the splits): 0.25 measured for sweeps over H-deep tiles with a merge
+    double unit_cost = 0.25;
+    int col_major = 1;                  // 1: the 8 XCDs sweep the same W-role slice together; 0: the same token rows
 };
 // Number of vocabulary splits.  A unit is 8 token tiles x min(splits, 4 per CU slot) splits
 // and every XCD works through ceil(units / 8) units of ceil(vocab_tiles /
@@ -427,7 +431,7 @@ static int choose_splits(const HeadVariant& hv, int64_t M, int64_t V) {
         if (s > us && s % us != 0) continue;
         const int64_t units = unit_rows * (s <= us ? 1 : s / us);
         const double rounds = (double)((units + 7) / 8);
-        const double per = (double)((vocab_tiles + s - 1) / s) + 0.25;
+        const double per = (double)((vocab_tiles + s - 1) / s) + hv.unit_cost;
         // fewer than `us` splits leave CUs idle: 8*s of the 8*us workgroups of an XCD work
         const double cost = rounds * per;
         if (cost < best_cost - 1e-9) {
@@ -443,20 +447,28 @@ static size_t arrivals_bytes(int64_t M) { return round_up((size_t)((M / 128 / 8 
 
 
 // Fill in the schedule fields of `p` for M token-role rows and V W-role rows.
-static void plan_sweep(HeadParams& p, const HeadVariant& hv, int64_t M, int64_t V, void* arrivals) {
+static void plan_sweep(HeadParams& p, const HeadVariant& hv, int64_t M, int64_t V, void* arrivals,
+                       const char* tune_splits = nullptr, const char* tune_order = nullptr) {
     p.M = M;
     p.V = (int)V;
     p.row_tiles = (int)((M + hv.tile_t - 1) / hv.tile_t);
     p.vocab_tiles = (int)((V + hv.tile_v - 1) / hv.tile_v);
     p.splits = choose_splits(hv, M, V);
+#ifdef TPPO_TUNING
+    if (const char* e = tune_splits ? getenv(tune_splits) : nullptr) {
+        const int forced = atoi(e), us4 = 4 * hv.wgs_per_cu;
+        if (forced >= 1 && forced <= p.vocab_tiles && forced <= kMaxSplits && (forced < us4 || forced % us4 == 0)) p.splits = forced;
+    }
+#endif
     const int us = 4 * hv.wgs_per_cu;
     p.unit_splits = p.splits < us ? p.splits : us;
     p.unit_cols = p.splits / p.unit_splits;
     p.unit_rows = (p.row_tiles + 7) / 8;
     p.n_units = p.unit_rows * p.unit_cols;
-    p.col_major = 1;
+    p.col_major = hv.col_major;
 #ifdef TPPO_TUNING
     if (const char* e = getenv("TPPO_HEAD_ORDER")) p.col_major = atoi(e);     // tuning builds only: 0 = row-major units
+    if (const char* e = tune_order ? getenv(tune_order) : nullptr) p.col_major = atoi(e);
 #endif
     p.unit_arrivals = static_cast<int32_t*>(arrivals);
 }
