@@ -219,7 +219,7 @@ int tppo_egae(const float* rewards, const float* values, const int32_t* resp_off
  * or may not call anything that does: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs,
  * results and errors as tppo_egae with plan = NULL, but there is no workspace
- * argument: the call builds its plan in a fixed array of just under 4 MiB that
+ * argument: the call builds its plan in a fixed array of 5.3 MiB that
  * is part of the library's image on every GPU the library runs on (it stays
  * there until the process ends).  It calls no hipMalloc / hipFree and no
  * library routine that allocates; the first call on a device asks the runtime

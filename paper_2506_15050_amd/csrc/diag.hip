@@ -12,7 +12,6 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float diag_f32x4;
 
 constexpr int kDiagThreads = 512, kDiagGroups = 256;
 constexpr int kDiagFragsPerLane = 8 + 4;                       // W-role and token-role fragments of one K step of 32
-constexpr int kDiagOperandElems = 64 * kDiagFragsPerLane * 8;  // bf16 values the caller provides
 
 __global__ __launch_bounds__(kDiagThreads, 2) void diag_mfma_rate_kernel(const uint16_t* __restrict__ operands,
                                                                         float* __restrict__ out, int iters) {
@@ -52,7 +51,6 @@ __global__ __launch_bounds__(kDiagThreads, 2) void diag_mfma_rate_kernel(const u
 // mix: lanes on consecutive 16 bytes, non-temporal loads and stores (every byte is touched once), ONE 16-byte
 // element per thread and stream, small workgroups that come and go (the dispatcher keeps the chip full; a
 // grid-stride loop of resident workgroups was measured 5-8 % slower with stores in the mix).
-constexpr int kStreamMax = 8;
 typedef float stream_vec __attribute__((ext_vector_type(4)));
 
 template <int NR, int NW, int T>

@@ -280,7 +280,7 @@ __device__ __forceinline__ void tile_front(TileIn& x, TileMid& m, lds_float4* s_
                                            const Plan& pl, int lane, const LaneWeights& wa,
                                            const LaneWeights& wr) {
     const double gamma = p.gamma, c = p.sa.m;
-    const int n_resp = p.n_resp, pos = x.pos;
+    const int n_resp = p.n_resp;
     const int base = x.t.base(), begin = kFull ? 0 : x.t.begin(), end = kFull ? kTileTokens : begin + x.t.len();
     // V(s_{t+1}) of the tile's last token: the next tile's first value, or the value of the state after the
     // sequence -- 0 for a finished one, else the bootstrap value, by default V(s_{l-1}) (Sec. 3.1)
@@ -633,7 +633,7 @@ extern "C" int tppo_egae(const float* rewards, const float* values, const int32_
 // part of the library's image on every GPU it runs on.
 namespace tppo {
 constexpr int64_t kStaticTiles = 47872;                            // plan capacity of the array, in tiles
-constexpr size_t kStaticBytes = plan_bytes_for(kStaticTiles);      // just under 4 MiB
+constexpr size_t kStaticBytes = plan_bytes_for(kStaticTiles);      // 5.27 MiB
 static __device__ __align__(256) unsigned char scratch[kStaticBytes];
 
 // The array's address on the current device.  In host code `scratch` is only a handle: the address has to be

@@ -2,13 +2,17 @@
 // (Eqs. (valueclip), (valueloss)) as masked streaming reductions over the
 // response-packed arrays.  Token sets follow Sec. 3.2: policy tokens are the
 // first keep_len[i] window tokens of each sequence, value tokens all window
-// tokens of finished sequences.  The tokens are cut into tiles that never
-// straddle two sequences (plan.h), so set membership is one comparison per
-// token for the policy set and one flag per tile for the value set: no mask
-// array is read, and a tile outside a set issues no loads for that set.
+// tokens of finished sequences.  No token depends on another, so the pass walks
+// the arrays in aligned frames of 1024 tokens (plan.h), four consecutive tokens
+// per thread: a frame's descriptor names the sequence of its first token, and
+// a thread whose four tokens lie inside that sequence (all threads of most
+// frames) knows its share of both sets from two comparisons.  Only a thread at
+// or beyond a sequence boundary inside the frame looks into the offset arrays.
+// No mask array is read, and a thread with no member of a set issues no loads
+// for that set.
 //
-// One launch per call.  A persistent grid walks the tile list; a thread issues all loads of its share of a
-// tile at once (non-temporal 16-byte accesses, consecutive lanes on consecutive 16 bytes, no branch and no wait
+// One launch per call.  A persistent grid walks the frames; a thread issues all loads of its share of a
+// frame at once (non-temporal 16-byte accesses, consecutive lanes on consecutive 16 bytes, no branch and no wait
 // between them), and the many co-resident wavefronts cover each other's memory latency: there is deliberately
 // no software pipeline, whose second register set would halve the wavefronts per CU while the compiler, unable
 // to count loads issued under a predicate, waits for all of them anyway.  Sums are token-level (Sec. 4.1.1): a
@@ -27,14 +31,18 @@ namespace tppo {
 #define TPPO_LOSS_THREADS 256
 #endif
 constexpr int kLossThreads = TPPO_LOSS_THREADS;
-constexpr int kLossSlots = kTileTokens / (4 * kLossThreads);      // 16-byte groups per thread and array: 1
-constexpr int kLossGroups = 2048;                                  // workgroups of the persistent grid: 8 per CU
+constexpr int kLossParts = kTileTokens / (4 * kLossThreads);      // a workgroup takes this fraction of a frame, four tokens per thread
+static_assert(kLossParts >= 1 && kLossParts * 4 * kLossThreads == kTileTokens, "whole parts of a frame");
+// Workgroups of the persistent grids, measured on 40 M tokens: the read-only pass is fastest with 8 per CU; the
+// pass that also writes two arrays with 4 per CU (fewer accesses in flight at once, as for a bare elementwise
+// pass of 6 reads and 2 writes).
+constexpr int kLossGroups = 2048, kGradGroups = 1024;
 constexpr int kFinishSpin = 1 << 20;
 static_assert(kLossGroups <= kFinishGroups, "the plan holds partial sums for kFinishGroups workgroups");
 
 struct LossParams {
     const float *logp_new, *logp_old, *adv, *v_new, *v_old, *ret;
-    const int32_t *keep_len, *done;
+    const int32_t *resp_off, *keep_len, *done;
     void* plan;
     int32_t* status;
     int B, n_resp;
@@ -100,63 +108,106 @@ __device__ __forceinline__ void store4(float* __restrict__ dst, int first, const
     }
 }
 
-// What one thread holds of one tile: kLossSlots 16-byte groups of each of the six arrays.
+// What one thread holds of one frame: 16 bytes of each of the six arrays.
 struct LossRegs {
-    float4u ln[kLossSlots], lo[kLossSlots], a[kLossSlots];
-    float4u v[kLossSlots], vo[kLossSlots], r[kLossSlots];
+    float4u ln, lo, a, v, vo, r;
 };
 
-// Which of a tile's tokens are in the two sets (wave-uniform, lives in scalar registers), and from it how many
-// of the four tokens of group g of thread tid exist / are policy tokens / are value tokens.
-struct TileSets {
-    int start, len, pol, val;      // first token; tokens; policy tokens (a prefix); value tokens (all or none)
-    __device__ __forceinline__ int k0(int g, int tid) const { return g * 4 * kLossThreads + tid * 4; }
-    __device__ __forceinline__ int n_tok(int g, int tid) const { return min(max(len - k0(g, tid), 0), 4); }
-    __device__ __forceinline__ int n_pol(int g, int tid) const { return min(max(pol - k0(g, tid), 0), 4); }
-    __device__ __forceinline__ int n_val(int g, int tid) const { return min(max(val - k0(g, tid), 0), 4); }
+// A thread's four consecutive tokens: the first one's index, how many of the four exist, and which are policy /
+// value tokens (bit e: token first + e).
+struct TokenSets {
+    int first, n_tok, pol, val;
 };
 
-__device__ __forceinline__ TileSets tile_sets(const Tile& t, int32_t word, bool has_pol, bool has_val) {
-    TileSets s;
-    s.start = t.start;
-    s.len = t.len();
-    s.pol = has_pol ? min(word & 0xFFFF, s.len) : 0;
-    s.val = (has_val && (word >> 16) != 0) ? s.len : 0;
-    return s;
+// The sets of the tokens at or beyond `end` of sequence `seg` (the last one the frame's descriptor knows):
+// token by token, moving on to the sequence that holds the token -- normally the next one, whose four
+// metadata words are asked for together; past empty sequences by bisection of the offsets, so the work is
+// bounded whatever the layout.  Offsets that are not a layout (decreasing, beyond the arrays) put a token in
+// no set; they cannot make an access leave the arrays.
+__device__ __forceinline__ void walk_sets(const LossParams& p, int seg, int end, TokenSets& ts) {
+    int pol_end = end;
+    bool fin = false, inside = false;
+    for (int e = 0; e < ts.n_tok; ++e) {
+        const int q = ts.first + e;
+        if (q < end && !inside) continue;                          // a token the descriptor covered
+        if (q >= end) {                                            // find the sequence that holds q
+            int nxt = seg + 1;
+            if (nxt >= p.B) break;                                 // beyond the last sequence
+            int lo = p.resp_off[nxt], hi = p.resp_off[nxt + 1], keep = p.keep_len[nxt], dn = p.done[nxt];
+            if (hi <= q) {                                         // not the next one: the last sequence that begins at or before q
+                int a = nxt + 1, b = p.B - 1;
+                if (a > b) break;
+                while (a < b) {
+                    const int m = (a + b + 1) >> 1;
+                    if (p.resp_off[m] <= q) a = m; else b = m - 1;
+                }
+                nxt = a;
+                lo = p.resp_off[nxt]; hi = p.resp_off[nxt + 1]; keep = p.keep_len[nxt]; dn = p.done[nxt];
+            }
+            inside = q >= lo && q < hi;
+            if (!inside) continue;                                 // no sequence holds q (seg, end unchanged: look again)
+            seg = nxt;
+            end = hi;
+            pol_end = lo + min(max(keep, 0), hi - lo);
+            fin = dn != 0;
+        }
+        ts.pol |= q < pol_end ? 1 << e : 0;
+        ts.val |= fin ? 1 << e : 0;
+    }
 }
 
-// What the loop keeps of the NEXT tile while it works on the current one: descriptor and set word, both asked
-// for a whole tile ahead and independent of each other (one trip through the scalar cache, not two in a row).
-struct TileAhead {
-    Tile d;
-    int32_t word;
-};
-
-__device__ __forceinline__ TileAhead fetch_ahead(const Plan& pl, int pos) {
-    return TileAhead{load_tile(pl.tiles + pos), load_uniform(pl.sets + pos)};
-}
-
-// Issue the loads of a tile.  Four consecutive tokens per access, consecutive lanes on consecutive 16 bytes (the
-// access shape that streams at full rate), non-temporal.  Nothing is loaded for groups that hold no member of a
-// set.  A group with 1..3 members is loaded whole -- the surplus elements are never used -- so that no branch
-// and no wait separates the loads and all of them are in flight together; the one group that would read past
-// the END OF THE ARRAY reads the array's last 16 bytes instead (see unshift).  Needs n_resp >= 4.
-__device__ __forceinline__ void loss_load(LossRegs& x, const LossParams& p, const TileSets& ts, int tid) {
-    const float4u zero = {0.f, 0.f, 0.f, 0.f};
+__device__ __forceinline__ TokenSets token_sets(const LossParams& p, const FrameDesc& d, int item, int tid,
+                                                bool has_pol, bool has_val) {
+    TokenSets ts;
+    ts.first = item * (4 * kLossThreads) + 4 * tid;                // item: part item % kLossParts of frame item / kLossParts
+    ts.n_tok = min(max(p.n_resp - ts.first, 0), 4);
+    if (ts.first + 4 <= d.end) {                                   // all four in the frame's first sequence
+        ts.pol = (1 << min(max(d.pol_end - ts.first, 0), 4)) - 1;
+        ts.val = d.fin != 0 ? 0xF : 0;
+    } else {                                                       // token by token: first sequence, second, or beyond
+        ts.pol = ts.val = 0;
 #pragma unroll
-    for (int g = 0; g < kLossSlots; ++g) {
-        const int at = min(ts.start + ts.k0(g, tid), p.n_resp - 4);
-        x.ln[g] = x.lo[g] = x.a[g] = x.v[g] = x.vo[g] = x.r[g] = zero;
-        if (ts.n_pol(g, tid) > 0) {
-            x.ln[g] = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.logp_new + at));
-            x.lo[g] = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.logp_old + at));
-            x.a[g] = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.adv + at));
+        for (int e = 0; e < 4; ++e) {
+            const int q = ts.first + e;
+            const bool in1 = q < d.end, in2 = !in1 && q < d.end2;
+            ts.pol |= ((in1 && q < d.pol_end) || (in2 && q < d.pol_end2)) ? 1 << e : 0;
+            ts.val |= ((in1 && d.fin != 0) || (in2 && d.fin2 != 0)) ? 1 << e : 0;
         }
-        if (ts.n_val(g, tid) > 0) {
-            x.v[g] = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.v_new + at));
-            x.vo[g] = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.v_old + at));
-            x.r[g] = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.ret + at));
-        }
+        if (ts.first + ts.n_tok > d.end2) walk_sets(p, d.seg2, d.end2, ts);
+    }
+    ts.pol = (has_pol && ts.n_tok > 0) ? ts.pol & ((1 << ts.n_tok) - 1) : 0;
+    ts.val = (has_val && ts.n_tok > 0) ? ts.val & ((1 << ts.n_tok) - 1) : 0;
+    return ts;
+}
+
+// A frame's descriptor, checked: a plan is caller-held memory.  Whatever it says, no access leaves the arrays
+// (tokens are addressed by frame and thread, not through the descriptor); only `seg2` indexes the metadata.
+__device__ __forceinline__ FrameDesc checked_frame(FrameDesc d, const LossParams& p, int tid) {
+    if (d.seg < 0 || d.seg >= p.B || d.seg2 < 0 || d.seg2 >= p.B) {
+        if (tid == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
+        d = FrameDesc{p.B - 1, 0, 0, 0, p.B - 1, 0, 0, 0};         // every token looks for its sequence itself and finds none
+    }
+    return d;
+}
+
+// Issue the loads of a thread's four tokens.  Consecutive lanes on consecutive 16 bytes (the access shape that
+// streams at full rate), non-temporal.  Nothing is loaded for a set none of the four is in; with 1..3 members
+// the 16 bytes are loaded whole -- the surplus elements are never used -- so that no branch and no wait
+// separates the loads and all of them are in flight together; the one thread that would read past the END OF
+// THE ARRAY reads the array's last 16 bytes instead (see unshift).  Needs n_resp >= 4.
+__device__ __forceinline__ void loss_load(LossRegs& x, const LossParams& p, const TokenSets& ts) {
+    const float4u zero = {0.f, 0.f, 0.f, 0.f};
+    const int at = min(ts.first, p.n_resp - 4);
+    x.ln = x.lo = x.a = x.v = x.vo = x.r = zero;
+    if (ts.pol != 0) {
+        x.ln = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.logp_new + at));
+        x.lo = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.logp_old + at));
+        x.a = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.adv + at));
+    }
+    if (ts.val != 0) {
+        x.v = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.v_new + at));
+        x.vo = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.v_old + at));
+        x.r = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(p.ret + at));
     }
 }
 
@@ -168,41 +219,58 @@ __device__ __forceinline__ float4u rotate_left(float4u t, int sh) {
     return o;
 }
 
-// the array's last few tokens were loaded as part of its last 16 bytes: move them into place (practically never
-// taken: at most one group of the whole batch is affected)
-__device__ __forceinline__ void unshift(LossRegs& x, const TileSets& ts, int n_resp, int tid) {
-    if (__builtin_expect(ts.start + ts.len <= n_resp - 4, 1)) return;        // wave-uniform: not the array's end
-#pragma unroll
-    for (int g = 0; g < kLossSlots; ++g) {
-        const int first = ts.start + ts.k0(g, tid);
-        const int sh = ts.k0(g, tid) < ts.len ? max(first - (n_resp - 4), 0) : 0;
-        x.ln[g] = rotate_left(x.ln[g], sh); x.lo[g] = rotate_left(x.lo[g], sh); x.a[g] = rotate_left(x.a[g], sh);
-        x.v[g] = rotate_left(x.v[g], sh); x.vo[g] = rotate_left(x.vo[g], sh); x.r[g] = rotate_left(x.r[g], sh);
-    }
+// the array's last few tokens were loaded as part of its last 16 bytes: move them into place (only in the last
+// frame, and there for at most one thread)
+__device__ __forceinline__ void unshift(LossRegs& x, const TokenSets& ts, int item, int n_resp) {
+    if (__builtin_expect((item + 1) * (4 * kLossThreads) <= n_resp, 1)) return;   // wave-uniform: not the array's end
+    const int sh = ts.n_tok > 0 ? max(ts.first - (n_resp - 4), 0) : 0;
+    x.ln = rotate_left(x.ln, sh); x.lo = rotate_left(x.lo, sh); x.a = rotate_left(x.a, sh);
+    x.v = rotate_left(x.v, sh); x.vo = rotate_left(x.vo, sh); x.r = rotate_left(x.r, sh);
 }
 
 // The sums of all workgroups, collected by the one with the highest id.  Every thread adds up the workgroups
 // tid, tid + blockDim, ... in that order, then the threads are added up in a fixed tree: deterministic.
-// Returns false when a wait gave up.
-template <int kSums>
+// The words of kBatch workgroups are asked for together -- a thread's polls are round trips through the L2, and
+// one after the other they would be the longest part of a call on a small batch; only a workgroup that has
+// not published yet is polled again (bounded).  Returns false when a wait gave up.
+template <int kSums, int kBatch>
 __device__ __forceinline__ bool collect_sums(const unsigned long long* words, uint32_t tag, int groups,
                                              double (&tot)[kSums], double* s_red, int* s_flag) {
+    constexpr int kWords = 2 * kSums;
     double acc[kSums];
 #pragma unroll
     for (int q = 0; q < kSums; ++q) acc[q] = 0.0;
     bool ok = true;
-    for (int g = threadIdx.x; g < groups; g += blockDim.x) {
+    const int step = (int)blockDim.x;
+    for (int g0 = threadIdx.x; g0 < groups; g0 += step * kBatch) {
+        unsigned long long w[kBatch][kWords];
 #pragma unroll
-        for (int q = 0; q < kSums; ++q) {
-            const unsigned long long* p = words + (int64_t)g * kFinishWords + 2 * q;
-            double x = 0.0;
-            bool ready = false;
+        for (int b = 0; b < kBatch; ++b) {
+            const int g = min(g0 + b * step, groups - 1);          // (a clamped duplicate is read and not used)
+#pragma unroll
+            for (int q = 0; q < kWords; ++q)
+                w[b][q] = __hip_atomic_load(words + (int64_t)g * kFinishWords + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            const int g = g0 + b * step;
+            if (g >= groups) break;
+            bool ready = true;
+#pragma unroll
+            for (int q = 0; q < kWords; ++q) ready = ready && (uint32_t)(w[b][q] >> 32) == tag;
             for (int spin = 0; spin < kFinishSpin && !ready; ++spin) {
-                ready = poll(p, tag, x);
-                if (!ready) __builtin_amdgcn_s_sleep(2);
+                __builtin_amdgcn_s_sleep(2);
+                ready = true;
+#pragma unroll
+                for (int q = 0; q < kWords; ++q) {
+                    w[b][q] = __hip_atomic_load(words + (int64_t)g * kFinishWords + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ready = ready && (uint32_t)(w[b][q] >> 32) == tag;
+                }
             }
             ok = ok && ready;
-            acc[q] += x;
+#pragma unroll
+            for (int q = 0; q < kSums; ++q)
+                acc[q] += ready ? (double)__uint_as_float((unsigned)w[b][2 * q]) + (double)__uint_as_float((unsigned)w[b][2 * q + 1]) : 0.0;
         }
     }
     if (threadIdx.x == 0) *s_flag = 1;
@@ -237,7 +305,7 @@ __global__ __launch_bounds__(kLossThreads, 8) void loss_kernel(LossParams p, tpp
     const int tid = threadIdx.x;
     const bool has_pol = p.logp_new != nullptr, has_val = p.v_new != nullptr;
     const bool plan_ok = pl.hdr->B == p.B && pl.hdr->n_resp == p.n_resp && pl.hdr->has_sets != 0 &&
-                         pl.hdr->n_tiles <= pl.cap && pl.cap >= p.n_resp / kTileTokens + p.B + 1;
+                         pl.cap >= p.n_resp / kTileTokens + p.B + 1;
     if (!plan_ok) {                                                // not this batch's plan: touch nothing of it
         if (blockIdx.x == 0 && tid == 0) {
             set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
@@ -245,41 +313,31 @@ __global__ __launch_bounds__(kLossThreads, 8) void loss_kernel(LossParams p, tpp
         }
         return;
     }
-    const int count = pl.hdr->n_tiles;
+    const int count = (p.n_resp + 4 * kLossThreads - 1) / (4 * kLossThreads);     // work items: parts of frames
 
     double pol_acc = 0.0, val_acc = 0.0;
-    auto sets_of = [&](const TileAhead& a) {
-        if (!tile_valid(a.d, p.n_resp, p.B, pl.cap)) {             // a damaged plan: no tokens, and the call says so
-            if (tid == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
-            return TileSets{0, 0, 0, 0};
-        }
-        return tile_sets(a.d, a.word, has_pol, has_val);
-    };
-    TileAhead ahead = {};
-    if ((int)blockIdx.x < count) ahead = fetch_ahead(pl, blockIdx.x);
-    for (int w = blockIdx.x; w < count; w += gridDim.x) {
-        const TileSets ts_cur = sets_of(ahead);
-        if (w + (int)gridDim.x < count) ahead = fetch_ahead(pl, w + gridDim.x);     // the next tile's, meanwhile
+    FrameDesc ahead = {};
+    if ((int)blockIdx.x < count) ahead = load_frame(pl.frames + blockIdx.x / kLossParts);
+    for (int f = blockIdx.x; f < count; f += gridDim.x) {
+        const FrameDesc d = checked_frame(ahead, p, tid);
+        if (f + (int)gridDim.x < count) ahead = load_frame(pl.frames + (f + gridDim.x) / kLossParts);     // the next item's, meanwhile
+        const TokenSets ts = token_sets(p, d, f, tid, has_pol, has_val);
         LossRegs cur;
-        loss_load(cur, p, ts_cur, tid);
-        unshift(cur, ts_cur, p.n_resp, tid);
-        float pol_t = 0.f, val_t = 0.f;                            // this thread's <= 8 terms of the tile
+        loss_load(cur, p, ts);
+        unshift(cur, ts, f, p.n_resp);
+        float pol_t = 0.f, val_t = 0.f;                            // this thread's <= 8 terms of the frame
+        if (ts.pol != 0) {
 #pragma unroll
-        for (int g = 0; g < kLossSlots; ++g) {
-            const int n_pol = ts_cur.n_pol(g, tid), n_val = ts_cur.n_val(g, tid);
-            if (n_pol > 0) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float t = surrogate(cur.ln[g][e], cur.lo[g][e], cur.a[g][e], p.ratio_lo, p.ratio_hi);
-                    pol_t += e < n_pol ? t : 0.f;                  // select, never multiply by a mask
-                }
+            for (int e = 0; e < 4; ++e) {
+                const float t = surrogate(cur.ln[e], cur.lo[e], cur.a[e], p.ratio_lo, p.ratio_hi);
+                pol_t += (ts.pol >> e & 1) ? t : 0.f;              // select, never multiply by a mask
             }
-            if (n_val > 0) {
+        }
+        if (ts.val != 0) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float t = value_term(cur.v[g][e], cur.vo[g][e], cur.r[g][e], p.xi_low, p.xi_high);
-                    val_t += e < n_val ? t : 0.f;
-                }
+            for (int e = 0; e < 4; ++e) {
+                const float t = value_term(cur.v[e], cur.vo[e], cur.r[e], p.xi_low, p.xi_high);
+                val_t += (ts.val >> e & 1) ? t : 0.f;
             }
         }
         pol_acc += (double)pol_t;
@@ -294,7 +352,7 @@ __global__ __launch_bounds__(kLossThreads, 8) void loss_kernel(LossParams p, tpp
     }
     if (blockIdx.x != gridDim.x - 1) return;
     double tot[2];
-    const bool ok = collect_sums<2>(pl.finish_words, p.tag, (int)gridDim.x, tot, s_red, &s_flag);
+    const bool ok = collect_sums<2, 4>(pl.finish_words, p.tag, (int)gridDim.x, tot, s_red, &s_flag);
     if (tid == 0) {
         if (!ok) {
             set_status(p.status, TPPO_STATUS_TIMEOUT);
@@ -342,7 +400,7 @@ struct GradParams {
     long long policy_denominator, value_denominator;     // <= 0: the call's own token counts
 };
 
-__global__ __launch_bounds__(kLossThreads, 8) void loss_grad_kernel(GradParams gp, tppo_loss_out* __restrict__ out,
+__global__ __launch_bounds__(kLossThreads, 4) void loss_grad_kernel(GradParams gp, tppo_loss_out* __restrict__ out,
                                                                 tppo_loss_stats* __restrict__ stats) {
     __shared__ double s_red[kLossThreads / kWave];
     __shared__ int s_flag;
@@ -351,7 +409,7 @@ __global__ __launch_bounds__(kLossThreads, 8) void loss_grad_kernel(GradParams g
     const int tid = threadIdx.x;
     const bool has_pol = p.logp_new != nullptr, has_val = p.v_new != nullptr;
     const bool plan_ok = pl.hdr->B == p.B && pl.hdr->n_resp == p.n_resp && pl.hdr->has_sets != 0 &&
-                         pl.hdr->n_tiles <= pl.cap && pl.cap >= p.n_resp / kTileTokens + p.B + 1;
+                         pl.cap >= p.n_resp / kTileTokens + p.B + 1;
     if (!plan_ok) {                                                // not this batch's plan: touch nothing of it
         if (blockIdx.x == 0 && tid == 0) {
             set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
@@ -359,7 +417,7 @@ __global__ __launch_bounds__(kLossThreads, 8) void loss_grad_kernel(GradParams g
         }
         return;
     }
-    const int count = pl.hdr->n_tiles;
+    const int count = (p.n_resp + 4 * kLossThreads - 1) / (4 * kLossThreads);     // work items: parts of frames
     const long long np = has_pol ? pl.hdr->n_policy : 0, nv = has_val ? pl.hdr->n_value : 0;
     const long long den_p = gp.policy_denominator > 0 ? gp.policy_denominator : np;
     const long long den_v = gp.value_denominator > 0 ? gp.value_denominator : nv;
@@ -368,61 +426,50 @@ __global__ __launch_bounds__(kLossThreads, 8) void loss_grad_kernel(GradParams g
 
     double pol_acc = 0.0, val_acc = 0.0, ratio_acc = 0.0;
     int pol_clipped = 0, val_clipped = 0;
-    auto sets_of = [&](const TileAhead& a) {
-        if (!tile_valid(a.d, p.n_resp, p.B, pl.cap)) {             // a damaged plan: no tokens, and the call says so
-            if (tid == 0) set_status(p.status, TPPO_STATUS_BAD_LAYOUT);
-            return TileSets{0, 0, 0, 0};
-        }
-        return tile_sets(a.d, a.word, has_pol, has_val);
-    };
-    TileAhead ahead = {};
-    if ((int)blockIdx.x < count) ahead = fetch_ahead(pl, blockIdx.x);
-    for (int w = blockIdx.x; w < count; w += gridDim.x) {
-        const TileSets ts_cur = sets_of(ahead);
-        if (w + (int)gridDim.x < count) ahead = fetch_ahead(pl, w + gridDim.x);     // the next tile's, meanwhile
+    FrameDesc ahead = {};
+    if ((int)blockIdx.x < count) ahead = load_frame(pl.frames + blockIdx.x / kLossParts);
+    for (int f = blockIdx.x; f < count; f += gridDim.x) {
+        const FrameDesc d = checked_frame(ahead, p, tid);
+        if (f + (int)gridDim.x < count) ahead = load_frame(pl.frames + (f + gridDim.x) / kLossParts);     // the next item's, meanwhile
+        const TokenSets ts = token_sets(p, d, f, tid, has_pol, has_val);
         LossRegs cur;
-        loss_load(cur, p, ts_cur, tid);
-        unshift(cur, ts_cur, p.n_resp, tid);
+        loss_load(cur, p, ts);
+        unshift(cur, ts, f, p.n_resp);
         float pol_t = 0.f, val_t = 0.f, ratio_t = 0.f;
+        if (has_pol && ts.n_tok > 0) {
+            float gl[4] = {0.f, 0.f, 0.f, 0.f};
+            if (ts.pol != 0) {
 #pragma unroll
-        for (int g = 0; g < kLossSlots; ++g) {
-            const int first = ts_cur.start + ts_cur.k0(g, tid);
-            const int n_tok = ts_cur.n_tok(g, tid), n_pol = ts_cur.n_pol(g, tid), n_val = ts_cur.n_val(g, tid);
-            if (has_pol && n_tok > 0) {
-                float gl[4] = {0.f, 0.f, 0.f, 0.f};
-                if (n_pol > 0) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float rho = ratio_exp(cur.ln[g][e] - cur.lo[g][e]);
-                        const float u = rho * cur.a[g][e];
-                        const float c = clampf(rho, p.ratio_lo, p.ratio_hi) * cur.a[g][e];
-                        const bool in_set = e < n_pol, unclipped = u <= c, undefined = u != u;
-                        pol_t += in_set ? (undefined ? u : fminf(u, c)) : 0.f;     // select, never multiply by a mask
-                        ratio_t += in_set ? rho : 0.f;
-                        pol_clipped += (in_set && !unclipped && !undefined) ? 1 : 0;
-                        gl[e] = in_set ? (undefined ? u : unclipped ? pol_coef * u : 0.f) : 0.f;
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    const float rho = ratio_exp(cur.ln[e] - cur.lo[e]);
+                    const float u = rho * cur.a[e];
+                    const float c = clampf(rho, p.ratio_lo, p.ratio_hi) * cur.a[e];
+                    const bool in_set = (ts.pol >> e & 1) != 0, unclipped = u <= c, undefined = u != u;
+                    pol_t += in_set ? (undefined ? u : fminf(u, c)) : 0.f;     // select, never multiply by a mask
+                    ratio_t += in_set ? rho : 0.f;
+                    pol_clipped += (in_set && !unclipped && !undefined) ? 1 : 0;
+                    gl[e] = in_set ? (undefined ? u : unclipped ? pol_coef * u : 0.f) : 0.f;
                 }
-                store4(gp.grad_logp, first, gl, n_tok);
             }
-            if (has_val && n_tok > 0) {
-                float gv[4] = {0.f, 0.f, 0.f, 0.f};
-                if (n_val > 0) {
+            store4(gp.grad_logp, ts.first, gl, ts.n_tok);
+        }
+        if (has_val && ts.n_tok > 0) {
+            float gv[4] = {0.f, 0.f, 0.f, 0.f};
+            if (ts.val != 0) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float d0 = cur.v[g][e] - cur.r[g][e];
-                        const float d1 = clampf(cur.v[g][e], cur.vo[g][e] - p.xi_low, cur.vo[g][e] + p.xi_high) - cur.r[g][e];
-                        const float q0 = d0 * d0, q1 = d1 * d1;
-                        const bool in_set = e < n_val, unclipped = q0 >= q1;
-                        const bool undefined = value_undefined(d0, d1, cur.vo[g][e]);
-                        const float nan = __builtin_nanf("");
-                        val_t += in_set ? (undefined ? nan : fmaxf(q0, q1)) : 0.f;
-                        val_clipped += (in_set && !unclipped && !undefined) ? 1 : 0;
-                        gv[e] = in_set ? (undefined ? nan : unclipped ? val_coef * d0 : 0.f) : 0.f;
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    const float d0 = cur.v[e] - cur.r[e];
+                    const float d1 = clampf(cur.v[e], cur.vo[e] - p.xi_low, cur.vo[e] + p.xi_high) - cur.r[e];
+                    const float q0 = d0 * d0, q1 = d1 * d1;
+                    const bool in_set = (ts.val >> e & 1) != 0, unclipped = q0 >= q1;
+                    const bool undefined = value_undefined(d0, d1, cur.vo[e]);
+                    const float nan = __builtin_nanf("");
+                    val_t += in_set ? (undefined ? nan : fmaxf(q0, q1)) : 0.f;
+                    val_clipped += (in_set && !unclipped && !undefined) ? 1 : 0;
+                    gv[e] = in_set ? (undefined ? nan : unclipped ? val_coef * d0 : 0.f) : 0.f;
                 }
-                store4(gp.grad_v, first, gv, n_tok);
             }
+            store4(gp.grad_v, ts.first, gv, ts.n_tok);
         }
         pol_acc += (double)pol_t;
         val_acc += (double)val_t;
@@ -437,7 +484,7 @@ __global__ __launch_bounds__(kLossThreads, 8) void loss_grad_kernel(GradParams g
     }
     if (blockIdx.x != gridDim.x - 1 || (!out && !stats)) return;
     double tot[kGradSums];
-    const bool ok = collect_sums<kGradSums>(pl.finish_words, p.tag, (int)gridDim.x, tot, s_red, &s_flag);
+    const bool ok = collect_sums<kGradSums, 2>(pl.finish_words, p.tag, (int)gridDim.x, tot, s_red, &s_flag);
     if (tid == 0) {
         if (!ok) {
             set_status(p.status, TPPO_STATUS_TIMEOUT);
@@ -535,15 +582,16 @@ __global__ __launch_bounds__(256) void loss_tiny_kernel(GradParams gp, const int
 
 // Workgroups of the persistent grids.  Nothing depends on all of them being resident at once: only the
 // workgroup dispatched last waits, and only for workgroups dispatched before it.
-static int loss_groups(int64_t cap) {
-    int groups = kLossGroups;
+static int loss_groups(int64_t n_resp, bool grad) {
+    const int64_t frames = (n_resp + 4 * kLossThreads - 1) / (4 * kLossThreads);    // work items
+    int groups = grad ? kGradGroups : kLossGroups;
 #ifdef TPPO_TUNING
     if (const char* e = getenv("TPPO_LOSS_GROUPS")) {
         const int forced = atoi(e);
         if (forced >= 1 && forced <= kFinishGroups) groups = forced;
     }
 #endif
-    return cap < groups ? (int)cap : groups;
+    return frames < groups ? (int)frames : groups;
 }
 
 // checks shared by the forward and the backward entry point; on TPPO_OK `plan` points at a plan of this layout
@@ -572,12 +620,12 @@ static int loss_prepare(int n_pol_ptr, int n_val_ptr, const int32_t* resp_off, c
 }
 
 static void fill_params(LossParams& p, const float* logp_new, const float* logp_old, const float* adv,
-                        const float* v_new, const float* v_old, const float* ret, const int32_t* keep_len,
-                        const int32_t* done, void* plan, int32_t* status, int64_t B, int64_t n_resp, float eps_low,
+                        const float* v_new, const float* v_old, const float* ret, const int32_t* resp_off,
+                        const int32_t* keep_len, const int32_t* done, void* plan, int32_t* status, int64_t B, int64_t n_resp, float eps_low,
                         float eps_high, float xi_low, float xi_high) {
     p.logp_new = logp_new; p.logp_old = logp_old; p.adv = adv;
     p.v_new = v_new; p.v_old = v_old; p.ret = ret;
-    p.keep_len = keep_len; p.done = done;
+    p.resp_off = resp_off; p.keep_len = keep_len; p.done = done;
     p.plan = plan; p.status = status;
     p.B = (int)B; p.n_resp = (int)n_resp;
     p.tag = next_call_tag();
@@ -614,15 +662,15 @@ extern "C" int tppo_ppo_losses(const float* logp_new, const float* logp_old, con
     }
     if (n_resp < 4) {
         GradParams gp = {};
-        fill_params(gp.fwd, logp_new, logp_old, adv, v_new, v_old, ret, keep_len, done, plan, status, B, n_resp,
+        fill_params(gp.fwd, logp_new, logp_old, adv, v_new, v_old, ret, resp_off, keep_len, done, plan, status, B, n_resp,
                     eps_low, eps_high, xi_low, xi_high);
         hipLaunchKernelGGL(loss_tiny_kernel<false>, dim3(1), dim3(256), 0, s, gp, resp_off, out, (tppo_loss_stats*)nullptr);
         return launch_result();
     }
     LossParams p;
-    fill_params(p, logp_new, logp_old, adv, v_new, v_old, ret, keep_len, done, plan, status, B, n_resp, eps_low,
+    fill_params(p, logp_new, logp_old, adv, v_new, v_old, ret, resp_off, keep_len, done, plan, status, B, n_resp, eps_low,
                 eps_high, xi_low, xi_high);
-    hipLaunchKernelGGL(loss_kernel, dim3(loss_groups(plan_max_tiles(n_resp, B))), dim3(kLossThreads), 0, s, p, out);
+    hipLaunchKernelGGL(loss_kernel, dim3(loss_groups(n_resp, false)), dim3(kLossThreads), 0, s, p, out);
     return launch_result();
 }
 
@@ -656,7 +704,7 @@ extern "C" int tppo_ppo_losses_backward(const float* logp_new, const float* logp
         return launch_result();
     }
     GradParams gp;
-    fill_params(gp.fwd, logp_new, logp_old, adv, v_new, v_old, ret, keep_len, done, plan, status, B, n_resp, eps_low,
+    fill_params(gp.fwd, logp_new, logp_old, adv, v_new, v_old, ret, resp_off, keep_len, done, plan, status, B, n_resp, eps_low,
                 eps_high, xi_low, xi_high);
     gp.grad_logp = grad_logp; gp.grad_v = grad_v;
     gp.policy_scale = policy_scale; gp.value_scale = value_scale;
@@ -665,6 +713,6 @@ extern "C" int tppo_ppo_losses_backward(const float* logp_new, const float* logp
         hipLaunchKernelGGL(loss_tiny_kernel<true>, dim3(1), dim3(256), 0, s, gp, resp_off, out, stats);
         return launch_result();
     }
-    hipLaunchKernelGGL(loss_grad_kernel, dim3(loss_groups(plan_max_tiles(n_resp, B))), dim3(kLossThreads), 0, s, gp, out, stats);
+    hipLaunchKernelGGL(loss_grad_kernel, dim3(loss_groups(n_resp, true)), dim3(kLossThreads), 0, s, gp, out, stats);
     return launch_result();
 }

@@ -23,9 +23,13 @@
 //   header (256 B)   tile count, the sizes it was built for, the sizes of the
 //                    policy / value token sets of Sec. 3.2
 //   tiles[cap]       the descriptors
-//   sets[cap]        per tile: how many of its tokens are policy tokens (a prefix,
-//                    Sec. 3.2) and whether all of them are value tokens, so that
-//                    the loss kernels need no second, dependent look-up per tile
+//   frames[cap]      per aligned block ("frame") of kTileTokens tokens of the arrays:
+//                    which sequence its first token belongs to, where that sequence
+//                    and its policy tokens (a prefix, Sec. 3.2) end and whether it is
+//                    finished.  The loss kernels, which have no dependency between
+//                    tokens, walk frames instead of tiles: every access is a whole,
+//                    aligned one, and a frame inside one sequence (most are) needs
+//                    no look-up in the offset arrays
 //   scan_words[cap][8]   what a tile of the scan publishes for the tiles to its
 //                    left, {tag << 32 | float bits} each: A hi, A lo, R hi, R lo
 //                    of the tile alone, then the same four with everything to
@@ -76,15 +80,24 @@ struct PlanHeader {
     int32_t cap;                   // descriptors the plan has room for (fixes where the tagged words start)
 };
 
-// a tile's share of the two token sets: policy tokens in the low 16 bits, bit 16 set when the sequence is finished
-__host__ __device__ __forceinline__ int32_t pack_sets(int policy_tokens, bool finished) {
-    return policy_tokens | (finished ? 1 << 16 : 0);
-}
+// What is known about frame f (tokens f * kTileTokens ...) without looking at the offset arrays: the sequence
+// that holds its first token and, when that one ends inside the frame, the sequence that follows it there.
+// Tokens of the frame at or beyond `end2` (a third sequence: only after one of fewer than kTileTokens
+// tokens) are looked up in the offset arrays.
+struct FrameDesc {
+    int32_t seg;       // sequence of the frame's first token
+    int32_t end;       // response-packed index one past that sequence's last token
+    int32_t pol_end;   // one past its last policy token (Sec. 3.2: the first keep_len tokens of the window)
+    int32_t fin;       // != 0: the sequence is finished, its tokens are value tokens
+    int32_t seg2;      // the sequence of token `end` (seg, with end2 == end, when the builder did not look)
+    int32_t end2, pol_end2, fin2;
+};
+static_assert(sizeof(FrameDesc) == 32, "a frame's descriptor is one 32-byte scalar load");
 
 struct Plan {
     PlanHeader* hdr;
     Tile* tiles;
-    int32_t* sets;                       // [cap], pack_sets(); meaningful when hdr->has_sets
+    FrameDesc* frames;                   // [cap], by frame number; the set fields are meaningful when hdr->has_sets
     unsigned long long* scan_words;      // [cap][kScanWords], by Tile::slot()
     unsigned long long* finish_words;    // [kFinishGroups][kFinishWords]
     int cap;
@@ -94,7 +107,7 @@ struct Plan {
 static constexpr int64_t plan_max_tiles(int64_t n_resp, int64_t B) { return n_resp / kTileTokens + B + 1; }
 
 static constexpr size_t plan_bytes_for(int64_t cap) {
-    return 256 + round_up((size_t)cap * sizeof(Tile), 256) + round_up((size_t)cap * 4, 256) +
+    return 256 + round_up((size_t)cap * sizeof(Tile), 256) + round_up((size_t)cap * sizeof(FrameDesc), 256) +
            round_up((size_t)cap * kScanWords * 8, 256) +
            (size_t)kFinishGroups * kFinishWords * sizeof(unsigned long long);
 }
@@ -106,8 +119,8 @@ __host__ __device__ __forceinline__ Plan plan_view(void* raw, int64_t cap) {
     p += 256;
     pl.tiles = reinterpret_cast<Tile*>(p);
     p += ((size_t)cap * sizeof(Tile) + 255) / 256 * 256;
-    pl.sets = reinterpret_cast<int32_t*>(p);
-    p += ((size_t)cap * 4 + 255) / 256 * 256;
+    pl.frames = reinterpret_cast<FrameDesc*>(p);
+    p += ((size_t)cap * sizeof(FrameDesc) + 255) / 256 * 256;
     pl.scan_words = reinterpret_cast<unsigned long long*>(p);
     p += ((size_t)cap * kScanWords * 8 + 255) / 256 * 256;
     pl.finish_words = reinterpret_cast<unsigned long long*>(p);
@@ -125,6 +138,12 @@ __device__ __forceinline__ Tile load_tile(const Tile* p) {
     typedef int int4v __attribute__((ext_vector_type(4)));
     const int4v x = *(const int4v __attribute__((address_space(4)))*)(p);
     return Tile{x[0], x[1], x[2], x[3]};
+}
+
+__device__ __forceinline__ FrameDesc load_frame(const FrameDesc* p) {
+    typedef int int8v __attribute__((ext_vector_type(8)));
+    const int8v x = *(const int8v __attribute__((address_space(4)))*)(p);
+    return FrameDesc{x[0], x[1], x[2], x[3], x[4], x[5], x[6], x[7]};
 }
 
 // A zero the compiler cannot see through.  Added to a wave-uniform address it keeps the load a VECTOR load: with

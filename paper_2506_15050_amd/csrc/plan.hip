@@ -56,6 +56,32 @@ __device__ __forceinline__ int wave_max(int x) {
     return __builtin_amdgcn_readfirstlane(x);
 }
 
+// The tile that begins a frame describes the frame.  If its sequence ends inside the frame, the builder also
+// looks up the sequence that follows (skipping at most kSkipEmpty empty ones; beyond that the consumers look
+// for themselves).
+constexpr int kSkipEmpty = 64;
+__device__ __forceinline__ void note_frame(const Plan& pl, const Tile& d, int lo, int len, const int32_t* resp_off,
+                                           const int32_t* keep_len, const int32_t* done, int B, int n_resp, int keep,
+                                           bool fin) {
+    if ((d.start & (kTileTokens - 1)) != 0) return;
+    const int f = d.start / kTileTokens;
+    if (f >= pl.cap) return;
+    const int end = lo + len;
+    FrameDesc x = {d.seg, end, keep_len ? lo + min(max(keep, 0), len) : lo, fin ? 1 : 0, d.seg, end, end, 0};
+    if (end < d.start + kTileTokens && end < n_resp) {
+        int j = d.seg + 1;
+        for (int step = 0; step < kSkipEmpty && j < B && resp_off[j + 1] <= end; ++step) ++j;
+        if (j < B && resp_off[j] == end && resp_off[j + 1] > end && resp_off[j + 1] <= n_resp) {
+            const int len2 = resp_off[j + 1] - end;
+            x.seg2 = j;
+            x.end2 = end + len2;
+            x.pol_end2 = keep_len ? end + min(max(keep_len[j], 0), len2) : end;
+            x.fin2 = (keep_len && done[j] != 0) ? 1 : 0;
+        }
+    }
+    pl.frames[f] = x;
+}
+
 __device__ __forceinline__ Tile make_tile(int seg, int lo, int len, int tiles, int after) {
     const int c = tiles - 1 - after;
     const int block = lo / kTileTokens + c;                             // which aligned block of the arrays
@@ -223,7 +249,7 @@ __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t
             if (tiles > l && at < cap) {                            // (invalid offsets cannot overflow the list)
                 const Tile d = make_tile(i, lo, len, tiles, l);
                 pl.tiles[at] = d;
-                pl.sets[at] = keep_len ? pack_sets(min(max(keep - (d.start - lo), 0), d.len()), fin) : 0;
+                note_frame(pl, d, lo, len, resp_off, keep_len, done, B, n_resp, keep, fin);
             }
             if (lane == 0) s_cnt3[2][wave][l] += __popcll(has);
         }
@@ -240,7 +266,7 @@ __global__ __launch_bounds__(kBuildThreads) void plan_build_kernel(const int32_t
                 if (at < cap) {
                     const Tile d = make_tile(i, lo, len, tiles, l);
                     pl.tiles[at] = d;
-                    pl.sets[at] = keep_len ? pack_sets(min(max(keep - (d.start - lo), 0), d.len()), fin) : 0;
+                    note_frame(pl, d, lo, len, resp_off, keep_len, done, B, n_resp, keep, fin);
                 }
             }
             const int total = __shfl(inc, kWave - 1);

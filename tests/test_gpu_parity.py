@@ -1192,8 +1192,8 @@ def test_plan_build_and_a_plan_of_another_batch(tp):
 
 def expected_tiles(off, keep, done):
     """The plan's tiles as the header documents them, worked out on the host: a sequence is cut at multiples of
-    1024 of the response-packed index; per tile (first token, tokens, sequence, tile number in the sequence,
-    tiles after it, policy tokens, finished)."""
+    1024 of the response-packed index; per tile (first token, tokens, tiles after it), keyed by (sequence, tile
+    number in the sequence)."""
     out = {}
     for i in range(len(done)):
         lo, hi = int(off[i]), int(off[i + 1])
@@ -1202,16 +1202,36 @@ def expected_tiles(off, keep, done):
         cuts = [lo] + list(range((lo // 1024 + 1) * 1024, hi, 1024)) + [hi]
         for c in range(len(cuts) - 1):
             first, n = cuts[c], cuts[c + 1] - cuts[c]
-            pol = min(max(int(keep[i]) - (first - lo), 0), n) if keep is not None else 0
-            out[(i, c)] = (first, n, len(cuts) - 2 - c, pol, bool(done[i]) if keep is not None else False)
+            out[(i, c)] = (first, n, len(cuts) - 2 - c)
     return out
+
+
+def expected_frames(off, keep, done):
+    """Per aligned block of 1024 tokens: (sequence of its first token, where that sequence ends, where its
+    policy tokens end, finished) and the same for the sequence that follows it inside the block, if one does
+    (else the first sequence again, as an empty range)."""
+    n, B = int(off[-1]), len(done)
+    rows = []
+    for start in range(0, n, 1024):
+        seg = int(np.searchsorted(off, start, side="right")) - 1  # the last sequence that begins at or before
+        lo, hi = int(off[seg]), int(off[seg + 1])
+        row = [seg, hi, lo + min(max(int(keep[seg]), 0), hi - lo), int(done[seg] != 0), seg, hi, hi, 0]
+        if hi < start + 1024 and hi < n:
+            j = seg + 1
+            while off[j + 1] <= hi:                               # (the builder gives up after 64 empty sequences)
+                j += 1
+            assert j - seg <= 64
+            hi2 = int(off[j + 1])
+            row[4:] = [j, hi2, hi + min(max(int(keep[j]), 0), hi2 - hi), int(done[j] != 0)]
+        rows.append(row)
+    return np.array(rows, dtype=np.int32).reshape(-1, 8)
 
 
 @pytest.mark.parametrize("case", ["small", "longcot", "many", "deep", "select"])
 def test_plan_lists_every_tile_once_in_level_order(tp, case):
     """The work plan read back from the device: every tile of every sequence exactly once, with the fields the
     consumers rely on, sorted by the number of tiles after it in its sequence (beyond 32, sequence by sequence);
-    all tagged words zero after the build."""
+    every frame's descriptor; all tagged words zero after the build."""
     import torch
     rng = np.random.default_rng(77)
     if case in ("small", "longcot", "select"):
@@ -1243,18 +1263,18 @@ def test_plan_lists_every_tile_once_in_level_order(tp, case):
     assert n_tiles == len(want)
     tiles = raw[256:256 + 16 * cap].view(np.int32).reshape(cap, 4)[:n_tiles]
     at = 256 + (16 * cap + 255) // 256 * 256
-    sets = raw[at:at + 4 * cap].view(np.int32)[:n_tiles]
-    at += (4 * cap + 255) // 256 * 256
+    want_frames = expected_frames(off, keep, done)
+    frames = raw[at:at + 32 * cap].view(np.int32).reshape(cap, 8)[:len(want_frames)]
+    assert np.array_equal(frames, want_frames)
+    at += (32 * cap + 255) // 256 * 256
     assert not raw[at:].any(), "tagged words must be zero after the build"
     seen = set()
     afters = []
-    for (start, pos_len, seg, after), word in zip(tiles.tolist(), sets.tolist()):
+    for start, pos_len, seg, after in tiles.tolist():
         key = (seg, pos_len >> 11)
         assert key in want and key not in seen, key
         seen.add(key)
-        first, ntok, aft, pol, fin = want[key]
-        assert (start, (pos_len & 2047) + 1, after) == (first, ntok, aft), key
-        assert (word & 0xFFFF, bool(word >> 16)) == (pol, fin), key
+        assert (start, (pos_len & 2047) + 1, after) == want[key], key
         afters.append(after)
     afters = np.array(afters)
     sorted_part = afters[afters < 32]
