@@ -76,15 +76,23 @@ static ScanConsts make_consts(double m) {
 // source (start of a row, a row that row_mask leaves out) receive 0
 template <int kCtrl, int kRowMask>
 __device__ __forceinline__ double dpp_move(double x) {
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), kCtrl, kRowMask, 0xF, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), kCtrl, kRowMask, 0xF, false);
-    return __hiloint2double(hi, lo);
+    if constexpr (kRowMask == 0xF) {
+        // every row is written: a lane without a source reads 0 by itself (bound_ctrl), and the destination
+        // needs no initial value -- one instruction per half instead of two
+        const int lo = __builtin_amdgcn_mov_dpp(__double2loint(x), kCtrl, 0xF, 0xF, true);
+        const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(x), kCtrl, 0xF, 0xF, true);
+        return __hiloint2double(hi, lo);
+    } else {
+        const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), kCtrl, kRowMask, 0xF, false);
+        const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), kCtrl, kRowMask, 0xF, false);
+        return __hiloint2double(hi, lo);
+    }
 }
 constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
 constexpr int kWaveShr1 = 0x138, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
 
 __device__ __forceinline__ float wave_shr1(float x) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), kWaveShr1, 0xF, 0xF, false));
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), kWaveShr1, 0xF, 0xF, true));
 }
 
 __device__ __forceinline__ double read_lane63(double x) {
@@ -427,21 +435,24 @@ __device__ __forceinline__ void tile_back(const TileIn& x, const TileMid& m, con
     }
     // a token's value is what pass 1 kept for it plus m^(tokens to the run's end) times the value carried into
     // the run
-    const double pw_a[4] = {p.sa.q[0], c * c * c, c * c, c}, pw_r[4] = {p.sr.q[0], gamma * gamma * gamma, gamma * gamma, gamma};
+    // (in fp32: what pass 1 kept is fp32 already and the result is rounded to fp32; the carry, an fp64 sum over
+    // the whole rest of the sequence, is rounded once per run)
+    const float pw_a[4] = {(float)p.sa.q[0], (float)(c * c * c), (float)(c * c), (float)c};
+    const float pw_r[4] = {(float)p.sr.q[0], (float)(gamma * gamma * gamma), (float)(gamma * gamma), (float)gamma};
     float* __restrict__ adv = p.adv;
     float* __restrict__ ret = p.ret;
 #pragma unroll
     for (int j = kSlots - 1; j >= 0; --j) {
         const int k0 = 4 * (64 * j + 63 - lane);
         if (kFull || (256 * j < end && 256 * (j + 1) > begin)) {
-            const double xa = fma(wa.p, carry_a, dpp_move<kWaveShr1, 0xF>(m.inc_a[j]));
-            const double xr = fma(wr.p, carry_r, dpp_move<kWaveShr1, 0xF>(m.inc_r[j]));
+            const float xa = (float)fma(wa.p, carry_a, dpp_move<kWaveShr1, 0xF>(m.inc_a[j]));
+            const float xr = (float)fma(wr.p, carry_r, dpp_move<kWaveShr1, 0xF>(m.inc_r[j]));
             const lds_float4 la = s_loc[(2 * j) * kWave + lane], lr = s_loc[(2 * j + 1) * kWave + lane];
             float4u oa, orr;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                oa[e] = (float)fma(pw_a[e], xa, (double)la[e]);
-                orr[e] = (float)fma(pw_r[e], xr, (double)lr[e]);
+                oa[e] = fmaf(pw_a[e], xa, la[e]);
+                orr[e] = fmaf(pw_r[e], xr, lr[e]);
             }
             if (kFull || (k0 >= begin && k0 + 4 <= end)) {
                 __builtin_nontemporal_store(oa, reinterpret_cast<float4u*>(adv + base + k0));

@@ -283,7 +283,7 @@ static const HeadVariant kVariants[] = {make_variant<Cfg0>(), make_variant<Cfg1>
 #else
 static const HeadVariant kVariants[] = {make_variant<Cfg0>()};
 #endif
-[[maybe_unused]] constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+[[maybe_unused]] [[maybe_unused]] constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 static const HeadVariant& pick_variant() {
     int id = 0;
