@@ -1310,6 +1310,21 @@ def test_many_sequences_all_stages(tp, B):
     all_stages_against_oracle(tp, rng, win, B)
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_long_runs_of_empty_sequences_all_stages(tp, seed):
+    """Sequences that end in mid-frame and are followed by runs of up to 300 empty sequences (more than the plan
+    builder skips when it describes a frame, so the loss kernels find the next sequence by themselves), by
+    sequences of 1-3 tokens (several boundaries inside one frame) and by the end of the batch."""
+    rng = np.random.default_rng(3000 + seed)
+    parts = []
+    for _ in range(12):
+        parts += [rng.integers(1, 3000, size=1), np.zeros(int(rng.choice([1, 63, 64, 65, 100, 300])), np.int64),
+                  rng.integers(1, 4, size=int(rng.integers(0, 5)))]
+    if seed == 1:
+        parts.append(np.zeros(200, np.int64))                # the batch ends with empty sequences
+    all_stages_against_oracle(tp, rng, np.concatenate(parts), seed)
+
+
 def all_stages_against_oracle(tp, rng, win, seed):
     B = win.size
     ctx = rng.integers(1, 51, size=B)
