@@ -1188,6 +1188,25 @@ def test_plan_build_and_a_plan_of_another_batch(tp):
     tp.tppo_egae(dev(b2["rewards"]), dev(b2["values"]), dev(b2["resp_off"]), dev(b2["done"]), 1.0, 0.95,
                  status=st, plan=plan, out=out)
     assert int(host(st)[0]) == tp.STATUS_BAD_LAYOUT and bool((out[0] == 7.0).all())
+    # a frame descriptor that names no sequence: the loss kernels say so and leave its tokens out; one whose
+    # other fields are nonsense only changes which tokens count (no access depends on them)
+    cap = int(plan[32:36].view(torch.int32)[0])
+    at = 256 + (16 * cap + 255) // 256 * 256
+    frames = plan[at:at + 32 * cap].view(torch.int32).view(cap, 8)
+    good = tp.read_loss_out(tp.tppo_ppo_losses(*(d[k] for k in order), off, keepd, done, 0.2, 0.28, 0.5, 0.6, plan=plan))
+    saved = frames[:3].clone()
+    frames[0, 0] = len(b["done"]) + 5                                # first sequence out of range
+    frames[1, 4] = -1                                          # second sequence out of range
+    frames[2, 1:4] = torch.tensor([2 ** 30, -5, 1], dtype=torch.int32, device="cuda")
+    st = tp.new_status("cuda")
+    res = tp.read_loss_out(tp.tppo_ppo_losses(*(d[k] for k in order), off, keepd, done, 0.2, 0.28, 0.5, 0.6,
+                                              status=st, plan=plan))
+    assert int(host(st)[0]) == tp.STATUS_BAD_LAYOUT and np.isfinite(res["policy_loss"])
+    frames[:3] = saved
+    st = tp.new_status("cuda")
+    again = tp.read_loss_out(tp.tppo_ppo_losses(*(d[k] for k in order), off, keepd, done, 0.2, 0.28, 0.5, 0.6,
+                                                status=st, plan=plan))
+    assert int(host(st)[0]) == 0 and again == good
 
 
 def expected_tiles(off, keep, done):
