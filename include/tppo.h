@@ -127,8 +127,10 @@ int tppo_select(const int32_t* cu_seqlens, const int32_t* ctx_len, const int32_t
 
 /* ---------------------------------------------------------------------------
  * tppo_plan_build -- the work plan of a batch layout: the response-packed
- * domain cut into tiles of <= 1024 tokens of one sequence, the sizes of the
- * policy / value token sets of Sec. 3.2, and zeroed words through which the
+ * domain cut into tiles of <= 1024 tokens of one sequence (what the scan
+ * walks), one descriptor per aligned block of 1024 tokens naming the sequences
+ * that meet there (what the loss passes walk), the sizes of the policy /
+ * value token sets of Sec. 3.2, and zeroed words through which the
  * workgroups of a later launch hand partial results to each other.  Every
  * entry point below that takes `plan` builds the same thing in its workspace
  * when plan is NULL; building it once per batch (here, or as a by-product of
