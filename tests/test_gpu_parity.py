@@ -765,6 +765,25 @@ def test_losses_configs(tp, name):
         assert_loss_close(run_losses(tp, a, b, keep, eps=(0.2, 0.28)), ref2)
 
 
+def test_losses_keep_len_outside_the_window(tp):
+    """keep_len beyond the window means every window token, a negative one none (the policy set is the window
+    tokens t < keep_len[i]): losses and derivatives as with the clamped values."""
+    b = synth.make_batch("small", with_head=False)
+    a, keep = loss_inputs(b)
+    win = np.diff(b["resp_off"])
+    wild = keep.copy()
+    wild[::3] = win[::3] + 7
+    wild[1::3] = -5
+    clamped = np.clip(wild, 0, win).astype(np.int32)
+    ref = ofast.ppo_losses(a["logp_new"], a["logp_old"], a["adv"], a["v_new"], a["v_old"], a["ret"],
+                           b["resp_off"], clamped, b["done"], b["eps_low"], b["eps_high"], b["xi_low"], b["xi_high"])
+    got = run_losses(tp, a, b, wild)
+    assert_loss_close(got, ref)
+    assert got == run_losses(tp, a, b, clamped)
+    g_wild, g_clamped = run_loss_grads(tp, a, b, wild), run_loss_grads(tp, a, b, clamped)
+    assert np.array_equal(g_wild[0], g_clamped[0]) and np.array_equal(g_wild[1], g_clamped[1])
+
+
 def test_losses_masked_entries_contribute_exactly_zero(tp):
     b = synth.make_batch("small", with_head=False)
     a, keep = loss_inputs(b)
