@@ -1363,6 +1363,15 @@ def test_long_runs_of_empty_sequences_all_stages(tp, seed):
     all_stages_against_oracle(tp, rng, np.concatenate(parts), seed)
 
 
+@pytest.mark.parametrize("win", [[1024], [1025], [1023, 1], [1, 1023], [4], [5], [3, 1], [2, 1], [2048], [1, 1023, 1024, 1],
+                                 [1020, 3, 2, 1, 1022], [0, 1024, 0], [4096, 4], [1, 1, 1, 1, 1, 1, 1, 1, 1017, 3000]])
+def test_frame_edges_all_stages(tp, win):
+    """Layouts whose sequence ends fall on, just before and just after the ends of the aligned 1024-token frames,
+    whose last frame is full, nearly empty or the only one, and batches of 3 and 4 tokens."""
+    rng = np.random.default_rng(4000 + sum(win) + len(win))
+    all_stages_against_oracle(tp, rng, np.asarray(win, dtype=np.int64), len(win))
+
+
 def all_stages_against_oracle(tp, rng, win, seed):
     B = win.size
     ctx = rng.integers(1, 51, size=B)
